@@ -1,0 +1,231 @@
+"""Seeded synthetic inputs for the decoder-layer forward step.
+
+This module is shared by the CPU oracle's tests and by the HIP path's tests and
+benchmark.  It holds no arithmetic of the method: it only draws random numbers,
+rounds stored values to their storage type and lays them out in the documented
+tensor formats.
+
+Tensor formats (all row-major, the last index fastest):
+
+  x            [n_tokens, hidden]
+  w_qkv        [(n_q + 2 n_kv) * d, hidden]   rows: all q heads, then k heads, then v heads
+  w_o          [hidden, n_q * d]
+  w_gate_up    [2 * inter, hidden]            rows: gate rows, then up rows   (dense MLP)
+               [E, 2 * inter, hidden]                                          (MoE)
+  w_down       [hidden, inter]   /  [E, hidden, inter]
+  w_router     [E, hidden]   (fp32 in every configuration)
+  g_norm1/2    [hidden]
+  k_cache      [n_pages, n_kv, page_size, d]  a page holds page_size consecutive positions
+  v_cache      [n_pages, n_kv, d, page_size]  (V is stored position-fastest inside a page)
+  block_table  [n_seqs, max_pages_per_seq]    int32 physical page of logical page j
+  seq_of_token, pos_of_token [n_tokens] int32;  q_start [n_seqs+1];  ctx_len [n_seqs]
+
+Every weight matrix is stored "output-major": y = x @ W^T.  ctx_len counts the keys a
+sequence attends to after this step's tokens have been appended.
+
+Workload shapes follow the paper's evaluation section only in shape (Llama-3-8B layer
+sizes, batches of hundreds of sequences with contexts of 0.5k-8k tokens, a prefill
+chunk mixed with decodes); values are N(0, 0.02^2) weights, N(0, 1) activations and
+cache entries, unit norm gains.
+"""
+from __future__ import annotations
+
+import dataclasses
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Tuple
+
+import numpy as np
+import torch
+
+
+@dataclass(frozen=True)
+class LayerShape:
+    dtype: str            # "f32" | "bf16"
+    hidden: int
+    n_q: int
+    n_kv: int
+    head_dim: int
+    inter: int
+    n_layers: int = 1
+    n_experts: int = 0
+    top_k: int = 0
+    eps: float = 1e-6
+    rope_base: float = 10000.0
+    page_size: int = 16
+
+    @property
+    def qkv_rows(self) -> int:
+        return (self.n_q + 2 * self.n_kv) * self.head_dim
+
+    @property
+    def torch_dtype(self):
+        return torch.float32 if self.dtype == "f32" else torch.bfloat16
+
+
+@dataclass(frozen=True)
+class Workload:
+    name: str
+    shape: LayerShape
+    # one entry per sequence: (q_len, ctx_len) with ctx_len >= q_len; the q_len new
+    # tokens occupy positions ctx_len - q_len .. ctx_len - 1.
+    seqs: Tuple[Tuple[int, int], ...]
+    seed: int = 0
+    nano_rows: Tuple[int, ...] = ()      # default token-row cut points [0, ..., n_tokens]
+
+    @property
+    def n_tokens(self) -> int:
+        return sum(q for q, _ in self.seqs)
+
+    @property
+    def n_seqs(self) -> int:
+        return len(self.seqs)
+
+
+LLAMA3_8B = LayerShape("bf16", 4096, 32, 8, 128, 14336)
+MOE_8X = dataclasses.replace(LLAMA3_8B, n_experts=8, top_k=2)
+
+
+def _uniform_ctx(seed: int, n: int, lo: int, hi: int) -> List[int]:
+    rng = np.random.default_rng(seed)
+    return [int(v) for v in rng.integers(lo, hi + 1, size=n)]
+
+
+def config(name: str) -> Workload:
+    """The named workloads: c1..c5 are the five benchmark configurations, the *_small
+    ones are reduced shapes the CPU oracle finishes in seconds."""
+    if name == "c1":
+        sh = LayerShape("f32", 256, 4, 4, 64, 1024)
+        return Workload("c1", sh, tuple((1, 128) for _ in range(4)), 0, (0, 2, 4))
+    if name == "c2":
+        ctx = _uniform_ctx(0, 128, 512, 4096)
+        return Workload("c2", LLAMA3_8B, tuple((1, c) for c in ctx), 0, (0, 64, 128))
+    if name == "c3":
+        seqs = ((2048, 2048),) + tuple((1, 2048) for _ in range(64))
+        return Workload("c3", LLAMA3_8B, seqs, 0, (0, 2048, 2112))
+    if name == "c4":
+        return Workload("c4", MOE_8X, tuple((1, 1024) for _ in range(256)), 0, (0, 128, 256))
+    if name == "c5":
+        ctx = _uniform_ctx(0, 256, 1024, 8192)
+        sh = dataclasses.replace(LLAMA3_8B, n_layers=32)
+        return Workload("c5", sh, tuple((1, c) for c in ctx), 0, (0, 128, 256))
+    if name == "c2_small":
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
+        ctx = _uniform_ctx(1, 13, 1, 700)
+        return Workload("c2_small", sh, tuple((1, c) for c in ctx), 1, (0, 6, 13))
+    if name == "c3_small":
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
+        seqs = ((150, 150), (1, 77), (37, 90), (1, 300), (1, 1))
+        return Workload("c3_small", sh, seqs, 2, (0, 150, 190))
+    if name == "c4_small":
+        sh = LayerShape("bf16", 512, 8, 2, 128, 768, n_experts=8, top_k=2)
+        ctx = _uniform_ctx(3, 40, 1, 200)
+        return Workload("c4_small", sh, tuple((1, c) for c in ctx), 3, (0, 17, 40))
+    if name == "c5_small":
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1536, n_layers=3)
+        ctx = _uniform_ctx(4, 24, 1, 520)
+        return Workload("c5_small", sh, tuple((1, c) for c in ctx), 4, (0, 5, 11, 18, 24))
+    if name == "f32_small":
+        sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
+        seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
+        return Workload("f32_small", sh, seqs, 5, (0, 9, 17))
+    if name == "f32_moe_small":
+        sh = LayerShape("f32", 128, 4, 2, 32, 192, n_experts=4, top_k=2)
+        ctx = _uniform_ctx(6, 11, 1, 50)
+        return Workload("f32_moe_small", sh, tuple((1, c) for c in ctx), 6, (0, 4, 11))
+    raise KeyError(name)
+
+
+def round_to(t: torch.Tensor, dtype: str) -> torch.Tensor:
+    """Round fp32 values to the storage type (round-to-nearest-even for bf16)."""
+    return t.to(torch.bfloat16) if dtype == "bf16" else t.to(torch.float32)
+
+
+def metadata(w: Workload, page_seed: Optional[int] = None) -> Dict[str, np.ndarray]:
+    """Token/sequence index arrays and a block table with randomly permuted physical pages."""
+    ps = w.shape.page_size
+    seq_of_token, pos_of_token, q_start, ctx_len = [], [], [0], []
+    for s, (q, c) in enumerate(w.seqs):
+        assert 1 <= q <= c
+        for i in range(q):
+            seq_of_token.append(s)
+            pos_of_token.append(c - q + i)
+        q_start.append(q_start[-1] + q)
+        ctx_len.append(c)
+    pages_per_seq = [(c + ps - 1) // ps for _, c in w.seqs]
+    max_pages = max(pages_per_seq)
+    n_pages = sum(pages_per_seq) + 3                       # a few spare pages never referenced
+    rng = np.random.default_rng((w.seed if page_seed is None else page_seed) + 7919)
+    perm = rng.permutation(n_pages).astype(np.int32)
+    bt = np.zeros((w.n_seqs, max_pages), dtype=np.int32)
+    nxt = 0
+    for s, n in enumerate(pages_per_seq):
+        bt[s, :n] = perm[nxt:nxt + n]
+        nxt += n
+    return dict(
+        seq_of_token=np.asarray(seq_of_token, dtype=np.int32),
+        pos_of_token=np.asarray(pos_of_token, dtype=np.int32),
+        q_start=np.asarray(q_start, dtype=np.int32),
+        ctx_len=np.asarray(ctx_len, dtype=np.int32),
+        block_table=bt, n_pages=n_pages, max_pages_per_seq=max_pages,
+    )
+
+
+def _normal(gen: torch.Generator, shape, std: float, dtype: str, device="cpu") -> torch.Tensor:
+    t = torch.empty(shape, dtype=torch.float32, device=device)
+    t.normal_(0.0, std, generator=gen)
+    return round_to(t, dtype)
+
+
+def layer_weights(sh: LayerShape, gen: torch.Generator, device="cpu") -> Dict[str, torch.Tensor]:
+    H, I, E = sh.hidden, sh.inter, sh.n_experts
+    wts = {
+        "w_qkv": _normal(gen, (sh.qkv_rows, H), 0.02, sh.dtype, device),
+        "w_o": _normal(gen, (H, sh.n_q * sh.head_dim), 0.02, sh.dtype, device),
+        "g_norm1": round_to(torch.ones(H, device=device), sh.dtype),
+        "g_norm2": round_to(torch.ones(H, device=device), sh.dtype),
+    }
+    if E:
+        wts["w_gate_up"] = _normal(gen, (E, 2 * I, H), 0.02, sh.dtype, device)
+        wts["w_down"] = _normal(gen, (E, H, I), 0.02, sh.dtype, device)
+        wts["w_router"] = _normal(gen, (E, H), H ** -0.5, "f32", device)
+    else:
+        wts["w_gate_up"] = _normal(gen, (2 * I, H), 0.02, sh.dtype, device)
+        wts["w_down"] = _normal(gen, (H, I), 0.02, sh.dtype, device)
+    return wts
+
+
+def generate(w: Workload, device="cpu") -> Dict[str, object]:
+    """All tensors of one step: per-layer weights, per-layer caches, x and the metadata.
+
+    With device="cpu" the torch CPU generator is used; a GPU device draws directly in
+    device memory (needed only for the 32-layer configuration whose caches exceed host
+    memory); the two do not produce the same numbers."""
+    sh = w.shape
+    gen = torch.Generator(device=device)
+    gen.manual_seed(w.seed)
+    md = metadata(w)
+    out: Dict[str, object] = dict(md)
+    out["weights"] = [layer_weights(sh, gen, device) for _ in range(sh.n_layers)]
+    out["x"] = _normal(gen, (w.n_tokens, sh.hidden), 1.0, sh.dtype, device)
+    kc, vc = [], []
+    for _ in range(sh.n_layers):
+        kc.append(_normal(gen, (md["n_pages"], sh.n_kv, sh.page_size, sh.head_dim), 1.0, sh.dtype, device))
+        vc.append(_normal(gen, (md["n_pages"], sh.n_kv, sh.head_dim, sh.page_size), 1.0, sh.dtype, device))
+    out["k_cache"], out["v_cache"] = kc, vc
+    return out
+
+
+def sub_batch(w: Workload, data: Dict[str, object], seq_ids: List[int]) -> Tuple[Workload, Dict[str, object]]:
+    """The same step restricted to some sequences (rows are independent per sequence).
+    The caches and block-table rows are shared with the full batch, x rows are gathered."""
+    q_start = data["q_start"]
+    rows = np.concatenate([np.arange(q_start[s], q_start[s + 1]) for s in seq_ids])
+    w2 = dataclasses.replace(w, name=w.name + "_sub", seqs=tuple(w.seqs[s] for s in seq_ids), nano_rows=())
+    md = metadata(w2)
+    d2 = dict(data)
+    for k in ("seq_of_token", "pos_of_token", "q_start", "ctx_len"):
+        d2[k] = md[k]
+    d2["block_table"] = np.ascontiguousarray(data["block_table"][seq_ids])
+    d2["x"] = data["x"][torch.as_tensor(rows, dtype=torch.long)].contiguous()
+    d2["rows"] = rows
+    return w2, d2
