@@ -1,0 +1,173 @@
+/*
+ * dynlayer - transformer decoder-layer forward step for MI355X (gfx950), run either
+ * sequentially or as nano-batches whose operators overlap on one GPU.
+ *
+ * The scheduling contract follows the paper's programmable operator scheduling
+ * (Section 3.2.2, Figure 6): a batch is split into k micro-batches of chosen sizes
+ * ("split"), each micro-batch advances through a chain of coarse operators in order
+ * (the "ready operators" rule), and every dispatch ("execute") names the operator, the
+ * micro-batches it covers - one (split form) or several adjacent ones (merge form) -
+ * and the stream it runs on.  Data flow between operators is the library's business
+ * (Section 3.3.1, Algorithm 1): every intermediate is one contiguous [tokens, width]
+ * buffer and a micro-batch is a row range of it, so splitting and merging never copy.
+ *
+ * All tensor arguments are DEVICE pointers owned by the caller and only borrowed here,
+ * unless a field says HOST.  The library owns streams, events, graphs and its handle.
+ * No function throws; each returns a dyn_status and dyn_last_error() gives the detail.
+ *
+ * Tensor layouts (row-major, last index fastest; element type = dyn_layer_config.dtype
+ * unless stated):
+ *   x, y         [n_tokens, hidden]
+ *   w_qkv        [(n_q_heads + 2 n_kv_heads) * head_dim, hidden]  q rows, k rows, v rows
+ *   w_o          [hidden, n_q_heads * head_dim]
+ *   w_gate_up    [2 * mlp_inter, hidden] gate rows then up rows;  MoE: [E, 2*mlp_inter, hidden]
+ *   w_down       [hidden, mlp_inter];                             MoE: [E, hidden, mlp_inter]
+ *   w_router     [E, hidden] float32 always (MoE only)
+ *   g_norm1/2    [hidden]
+ *   k_cache      [n_pages, n_kv_heads, page_size, head_dim]
+ *   v_cache      [n_pages, n_kv_heads, head_dim, page_size]   (position fastest in a page)
+ *   block_table  [n_seqs, max_pages_per_seq] int32: physical page of a logical page
+ * Every weight matrix is output-major: out = in * W^T.
+ */
+#ifndef DYNLAYER_H
+#define DYNLAYER_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    DYN_OK = 0,
+    DYN_ERR_INVALID_ARG = 1, /* NULL pointer, negative size, inconsistent shapes */
+    DYN_ERR_UNSUPPORTED = 2, /* a shape or dtype no kernel here handles */
+    DYN_ERR_SCHEDULE = 3,    /* descriptor breaks the ready-operator rule or its own bounds */
+    DYN_ERR_WORKSPACE = 4,   /* workspace missing, misaligned or too small */
+    DYN_ERR_HIP = 5          /* a HIP runtime call failed */
+} dyn_status;
+
+enum { DYN_F32 = 0, DYN_BF16 = 1 };
+
+/* The operator chain of one layer, in dependency order.  Granularity is the logical
+ * coarse operator (a norm, a projection, attention), as the paper's graph partitioning
+ * argues (Section 3.2.1).  DYN_OP_ROUTE exists only in MoE layers. */
+enum {
+    DYN_OP_NORM1 = 0,   /* h1 = RMSNorm(x) */
+    DYN_OP_QKV = 1,     /* [q|k|v] = h1 W_qkv^T */
+    DYN_OP_ROPE_KV = 2, /* rotary on q and k; k', v appended to the paged cache */
+    DYN_OP_ATTN = 3,    /* causal paged attention of each token over positions 0..pos */
+    DYN_OP_OPROJ = 4,   /* x2 = x + o W_o^T */
+    DYN_OP_NORM2 = 5,   /* h2 = RMSNorm(x2) */
+    DYN_OP_ROUTE = 6,   /* MoE: router logits, top-k selection, softmax weights */
+    DYN_OP_GATE_UP = 7, /* [g|u] = h2 W_gate_up^T   (MoE: per selected expert) */
+    DYN_OP_SILU = 8,    /* a = silu(g) * u */
+    DYN_OP_DOWN = 9,    /* y = x2 + a W_down^T      (MoE: weighted sum over selected experts) */
+    DYN_N_OPS = 10
+};
+
+typedef struct {
+    int dtype;                 /* DYN_F32 | DYN_BF16: weights, activations and caches */
+    int n_layers;              /* >= 1; layer l+1 takes layer l's output */
+    int hidden, n_q_heads, n_kv_heads, head_dim, mlp_inter;
+    int n_experts, top_k;      /* 0, 0 = dense MLP */
+    float rms_eps, rope_base;  /* rotary: rotate-half pairing (i, i + head_dim/2) */
+    int page_size;             /* positions per cache page */
+} dyn_layer_config;
+
+/* One entry per layer (array of n_layers). */
+typedef struct {
+    const void *w_qkv, *w_o, *w_gate_up, *w_down, *g_norm1, *g_norm2;
+    const float *w_router;     /* NULL for dense layers */
+} dyn_layer_weights;
+
+typedef struct {
+    int n_tokens, n_seqs;
+    const void *x;                 /* [n_tokens, hidden], read only */
+    void *y;                       /* [n_tokens, hidden], written; must not alias x */
+    const int32_t *seq_of_token;   /* [n_tokens] sequence of each token row */
+    const int32_t *pos_of_token;   /* [n_tokens] position in its sequence; it attends keys 0..pos */
+    const int32_t *block_table;    /* [n_seqs, max_pages_per_seq] */
+    int max_pages_per_seq;
+    const int32_t *q_start_host;   /* HOST [n_seqs + 1]: token rows of sequence s are
+                                      q_start_host[s] .. q_start_host[s+1]-1, in position order */
+    void *k_cache, *v_cache;       /* layer 0; MUTATED: this step's k', v are stored */
+    size_t kv_layer_stride;        /* bytes from layer l's cache to layer l+1's (both caches) */
+    void *workspace;               /* >= dyn_layer_workspace_bytes(...), 256-byte aligned */
+    size_t workspace_bytes;
+} dyn_batch;
+
+/* One dispatch: operator `op` over micro-batches nano .. nano + n_nano - 1 (n_nano = 1 is
+ * the paper's split form, n_nano > 1 its merge form) on stream `stream` of CU partition
+ * `partition` (0 = whole device; p >= 1 = cu_masks row p-1).  Stream 0 of partition 0 is
+ * the caller's stream. */
+typedef struct {
+    uint8_t op, nano, n_nano, stream, partition;
+} dyn_slot;
+
+enum { DYN_SCHED_SEQUENTIAL = 0, DYN_SCHED_EXPLICIT = 1 };
+enum { DYN_MAX_NANO = 8, DYN_MAX_STREAMS = 8, DYN_MAX_PARTITIONS = 4 };
+
+typedef struct {
+    int mode;                   /* SEQUENTIAL: whole batch, chain order, caller's stream; rest ignored
+                                   except use_graph */
+    int k;                      /* micro-batches, 1..DYN_MAX_NANO */
+    const int32_t *nano_rows;   /* HOST [k+1]: token-row cut points, 0 .. n_tokens, non-decreasing,
+                                   on sequence boundaries; unequal sizes allowed */
+    int n_streams;              /* stream ids 0..n_streams-1 */
+    int n_partitions;           /* masked partitions 1..n_partitions */
+    const uint32_t *cu_masks;   /* HOST [n_partitions, cu_mask_words] for hipExtStreamCreateWithCUMask */
+    int cu_mask_words;
+    int n_slots;                /* issue order within one layer; the list repeats for every layer */
+    const dyn_slot *slots;      /* HOST */
+    int use_graph;              /* 1: capture the whole step into a HIP graph once and replay it */
+} dyn_schedule;
+
+typedef struct dyn_layer dyn_layer;
+
+/* Records configuration and weight pointers.  Touches no GPU state (streams, events and
+ * graphs are created on first forward), so it and the validator run without a device. */
+dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights *weights, dyn_layer **out);
+
+/* Releases streams, events, graphs.  Outstanding work must have been synchronised. */
+void dyn_layer_destroy(dyn_layer *layer);
+
+/* Bytes of workspace a forward of up to max_tokens tokens needs when no sequence has more
+ * than max_pages_per_seq pages.  Independent of the schedule: overlap buffers results of
+ * concurrently running micro-batches (the paper's peak-memory remark, Section 2.1), and
+ * because a micro-batch is a row range of batch-sized buffers the bound is the same. */
+size_t dyn_layer_workspace_bytes(const dyn_layer *layer, int max_tokens, int max_pages_per_seq);
+
+/* Host-only check of a schedule against a batch's shapes (no device memory is read):
+ * cut points monotone, covering [0, n_tokens], on sequence boundaries; each (operator,
+ * micro-batch) dispatched exactly once per layer; every dispatch issued after the
+ * dispatches producing its inputs for all micro-batches it covers (ready-operator rule,
+ * Section 3.2.2); stream / partition ids in range.  batch->workspace may be NULL here. */
+dyn_status dyn_schedule_validate(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched);
+
+/* Runs all layers.  Asynchronous: work is forked from hip_stream (a hipStream_t, not the
+ * null stream when use_graph is set) and joined back to it; the host does not wait and
+ * nothing is allocated on the device.  Cross-stream dependencies are inserted by the
+ * library (the backend, not the scheduler author, owns data flow; Section 3.2.2).
+ * Output rows land at their global row index whatever the split (zero-copy merge,
+ * Section 3.3.1).  Any legal schedule gives bit-identical y and cache contents. */
+dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, void *hip_stream);
+
+/* Profiling (eager schedules only): when on, every dispatch is bracketed by events on its
+ * own stream.  After the caller has synchronised, dyn_layer_get_slot_times returns, for
+ * the last forward, one record per dispatch in issue order (layer-major). */
+typedef struct {
+    int layer, op, nano, n_nano, stream, partition;
+    float start_ms, stop_ms;   /* relative to the fork point of that forward */
+} dyn_slot_time;
+dyn_status dyn_layer_set_profiling(dyn_layer *layer, int on);
+dyn_status dyn_layer_get_slot_times(dyn_layer *layer, dyn_slot_time *out, int capacity, int *n_out);
+
+/* Thread-local description of the last error returned on this thread ("" if none). */
+const char *dyn_last_error(void);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DYNLAYER_H */

@@ -1,0 +1,252 @@
+"""ctypes binding of libdynlayer.so.  Argument marshalling only: every step of the layer
+runs in the library's HIP kernels.  PyTorch supplies device memory and streams."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass, field
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch  # must be imported before the library so both share one HIP runtime
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdynlayer.so")
+
+DYN_OK, DYN_ERR_INVALID_ARG, DYN_ERR_UNSUPPORTED, DYN_ERR_SCHEDULE, DYN_ERR_WORKSPACE, DYN_ERR_HIP = range(6)
+DYN_F32, DYN_BF16 = 0, 1
+(DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ, DYN_OP_NORM2, DYN_OP_ROUTE, DYN_OP_GATE_UP,
+ DYN_OP_SILU, DYN_OP_DOWN) = range(10)
+DYN_N_OPS = 10
+DYN_SCHED_SEQUENTIAL, DYN_SCHED_EXPLICIT = 0, 1
+DYN_MAX_NANO, DYN_MAX_STREAMS, DYN_MAX_PARTITIONS = 8, 8, 4
+OP_NAMES = ["norm1", "qkv", "rope_kv", "attn", "oproj", "norm2", "route", "gate_up", "silu", "down"]
+DENSE_CHAIN = [DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ, DYN_OP_NORM2, DYN_OP_GATE_UP,
+               DYN_OP_SILU, DYN_OP_DOWN]
+MOE_CHAIN = DENSE_CHAIN[:6] + [DYN_OP_ROUTE] + DENSE_CHAIN[6:]
+
+
+class dyn_layer_config(C.Structure):
+    _fields_ = [("dtype", C.c_int), ("n_layers", C.c_int), ("hidden", C.c_int), ("n_q_heads", C.c_int),
+                ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("mlp_inter", C.c_int), ("n_experts", C.c_int),
+                ("top_k", C.c_int), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("page_size", C.c_int)]
+
+
+class dyn_layer_weights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("w_qkv", "w_o", "w_gate_up", "w_down", "g_norm1", "g_norm2", "w_router")]
+
+
+class dyn_batch(C.Structure):
+    _fields_ = [("n_tokens", C.c_int), ("n_seqs", C.c_int), ("x", C.c_void_p), ("y", C.c_void_p),
+                ("seq_of_token", C.c_void_p), ("pos_of_token", C.c_void_p), ("block_table", C.c_void_p),
+                ("max_pages_per_seq", C.c_int), ("q_start_host", C.c_void_p), ("k_cache", C.c_void_p),
+                ("v_cache", C.c_void_p), ("kv_layer_stride", C.c_size_t), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t)]
+
+
+class dyn_slot(C.Structure):
+    _fields_ = [("op", C.c_uint8), ("nano", C.c_uint8), ("n_nano", C.c_uint8), ("stream", C.c_uint8),
+                ("partition", C.c_uint8)]
+
+
+class dyn_schedule(C.Structure):
+    _fields_ = [("mode", C.c_int), ("k", C.c_int), ("nano_rows", C.c_void_p), ("n_streams", C.c_int),
+                ("n_partitions", C.c_int), ("cu_masks", C.c_void_p), ("cu_mask_words", C.c_int), ("n_slots", C.c_int),
+                ("slots", C.c_void_p), ("use_graph", C.c_int)]
+
+
+class dyn_slot_time(C.Structure):
+    _fields_ = [("layer", C.c_int), ("op", C.c_int), ("nano", C.c_int), ("n_nano", C.c_int), ("stream", C.c_int),
+                ("partition", C.c_int), ("start_ms", C.c_float), ("stop_ms", C.c_float)]
+
+
+EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
+           "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error"]
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    """The loaded library.  There is no fallback: a missing build is an error."""
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise RuntimeError("libdynlayer.so is not built: run `python -m paper_2605_21603_amd.build`")
+        l = C.CDLL(LIB_PATH)
+        l.dyn_last_error.restype = C.c_char_p
+        l.dyn_layer_workspace_bytes.restype = C.c_size_t
+        l.dyn_layer_workspace_bytes.argtypes = [C.c_void_p, C.c_int, C.c_int]
+        l.dyn_layer_create.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_layer_destroy.argtypes = [C.c_void_p]
+        l.dyn_layer_destroy.restype = None
+        l.dyn_schedule_validate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_layer_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
+        l.dyn_layer_get_slot_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        _lib = l
+    return _lib
+
+
+class DynError(RuntimeError):
+    def __init__(self, status: int, msg: str):
+        super().__init__("dynlayer status %d: %s" % (status, msg))
+        self.status = status
+
+
+def _check(status: int) -> None:
+    if status != DYN_OK:
+        raise DynError(status, lib().dyn_last_error().decode())
+
+
+def dyn_last_error() -> str:
+    return lib().dyn_last_error().decode()
+
+
+def _ptr(t) -> Optional[int]:
+    if t is None:
+        return None
+    if isinstance(t, torch.Tensor):
+        assert t.is_contiguous()
+        return t.data_ptr()
+    if isinstance(t, np.ndarray):
+        assert t.flags["C_CONTIGUOUS"]
+        return t.ctypes.data
+    return int(t)
+
+
+@dataclass
+class Schedule:
+    """Host-side schedule descriptor; slots are (op, nano, n_nano, stream, partition)."""
+    mode: int = DYN_SCHED_SEQUENTIAL
+    nano_rows: Sequence[int] = ()
+    slots: Sequence[Sequence[int]] = ()
+    n_streams: int = 1
+    cu_masks: Sequence[Sequence[int]] = ()     # one row of uint32 words per masked partition
+    use_graph: bool = False
+    _keep: list = field(default_factory=list, repr=False)
+
+    def to_c(self) -> dyn_schedule:
+        rows = np.ascontiguousarray(self.nano_rows, dtype=np.int32)
+        slots = (dyn_slot * max(1, len(self.slots)))(*[dyn_slot(*s) for s in self.slots])
+        masks = np.ascontiguousarray(self.cu_masks, dtype=np.uint32).reshape(len(self.cu_masks), -1) \
+            if len(self.cu_masks) else np.zeros((0, 0), np.uint32)
+        self._keep = [rows, slots, masks]
+        return dyn_schedule(self.mode, max(0, len(rows) - 1), _ptr(rows) if len(rows) else None, self.n_streams,
+                            len(self.cu_masks), _ptr(masks) if len(self.cu_masks) else None,
+                            masks.shape[1] if len(self.cu_masks) else 0, len(self.slots),
+                            C.cast(slots, C.c_void_p).value if len(self.slots) else None, int(self.use_graph))
+
+
+def sequential(use_graph: bool = False) -> Schedule:
+    return Schedule(DYN_SCHED_SEQUENTIAL, use_graph=use_graph)
+
+
+def nano_schedule(nano_rows: Sequence[int], chain: Sequence[int] = DENSE_CHAIN, merged_ops: Sequence[int] = (),
+                  streams: Optional[Sequence[int]] = None, partitions: Optional[Sequence[int]] = None,
+                  cu_masks: Sequence[Sequence[int]] = (), use_graph: bool = False, stagger: int = 0) -> Schedule:
+    """Split-and-overlap schedule in the style of the paper's batch-splitting strategies:
+    micro-batch b runs its operators on stream streams[b]; operators in merged_ops are
+    dispatched once for all micro-batches (merge form) on stream 0.  Issue order interleaves
+    the micro-batches operator by operator, micro-batch b lagging `stagger` operators behind
+    micro-batch b-1, so that a memory-bound operator of one meets a GEMM of the other."""
+    k = len(nano_rows) - 1
+    streams = list(streams) if streams is not None else list(range(k))
+    partitions = list(partitions) if partitions is not None else [0] * k
+    slots, pos, n, tick = [], [0] * k, len(chain), 0
+    while min(pos) < n:
+        for b in range(k):
+            if pos[b] >= n or tick < b * stagger:
+                continue
+            op = chain[pos[b]]
+            if op not in merged_ops:
+                slots.append((op, b, 1, streams[b], partitions[b]))
+                pos[b] += 1
+            elif all(p == pos[b] for p in pos):      # the last micro-batch has arrived: merge form
+                slots.append((op, 0, k, 0, 0))
+                pos = [p + 1 for p in pos]
+        tick += 1
+    return Schedule(DYN_SCHED_EXPLICIT, list(nano_rows), slots, max(streams) + 1, cu_masks, use_graph)
+
+
+class DynLayer:
+    """Owns a dyn_layer handle and keeps the weight tensors alive."""
+
+    def __init__(self, cfg: dyn_layer_config, weights: List[Dict[str, torch.Tensor]]):
+        self.cfg = cfg
+        self.weights = weights
+        arr = (dyn_layer_weights * len(weights))()
+        for i, w in enumerate(weights):
+            arr[i] = dyn_layer_weights(*[_ptr(w.get(n)) for n in
+                                         ("w_qkv", "w_o", "w_gate_up", "w_down", "g_norm1", "g_norm2", "w_router")])
+        self._warr = arr
+        h = C.c_void_p()
+        _check(lib().dyn_layer_create(C.addressof(cfg), C.cast(arr, C.c_void_p), C.addressof(h)))
+        self.handle = h
+
+    def close(self):
+        if self.handle:
+            lib().dyn_layer_destroy(self.handle)
+            self.handle = None
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def workspace_bytes(self, max_tokens: int, max_pages_per_seq: int) -> int:
+        return lib().dyn_layer_workspace_bytes(self.handle, max_tokens, max_pages_per_seq)
+
+    def validate(self, batch: dyn_batch, sched: Schedule) -> None:
+        sc = sched.to_c()
+        _check(lib().dyn_schedule_validate(self.handle, C.addressof(batch), C.addressof(sc)))
+
+    def forward(self, batch: dyn_batch, sched: Schedule, stream: Optional[torch.cuda.Stream] = None) -> None:
+        sc = sched.to_c()
+        s = stream if stream is not None else torch.cuda.current_stream()
+        _check(lib().dyn_layer_forward(self.handle, C.addressof(batch), C.addressof(sc), C.c_void_p(s.cuda_stream)))
+
+    def set_profiling(self, on: bool) -> None:
+        _check(lib().dyn_layer_set_profiling(self.handle, int(on)))
+
+    def slot_times(self) -> List[dict]:
+        n = C.c_int(0)
+        _check(lib().dyn_layer_get_slot_times(self.handle, None, 0, C.addressof(n)))
+        arr = (dyn_slot_time * max(1, n.value))()
+        _check(lib().dyn_layer_get_slot_times(self.handle, C.cast(arr, C.c_void_p), n.value, C.addressof(n)))
+        return [dict(layer=a.layer, op=a.op, nano=a.nano, n_nano=a.n_nano, stream=a.stream, partition=a.partition,
+                     start_ms=a.start_ms, stop_ms=a.stop_ms) for a in arr[:n.value]]
+
+
+def make_config(sh) -> dyn_layer_config:
+    """From a workloads.gen.LayerShape-like object."""
+    return dyn_layer_config(DYN_BF16 if sh.dtype == "bf16" else DYN_F32, sh.n_layers, sh.hidden, sh.n_q, sh.n_kv,
+                            sh.head_dim, sh.inter, sh.n_experts, sh.top_k, sh.eps, sh.rope_base, sh.page_size)
+
+
+class DeviceStep:
+    """Device copies of one generated step (workloads.gen.generate output) and the dyn_batch
+    describing them.  Layer caches are stacked so that kv_layer_stride is uniform."""
+
+    def __init__(self, layer: DynLayer, data: dict, device="cuda:0"):
+        dev = torch.device(device)
+        self.x = data["x"].to(dev)
+        self.y = torch.empty_like(self.x)
+        self.k_cache = torch.stack([k.to(dev) for k in data["k_cache"]]) if isinstance(data["k_cache"], list) else data["k_cache"]
+        self.v_cache = torch.stack([v.to(dev) for v in data["v_cache"]]) if isinstance(data["v_cache"], list) else data["v_cache"]
+        self.seq_of_token = torch.from_numpy(data["seq_of_token"]).to(dev)
+        self.pos_of_token = torch.from_numpy(data["pos_of_token"]).to(dev)
+        self.block_table = torch.from_numpy(np.ascontiguousarray(data["block_table"])).to(dev)
+        self.q_start_host = np.ascontiguousarray(data["q_start"], dtype=np.int32)
+        n_tokens, n_seqs = self.x.shape[0], len(self.q_start_host) - 1
+        max_pages = int(data["block_table"].shape[1])
+        nbytes = layer.workspace_bytes(n_tokens, max_pages)
+        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
+        ws_ptr = (self.workspace.data_ptr() + 255) & ~255
+        stride = self.k_cache[0].numel() * self.k_cache.element_size()
+        self.batch = dyn_batch(n_tokens, n_seqs, _ptr(self.x), _ptr(self.y), _ptr(self.seq_of_token),
+                               _ptr(self.pos_of_token), _ptr(self.block_table), max_pages, _ptr(self.q_start_host),
+                               _ptr(self.k_cache), _ptr(self.v_cache), stride, ws_ptr, nbytes)
+        # uploads were queued on torch's current stream; forwards run on other, non-blocking
+        # streams, so wait here until the inputs have landed
+        torch.cuda.synchronize(dev)

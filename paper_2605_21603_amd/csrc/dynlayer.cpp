@@ -1,0 +1,538 @@
+// C-ABI library: layer handle, schedule validation, workspace layout and the overlap
+// executor (streams, CU-masked partitions, event dependencies, HIP-graph capture).
+//
+// The executor realises the paper's backend (Section 3.3, Section 4): the schedule names
+// what runs where and in which issue order; the dependency state - which dispatch produced
+// the rows another consumes - is derived here and turned into event edges between streams.
+// Splitting and merging micro-batches is pointer arithmetic on batch-sized buffers
+// (Algorithm 1's pre-allocated merge buffers, with every intermediate pre-allocated).
+#include "../../include/dynlayer.h"
+
+#include <hip/hip_ext.h>
+#include <hip/hip_runtime.h>
+
+#include <algorithm>
+#include <cmath>
+#include <cstdarg>
+#include <cstdio>
+#include <cstring>
+#include <string>
+#include <vector>
+
+#include "kernels.h"
+
+namespace {
+
+thread_local std::string g_err;
+
+dyn_status fail(dyn_status st, const char *fmt, ...) {
+    char buf[512];
+    va_list ap;
+    va_start(ap, fmt);
+    vsnprintf(buf, sizeof buf, fmt, ap);
+    va_end(ap);
+    g_err = buf;
+    return st;
+}
+
+#define HIP_TRY(expr)                                                                                  \
+    do {                                                                                               \
+        hipError_t e_ = (expr);                                                                        \
+        if (e_ != hipSuccess) return fail(DYN_ERR_HIP, "%s: %s", #expr, hipGetErrorString(e_));        \
+    } while (0)
+
+struct Dispatch {
+    int layer, op, nano, n_nano, r0, r1, stream, partition;
+    std::vector<int> deps;   // dispatches (indices into the plan) whose output rows this one reads
+    int key() const { return partition * DYN_MAX_STREAMS + stream; }
+};
+
+struct WsLayout {
+    size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, total;
+    size_t gemm_partial[4];   // split-K planes of the qkv, o, gate/up and down projections: operators of
+                              // different micro-batches run concurrently, so each has its own
+    int max_chunks;
+};
+
+struct GraphEntry {
+    uint64_t key;
+    hipGraphExec_t exec;
+    hipGraph_t graph;
+};
+
+}  // namespace
+
+struct dyn_layer {
+    dyn_layer_config cfg;
+    std::vector<dyn_layer_weights> w;
+    dyn::RopeTable rope;
+    int chunk_pages;
+    // GPU state, created on first use
+    hipStream_t streams[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS] = {};
+    std::vector<uint32_t> stream_mask[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
+    hipStream_t capture_stream = nullptr;
+    std::vector<hipEvent_t> events;          // dependency events, one per dispatch of a forward
+    hipEvent_t fork_event = nullptr;
+    std::vector<GraphEntry> graphs;
+    bool profiling = false;
+    std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, stop) per dispatch
+    std::vector<Dispatch> prof_plan;
+};
+
+namespace {
+
+size_t align_up(size_t v) { return (v + 255) & ~(size_t)255; }
+
+size_t esize(const dyn_layer_config &c) { return c.dtype == DYN_F32 ? 4 : 2; }
+
+int qkv_width(const dyn_layer_config &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
+
+WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
+    const dyn_layer_config &c = L->cfg;
+    const size_t e = esize(c), t = (size_t)std::max(T, 0);
+    WsLayout w{};
+    size_t off = 0;
+    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
+    const int pairs = c.n_experts ? c.top_k : 1;
+    w.h = take(t * c.hidden * e);
+    w.qkv = take(t * qkv_width(c) * e);
+    w.attn = take(t * c.n_q_heads * c.head_dim * e);
+    w.x2 = take(t * c.hidden * e);
+    w.gu = take(t * pairs * 2 * c.mlp_inter * e);
+    w.act = take(t * pairs * c.mlp_inter * e);
+    w.xa = take(c.n_layers > 1 ? t * c.hidden * e : 0);
+    w.xb = take(c.n_layers > 2 ? t * c.hidden * e : 0);
+    const int widths[4][2] = {{qkv_width(c), c.hidden}, {c.hidden, c.n_q_heads * c.head_dim},
+                              {2 * c.mlp_inter, c.hidden}, {c.hidden, c.mlp_inter}};
+    for (int i = 0; i < 4; ++i) {
+        const int S = dyn::gemm_split_k(c.dtype, widths[i][0], widths[i][1]);
+        w.gemm_partial[i] = take(S > 1 ? (size_t)S * t * widths[i][0] * sizeof(float) : 0);
+    }
+    w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
+    w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
+    w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
+    w.total = off;
+    return w;
+}
+
+const int kDenseChain[] = {DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ,
+                           DYN_OP_NORM2, DYN_OP_GATE_UP, DYN_OP_SILU, DYN_OP_DOWN};
+const int kMoeChain[] = {DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ,
+                         DYN_OP_NORM2, DYN_OP_ROUTE, DYN_OP_GATE_UP, DYN_OP_SILU, DYN_OP_DOWN};
+
+const char *op_name(int op) {
+    static const char *n[] = {"norm1", "qkv", "rope_kv", "attn", "oproj", "norm2", "route", "gate_up", "silu", "down"};
+    return op >= 0 && op < DYN_N_OPS ? n[op] : "?";
+}
+
+// Checks batch shapes and the schedule, and expands it into the per-forward dispatch list
+// with producer edges.
+dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, std::vector<Dispatch> &plan) {
+    if (!L || !b || !s) return fail(DYN_ERR_INVALID_ARG, "NULL layer, batch or schedule");
+    if (b->n_tokens < 0 || b->n_seqs < 0) return fail(DYN_ERR_INVALID_ARG, "negative n_tokens or n_seqs");
+    if (b->n_tokens > 0 && b->n_seqs == 0) return fail(DYN_ERR_INVALID_ARG, "tokens without sequences");
+    if (!b->q_start_host) return fail(DYN_ERR_INVALID_ARG, "q_start_host is NULL");
+    if (b->q_start_host[0] != 0 || b->q_start_host[b->n_seqs] != b->n_tokens)
+        return fail(DYN_ERR_INVALID_ARG, "q_start_host must run from 0 to n_tokens");
+    for (int i = 0; i < b->n_seqs; ++i)
+        if (b->q_start_host[i + 1] <= b->q_start_host[i])
+            return fail(DYN_ERR_INVALID_ARG, "sequence %d has no token in this step", i);
+    if (b->max_pages_per_seq < 1 && b->n_tokens > 0) return fail(DYN_ERR_INVALID_ARG, "max_pages_per_seq < 1");
+
+    const bool moe = L->cfg.n_experts > 0;
+    const int *chain = moe ? kMoeChain : kDenseChain;
+    const int n_chain = moe ? 10 : 9;
+    const int T = b->n_tokens;
+
+    std::vector<dyn_slot> seq_slots;
+    int32_t seq_rows[2] = {0, T};
+    int k = 1, n_slots = 0;
+    const int32_t *rows = seq_rows;
+    const dyn_slot *slots = nullptr;
+    if (s->mode == DYN_SCHED_SEQUENTIAL) {
+        for (int i = 0; i < n_chain; ++i) seq_slots.push_back(dyn_slot{(uint8_t)chain[i], 0, 1, 0, 0});
+        slots = seq_slots.data();
+        n_slots = n_chain;
+    } else if (s->mode == DYN_SCHED_EXPLICIT) {
+        k = s->k;
+        if (k < 1 || k > DYN_MAX_NANO) return fail(DYN_ERR_SCHEDULE, "k = %d outside 1..%d", k, DYN_MAX_NANO);
+        if (!s->nano_rows || !s->slots || s->n_slots < 1) return fail(DYN_ERR_SCHEDULE, "nano_rows or slots missing");
+        if (s->n_streams < 1 || s->n_streams > DYN_MAX_STREAMS)
+            return fail(DYN_ERR_SCHEDULE, "n_streams = %d outside 1..%d", s->n_streams, DYN_MAX_STREAMS);
+        if (s->n_partitions < 0 || s->n_partitions > DYN_MAX_PARTITIONS)
+            return fail(DYN_ERR_SCHEDULE, "n_partitions = %d outside 0..%d", s->n_partitions, DYN_MAX_PARTITIONS);
+        if (s->n_partitions > 0 && (!s->cu_masks || s->cu_mask_words < 1 || s->cu_mask_words > 32))
+            return fail(DYN_ERR_SCHEDULE, "partitions need cu_masks with 1..32 words each");
+        for (int p = 0; p < s->n_partitions; ++p) {
+            uint32_t any = 0;
+            for (int i = 0; i < s->cu_mask_words; ++i) any |= s->cu_masks[p * s->cu_mask_words + i];
+            if (!any) return fail(DYN_ERR_SCHEDULE, "CU mask of partition %d is empty", p + 1);
+        }
+        rows = s->nano_rows;
+        if (rows[0] != 0 || rows[k] != T) return fail(DYN_ERR_SCHEDULE, "nano_rows must run from 0 to n_tokens");
+        for (int i = 0; i < k; ++i) {
+            if (rows[i + 1] < rows[i]) return fail(DYN_ERR_SCHEDULE, "nano_rows decreases at %d", i);
+            if (!std::binary_search(b->q_start_host, b->q_start_host + b->n_seqs + 1, rows[i]))
+                return fail(DYN_ERR_SCHEDULE, "cut point %d (row %d) is inside a sequence", i, rows[i]);
+        }
+        slots = s->slots;
+        n_slots = s->n_slots;
+    } else {
+        return fail(DYN_ERR_SCHEDULE, "unknown schedule mode %d", s->mode);
+    }
+
+    // cover[op][nano] = slot index that dispatches it
+    int cover[DYN_N_OPS][DYN_MAX_NANO];
+    for (auto &r : cover) std::fill(r, r + DYN_MAX_NANO, -1);
+    int chain_pos[DYN_N_OPS];
+    std::fill(chain_pos, chain_pos + DYN_N_OPS, -1);
+    for (int i = 0; i < n_chain; ++i) chain_pos[chain[i]] = i;
+    for (int i = 0; i < n_slots; ++i) {
+        const dyn_slot &sl = slots[i];
+        if (sl.op >= DYN_N_OPS || chain_pos[sl.op] < 0)
+            return fail(DYN_ERR_SCHEDULE, "slot %d: operator %d is not part of this layer", i, sl.op);
+        if (sl.n_nano < 1 || sl.nano + sl.n_nano > k)
+            return fail(DYN_ERR_SCHEDULE, "slot %d: micro-batches %d..%d outside 0..%d", i, sl.nano,
+                        sl.nano + sl.n_nano - 1, k - 1);
+        if (s->mode == DYN_SCHED_EXPLICIT) {
+            if (sl.stream >= s->n_streams) return fail(DYN_ERR_SCHEDULE, "slot %d: stream %d out of range", i, sl.stream);
+            if (sl.partition > s->n_partitions)
+                return fail(DYN_ERR_SCHEDULE, "slot %d: partition %d out of range", i, sl.partition);
+        }
+        for (int nb = sl.nano; nb < sl.nano + sl.n_nano; ++nb) {
+            if (cover[sl.op][nb] >= 0)
+                return fail(DYN_ERR_SCHEDULE, "slot %d: %s of micro-batch %d dispatched twice", i, op_name(sl.op), nb);
+            const int pos = chain_pos[sl.op];
+            if (pos > 0 && cover[chain[pos - 1]][nb] < 0)
+                return fail(DYN_ERR_SCHEDULE, "slot %d: %s of micro-batch %d issued before its producer %s", i,
+                            op_name(sl.op), nb, op_name(chain[pos - 1]));
+            cover[sl.op][nb] = i;
+        }
+    }
+    for (int i = 0; i < n_chain; ++i)
+        for (int nb = 0; nb < k; ++nb)
+            if (cover[chain[i]][nb] < 0)
+                return fail(DYN_ERR_SCHEDULE, "%s of micro-batch %d is never dispatched", op_name(chain[i]), nb);
+
+    plan.clear();
+    plan.reserve((size_t)L->cfg.n_layers * n_slots);
+    for (int l = 0; l < L->cfg.n_layers; ++l)
+        for (int i = 0; i < n_slots; ++i) {
+            const dyn_slot &sl = slots[i];
+            Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, {}};
+            const int pos = chain_pos[sl.op];
+            for (int nb = sl.nano; nb < sl.nano + sl.n_nano; ++nb) {
+                int dep = -1;
+                if (pos > 0) dep = l * n_slots + cover[chain[pos - 1]][nb];
+                else if (l > 0) dep = (l - 1) * n_slots + cover[chain[n_chain - 1]][nb];
+                if (dep >= 0 && std::find(d.deps.begin(), d.deps.end(), dep) == d.deps.end()) d.deps.push_back(dep);
+            }
+            plan.push_back(std::move(d));
+        }
+    return DYN_OK;
+}
+
+dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream_t *out) {
+    const int partition = key / DYN_MAX_STREAMS;
+    std::vector<uint32_t> mask;
+    if (partition > 0)
+        mask.assign(s->cu_masks + (size_t)(partition - 1) * s->cu_mask_words,
+                    s->cu_masks + (size_t)partition * s->cu_mask_words);
+    if (L->streams[key] && L->stream_mask[key] != mask) {   // partition redefined: rebuild the stream
+        HIP_TRY(hipStreamSynchronize(L->streams[key]));
+        HIP_TRY(hipStreamDestroy(L->streams[key]));
+        L->streams[key] = nullptr;
+    }
+    if (!L->streams[key]) {
+        if (partition > 0)
+            HIP_TRY(hipExtStreamCreateWithCUMask(&L->streams[key], (uint32_t)mask.size(), mask.data()));
+        else
+            HIP_TRY(hipStreamCreateWithFlags(&L->streams[key], hipStreamNonBlocking));
+        L->stream_mask[key] = mask;
+    }
+    *out = L->streams[key];
+    return DYN_OK;
+}
+
+dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws, const Dispatch &d, hipStream_t st) {
+    const dyn_layer_config &c = L->cfg;
+    const dyn_layer_weights &w = L->w[d.layer];
+    const size_t e = esize(c);
+    const int rows = d.r1 - d.r0;
+    if (rows <= 0) return DYN_OK;
+    char *base = (char *)b->workspace;
+    const int H = c.hidden, NQ = c.n_q_heads * c.head_dim, NQKV = qkv_width(c), I = c.mlp_inter;
+    const int nl = c.n_layers;
+    const char *x_in = d.layer == 0 ? (const char *)b->x : (d.layer % 2 ? base + ws.xa : base + ws.xb);
+    char *x_out = d.layer == nl - 1 ? (char *)b->y : (d.layer % 2 ? base + ws.xb : base + ws.xa);
+    auto rowp = [&](const char *p, int width) { return p + (size_t)d.r0 * width * e; };
+    const size_t T = (size_t)b->n_tokens;
+    dyn::AttnShape sh{c.n_q_heads, c.n_kv_heads, c.head_dim, c.page_size, b->max_pages_per_seq, L->chunk_pages, ws.max_chunks};
+    char *kc = (char *)b->k_cache + (size_t)d.layer * b->kv_layer_stride;
+    char *vc = (char *)b->v_cache + (size_t)d.layer * b->kv_layer_stride;
+    auto partial = [&](int i, int width) { return (float *)(base + ws.gemm_partial[i]) + (size_t)d.r0 * width; };
+    hipError_t err = hipSuccess;
+    switch (d.op) {
+        case DYN_OP_NORM1:
+            err = dyn::launch_rmsnorm(c.dtype, rowp(x_in, H), w.g_norm1, (void *)rowp(base + ws.h, H), rows, H, c.rms_eps, st);
+            break;
+        case DYN_OP_QKV:
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, H), w.w_qkv, nullptr, (void *)rowp(base + ws.qkv, NQKV),
+                                   partial(0, NQKV), T * NQKV, rows, NQKV, H, st);
+            break;
+        case DYN_OP_ROPE_KV:
+            err = dyn::launch_rope_kv(c.dtype, (void *)rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0,
+                                      b->pos_of_token + d.r0, b->block_table, kc, vc, L->rope, sh, rows, st);
+            break;
+        case DYN_OP_ATTN:
+            err = dyn::launch_attention(c.dtype, rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0, b->pos_of_token + d.r0,
+                                        b->block_table, kc, vc, (void *)rowp(base + ws.attn, NQ),
+                                        (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
+                                        (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2, sh,
+                                        rows, st);
+            break;
+        case DYN_OP_OPROJ:
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, NQ), w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
+                                   partial(1, H), T * H, rows, H, NQ, st);
+            break;
+        case DYN_OP_NORM2:
+            err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, H), rows, H, c.rms_eps, st);
+            break;
+        case DYN_OP_GATE_UP:
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, H), w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
+                                   partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st);
+            break;
+        case DYN_OP_SILU:
+            err = dyn::launch_silu_mul(c.dtype, rowp(base + ws.gu, 2 * I), (void *)rowp(base + ws.act, I), rows, I, st);
+            break;
+        case DYN_OP_DOWN:
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, I), w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
+                                   partial(3, H), T * H, rows, H, I, st);
+            break;
+        default:
+            return fail(DYN_ERR_UNSUPPORTED, "operator %s has no kernel", op_name(d.op));
+    }
+    if (err != hipSuccess) return fail(DYN_ERR_HIP, "launch of %s failed: %s", op_name(d.op), hipGetErrorString(err));
+    return DYN_OK;
+}
+
+// Issues the plan: fork side streams from origin, wait on producers that ran on another
+// stream, record an event after every dispatch, join everything back into origin.
+dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, const WsLayout &ws,
+                    const std::vector<Dispatch> &plan, hipStream_t origin, bool profile) {
+    while (L->events.size() < plan.size()) {
+        hipEvent_t ev;
+        HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        L->events.push_back(ev);
+    }
+    if (!L->fork_event) HIP_TRY(hipEventCreateWithFlags(&L->fork_event, hipEventDisableTiming));
+    if (profile) {
+        while (L->prof_events.size() < 1 + 2 * plan.size()) {
+            hipEvent_t ev;
+            HIP_TRY(hipEventCreate(&ev));
+            L->prof_events.push_back(ev);
+        }
+        HIP_TRY(hipEventRecord(L->prof_events[0], origin));
+    }
+    HIP_TRY(hipEventRecord(L->fork_event, origin));
+    bool used[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS] = {};
+    int last_on[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
+    std::fill(last_on, last_on + (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS, -1);
+    std::vector<hipStream_t> st_of(plan.size());
+    for (size_t i = 0; i < plan.size(); ++i) {
+        const Dispatch &d = plan[i];
+        const int key = d.key();
+        hipStream_t st = origin;
+        if (key != 0) {
+            dyn_status rc = ensure_stream(L, s, key, &st);
+            if (rc != DYN_OK) return rc;
+            if (!used[key]) HIP_TRY(hipStreamWaitEvent(st, L->fork_event, 0));
+        }
+        used[key] = true;
+        st_of[i] = st;
+        for (int dep : d.deps)
+            if (st_of[dep] != st) HIP_TRY(hipStreamWaitEvent(st, L->events[dep], 0));
+        if (profile) HIP_TRY(hipEventRecord(L->prof_events[1 + 2 * i], st));
+        dyn_status rc = launch_op(L, b, ws, d, st);
+        if (rc != DYN_OK) return rc;
+        if (profile) HIP_TRY(hipEventRecord(L->prof_events[2 + 2 * i], st));
+        HIP_TRY(hipEventRecord(L->events[i], st));
+        last_on[key] = (int)i;
+    }
+    for (int key = 1; key < (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS; ++key)
+        if (last_on[key] >= 0) HIP_TRY(hipStreamWaitEvent(origin, L->events[last_on[key]], 0));
+    return DYN_OK;
+}
+
+uint64_t fnv(uint64_t h, const void *p, size_t n) {
+    const unsigned char *c = (const unsigned char *)p;
+    for (size_t i = 0; i < n; ++i) { h ^= c[i]; h *= 1099511628211ull; }
+    return h;
+}
+
+uint64_t graph_key(const dyn_batch *b, const dyn_schedule *s, const std::vector<Dispatch> &plan) {
+    uint64_t h = 1469598103934665603ull;
+    const void *ptrs[] = {b->x, b->y, b->seq_of_token, b->pos_of_token, b->block_table, b->k_cache, b->v_cache, b->workspace};
+    h = fnv(h, ptrs, sizeof ptrs);
+    const int64_t dims[] = {b->n_tokens, b->n_seqs, b->max_pages_per_seq, (int64_t)b->kv_layer_stride,
+                            (int64_t)b->workspace_bytes};
+    h = fnv(h, dims, sizeof dims);
+    for (const Dispatch &d : plan) {
+        const int f[] = {d.layer, d.op, d.r0, d.r1, d.stream, d.partition};
+        h = fnv(h, f, sizeof f);
+    }
+    if (s->mode == DYN_SCHED_EXPLICIT && s->n_partitions > 0)
+        h = fnv(h, s->cu_masks, sizeof(uint32_t) * s->n_partitions * s->cu_mask_words);
+    return h;
+}
+
+dyn_status check_config(const dyn_layer_config *c) {
+    if (c->dtype != DYN_F32 && c->dtype != DYN_BF16) return fail(DYN_ERR_INVALID_ARG, "dtype %d", c->dtype);
+    if (c->n_layers < 1 || c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 ||
+        c->mlp_inter < 1 || c->page_size < 1)
+        return fail(DYN_ERR_INVALID_ARG, "non-positive layer dimension");
+    if (c->n_q_heads % c->n_kv_heads) return fail(DYN_ERR_INVALID_ARG, "n_q_heads not a multiple of n_kv_heads");
+    if (c->n_experts < 0 || c->top_k < 0 || (c->n_experts == 0) != (c->top_k == 0) || c->top_k > c->n_experts)
+        return fail(DYN_ERR_INVALID_ARG, "n_experts / top_k inconsistent");
+    if (!(c->rms_eps >= 0.f) || !(c->rope_base > 0.f)) return fail(DYN_ERR_INVALID_ARG, "rms_eps or rope_base");
+    const int d = c->head_dim, vec = c->dtype == DYN_F32 ? 4 : 8;
+    if (d < 8 || d > 2 * dyn::kMaxHalfDim || (d & (d - 1))) return fail(DYN_ERR_UNSUPPORTED, "head_dim must be a power of two in 8..256");
+    if (c->hidden % vec || c->mlp_inter % vec) return fail(DYN_ERR_UNSUPPORTED, "hidden and mlp_inter must be multiples of %d", vec);
+    if (c->page_size > 512) return fail(DYN_ERR_UNSUPPORTED, "page_size > 512");
+    const int nk[4][2] = {{(c->n_q_heads + 2 * c->n_kv_heads) * d, c->hidden}, {c->hidden, c->n_q_heads * d},
+                          {2 * c->mlp_inter, c->hidden}, {c->hidden, c->mlp_inter}};
+    for (auto &p : nk)
+        if (!dyn::gemm_supported(c->dtype, p[0], p[1]))
+            return fail(DYN_ERR_UNSUPPORTED, "projection %d x %d: bf16 needs widths that are multiples of 128 and depths of 64", p[0], p[1]);
+    if (c->n_experts > 0) return fail(DYN_ERR_UNSUPPORTED, "mixture-of-experts layers are not built yet");
+    return DYN_OK;
+}
+
+}  // namespace
+
+extern "C" {
+
+const char *dyn_last_error(void) { return g_err.c_str(); }
+
+dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights *weights, dyn_layer **out) {
+    if (!cfg || !weights || !out) return fail(DYN_ERR_INVALID_ARG, "NULL argument");
+    *out = nullptr;
+    dyn_status rc = check_config(cfg);
+    if (rc != DYN_OK) return rc;
+    for (int l = 0; l < cfg->n_layers; ++l) {
+        const dyn_layer_weights &w = weights[l];
+        if (!w.w_qkv || !w.w_o || !w.w_gate_up || !w.w_down || !w.g_norm1 || !w.g_norm2 || (cfg->n_experts && !w.w_router))
+            return fail(DYN_ERR_INVALID_ARG, "layer %d: NULL weight pointer", l);
+    }
+    dyn_layer *L = new dyn_layer();
+    L->cfg = *cfg;
+    L->w.assign(weights, weights + cfg->n_layers);
+    for (int i = 0; i < cfg->head_dim / 2; ++i)
+        L->rope.inv_freq[i] = std::pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim);
+    // split-KV chunk: 256 positions, a constant of the layer
+    L->chunk_pages = std::max(1, 256 / cfg->page_size);
+    *out = L;
+    return DYN_OK;
+}
+
+void dyn_layer_destroy(dyn_layer *L) {
+    if (!L) return;
+    for (auto &g : L->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+    for (auto ev : L->events) (void)hipEventDestroy(ev);
+    for (auto ev : L->prof_events) (void)hipEventDestroy(ev);
+    if (L->fork_event) (void)hipEventDestroy(L->fork_event);
+    for (auto st : L->streams) if (st) (void)hipStreamDestroy(st);
+    if (L->capture_stream) (void)hipStreamDestroy(L->capture_stream);
+    delete L;
+}
+
+size_t dyn_layer_workspace_bytes(const dyn_layer *L, int max_tokens, int max_pages_per_seq) {
+    if (!L || max_tokens < 0 || max_pages_per_seq < 0) return 0;
+    return ws_layout(L, max_tokens, max_pages_per_seq).total;
+}
+
+dyn_status dyn_schedule_validate(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s) {
+    std::vector<Dispatch> plan;
+    return build_plan(L, b, s, plan);
+}
+
+dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, void *hip_stream) {
+    std::vector<Dispatch> plan;
+    dyn_status rc = build_plan(L, b, s, plan);
+    if (rc != DYN_OK) return rc;
+    if (b->n_tokens == 0) return DYN_OK;
+    if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table || !b->k_cache || !b->v_cache)
+        return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
+    if (b->x == b->y) return fail(DYN_ERR_INVALID_ARG, "y must not alias x");
+    if (L->cfg.n_layers > 1 && b->kv_layer_stride == 0) return fail(DYN_ERR_INVALID_ARG, "kv_layer_stride is 0 with several layers");
+    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    if (!b->workspace || ((uintptr_t)b->workspace & 255)) return fail(DYN_ERR_WORKSPACE, "workspace missing or not 256-byte aligned");
+    if (b->workspace_bytes < ws.total)
+        return fail(DYN_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", b->workspace_bytes, ws.total);
+    hipStream_t origin = (hipStream_t)hip_stream;
+
+    if (!s->use_graph) {
+        rc = run_plan(L, b, s, ws, plan, origin, L->profiling);
+        if (rc == DYN_OK && L->profiling) L->prof_plan = plan;
+        return rc;
+    }
+    if (L->profiling) return fail(DYN_ERR_UNSUPPORTED, "profiling records eager schedules only");
+    const uint64_t key = graph_key(b, s, plan);
+    for (auto &g : L->graphs)
+        if (g.key == key) {
+            HIP_TRY(hipGraphLaunch(g.exec, origin));
+            return DYN_OK;
+        }
+    if (!L->capture_stream) HIP_TRY(hipStreamCreateWithFlags(&L->capture_stream, hipStreamNonBlocking));
+    // create every stream and event before capture starts
+    for (const Dispatch &d : plan)
+        if (d.key() != 0) {
+            hipStream_t tmp;
+            rc = ensure_stream(L, s, d.key(), &tmp);
+            if (rc != DYN_OK) return rc;
+        }
+    while (L->events.size() < plan.size()) {
+        hipEvent_t ev;
+        HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));
+        L->events.push_back(ev);
+    }
+    if (!L->fork_event) HIP_TRY(hipEventCreateWithFlags(&L->fork_event, hipEventDisableTiming));
+    HIP_TRY(hipStreamBeginCapture(L->capture_stream, hipStreamCaptureModeRelaxed));
+    rc = run_plan(L, b, s, ws, plan, L->capture_stream, false);
+    hipGraph_t graph = nullptr;
+    hipError_t e = hipStreamEndCapture(L->capture_stream, &graph);
+    if (rc != DYN_OK) { if (graph) (void)hipGraphDestroy(graph); return rc; }
+    if (e != hipSuccess) return fail(DYN_ERR_HIP, "hipStreamEndCapture: %s", hipGetErrorString(e));
+    hipGraphExec_t exec = nullptr;
+    e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
+    if (e != hipSuccess) { (void)hipGraphDestroy(graph); return fail(DYN_ERR_HIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
+    if (L->graphs.size() >= 16) {
+        (void)hipGraphExecDestroy(L->graphs.front().exec);
+        (void)hipGraphDestroy(L->graphs.front().graph);
+        L->graphs.erase(L->graphs.begin());
+    }
+    L->graphs.push_back(GraphEntry{key, exec, graph});
+    HIP_TRY(hipGraphLaunch(exec, origin));
+    return DYN_OK;
+}
+
+dyn_status dyn_layer_set_profiling(dyn_layer *L, int on) {
+    if (!L) return fail(DYN_ERR_INVALID_ARG, "NULL layer");
+    L->profiling = on != 0;
+    return DYN_OK;
+}
+
+dyn_status dyn_layer_get_slot_times(dyn_layer *L, dyn_slot_time *out, int capacity, int *n_out) {
+    if (!L || !n_out || (capacity > 0 && !out)) return fail(DYN_ERR_INVALID_ARG, "NULL argument");
+    const int n = (int)L->prof_plan.size();
+    *n_out = n;
+    for (int i = 0; i < n && i < capacity; ++i) {
+        const Dispatch &d = L->prof_plan[i];
+        out[i] = dyn_slot_time{d.layer, d.op, d.nano, d.n_nano, d.stream, d.partition, 0.f, 0.f};
+        HIP_TRY(hipEventElapsedTime(&out[i].start_ms, L->prof_events[0], L->prof_events[1 + 2 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].stop_ms, L->prof_events[0], L->prof_events[2 + 2 * i]));
+    }
+    return DYN_OK;
+}
+
+}  // extern "C"

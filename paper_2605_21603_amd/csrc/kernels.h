@@ -1,0 +1,51 @@
+// Host-side launch functions of the gfx950 kernels.  Each takes pointers already offset to
+// the first token row of the dispatch and the number of rows; none synchronises or
+// allocates.  dtype is DYN_F32 (0) or DYN_BF16 (1).
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stddef.h>
+#include <stdint.h>
+
+namespace dyn {
+
+constexpr int kMaxHalfDim = 128;   // rotary tables are passed by value: head_dim <= 256
+
+struct RopeTable {                 // theta_i = base^(-2i/d), i < d/2, computed on the host in fp64
+    double inv_freq[kMaxHalfDim];
+};
+
+struct AttnShape {
+    int n_q, n_kv, head_dim, page_size;
+    int max_pages_per_seq;         // block-table row length
+    int chunk_pages;               // pages per split-KV chunk (a constant of the layer)
+    int max_chunks;                // chunks that fit max_pages_per_seq: stride of the partial arrays
+};
+
+// Split-K factor of a GEMM with output width N and depth K.  A function of (N, K) alone so
+// that a row's summation order never depends on how many rows are in flight.
+int gemm_split_k(int dtype, int N, int K);
+bool gemm_supported(int dtype, int N, int K);
+
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H, float eps,
+                          hipStream_t s);
+
+// Y[rows,N] = X[rows,K] W[N,K]^T (+ R[rows,N]).  partial: fp32 scratch for split-K planes,
+// plane p at partial + p * plane_stride (elements); unused when the split factor is 1.
+hipError_t launch_gemm(int dtype, const void *X, const void *W, const void *R, void *Y, float *partial,
+                       size_t plane_stride, int rows, int N, int K, hipStream_t s);
+
+// Rotary on the q and k heads of qkv rows (in place for q) and cache append of k', v.
+hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
+                          const int32_t *block_table, void *k_cache, void *v_cache, const RopeTable &tab,
+                          const AttnShape &sh, int rows, hipStream_t s);
+
+// Causal paged attention for token rows; part_o / part_ml are the split-KV partial arrays
+// ([rows, n_q, max_chunks, head_dim] and [rows, n_q, max_chunks, 2]).
+hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
+                            const int32_t *block_table, const void *k_cache, const void *v_cache, void *out,
+                            float *part_o, float *part_ml, const AttnShape &sh, int rows, hipStream_t s);
+
+// out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
+hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int rows, int I, hipStream_t s);
+
+}  // namespace dyn

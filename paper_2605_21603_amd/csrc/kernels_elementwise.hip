@@ -1,0 +1,142 @@
+// RMSNorm, rotary + KV-cache append, SiLU-gate: the memory-bound elementwise operators of
+// the layer (the paper's "normalization" class, Section 2).  fp32 arithmetic, storage
+// type T.  Every output row depends on its own input row only and is reduced in an order
+// fixed by the block shape, so results do not depend on how a batch is split.
+#include "common.h"
+#include "kernels.h"
+
+namespace dyn {
+
+// ------------------------------------------------------------------ RMSNorm
+// One 256-thread workgroup per row.  out = x * g / sqrt(mean(x^2) + eps).
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ x, const T *__restrict__ g,
+                                                      T *__restrict__ out, int H, float eps) {
+    constexpr int V = 16 / sizeof(T);
+    typedef T vec_t __attribute__((ext_vector_type(V)));
+    const size_t row = blockIdx.x;
+    const vec_t *xr = reinterpret_cast<const vec_t *>(x + row * H);
+    const vec_t *gr = reinterpret_cast<const vec_t *>(g);
+    vec_t *orow = reinterpret_cast<vec_t *>(out + row * H);
+    const int nv = H / V;
+    float ss = 0.f;
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        vec_t v = xr[i];
+#pragma unroll
+        for (int e = 0; e < V; ++e) { float f = to_f32<T>(v[e]); ss += f * f; }
+    }
+    ss = wave_sum(ss);
+    __shared__ float part[4];
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    const float total = ((part[0] + part[1]) + part[2]) + part[3];
+    const float r = 1.0f / sqrtf(total / (float)H + eps);
+    for (int i = threadIdx.x; i < nv; i += 256) {
+        vec_t v = xr[i], gv = gr[i], o;
+#pragma unroll
+        for (int e = 0; e < V; ++e) o[e] = from_f32<T>(to_f32<T>(v[e]) * r * to_f32<T>(gv[e]));
+        orow[i] = o;
+    }
+}
+
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H, float eps,
+                          hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype == 0)
+        hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)x, (const float *)g,
+                           (float *)out, H, eps);
+    else
+        hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)x,
+                           (const bf16_t *)g, (bf16_t *)out, H, eps);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ rotary + cache append
+// One 128-thread workgroup per token.  Thread (i, hg): pair index i < d/2, head group hg.
+// The angle pos * theta_i and its sine/cosine are formed in fp64 so that the rotation is
+// exact to fp32 rounding at any position.
+template <typename T>
+__global__ __launch_bounds__(128) void rope_kv_kernel(T *__restrict__ qkv, const int32_t *__restrict__ seq_of_token,
+                                                      const int32_t *__restrict__ pos_of_token,
+                                                      const int32_t *__restrict__ block_table,
+                                                      T *__restrict__ k_cache, T *__restrict__ v_cache,
+                                                      RopeTable tab, AttnShape sh) {
+    const int t = blockIdx.x;
+    const int d = sh.head_dim, half = d >> 1;
+    const int i = threadIdx.x % half, hg = threadIdx.x / half, n_hg = 128 / half;
+    const int pos = pos_of_token[t];
+    const int page = block_table[(size_t)seq_of_token[t] * sh.max_pages_per_seq + pos / sh.page_size];
+    const int slot = pos % sh.page_size;
+    double sn, cs;
+    sincos((double)pos * tab.inv_freq[i], &sn, &cs);
+    const float c = (float)cs, s = (float)sn;
+    T *row = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * d);
+    for (int h = hg; h < sh.n_q; h += n_hg) {            // q heads, in place
+        T *z = row + h * d;
+        const float a = to_f32<T>(z[i]), b = to_f32<T>(z[i + half]);
+        z[i] = from_f32<T>(a * c - b * s);
+        z[i + half] = from_f32<T>(b * c + a * s);
+    }
+    for (int g = hg; g < sh.n_kv; g += n_hg) {           // k heads -> K page [kvh][slot][d]
+        const T *z = row + (sh.n_q + g) * d;
+        const float a = to_f32<T>(z[i]), b = to_f32<T>(z[i + half]);
+        T *kp = k_cache + (((size_t)page * sh.n_kv + g) * sh.page_size + slot) * d;
+        kp[i] = from_f32<T>(a * c - b * s);
+        kp[i + half] = from_f32<T>(b * c + a * s);
+        const T *v = row + (sh.n_q + sh.n_kv + g) * d;   // v heads -> V page [kvh][d][slot]
+        T *vp = v_cache + ((size_t)page * sh.n_kv + g) * d * sh.page_size + slot;
+        vp[(size_t)i * sh.page_size] = v[i];
+        vp[(size_t)(i + half) * sh.page_size] = v[i + half];
+    }
+}
+
+hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
+                          const int32_t *block_table, void *k_cache, void *v_cache, const RopeTable &tab,
+                          const AttnShape &sh, int rows, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    if (dtype == 0)
+        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(128), 0, s, (float *)qkv, seq_of_token,
+                           pos_of_token, block_table, (float *)k_cache, (float *)v_cache, tab, sh);
+    else
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(rows), dim3(128), 0, s, (bf16_t *)qkv, seq_of_token,
+                           pos_of_token, block_table, (bf16_t *)k_cache, (bf16_t *)v_cache, tab, sh);
+    return hipGetLastError();
+}
+
+// ------------------------------------------------------------------ SiLU gate
+// out[t, i] = g / (1 + exp(-g)) * u with g = gu[t, i], u = gu[t, I + i].
+template <typename T>
+__global__ __launch_bounds__(256) void silu_mul_kernel(const T *__restrict__ gu, T *__restrict__ out, int I,
+                                                       size_t n_vec) {
+    constexpr int V = 16 / sizeof(T);
+    typedef T vec_t __attribute__((ext_vector_type(V)));
+    const int vec_per_row = I / V;
+    for (size_t idx = (size_t)blockIdx.x * 256 + threadIdx.x; idx < n_vec; idx += (size_t)gridDim.x * 256) {
+        const size_t t = idx / vec_per_row, c = idx % vec_per_row;
+        const vec_t g = *reinterpret_cast<const vec_t *>(gu + t * 2 * I + c * V);
+        const vec_t u = *reinterpret_cast<const vec_t *>(gu + t * 2 * I + I + c * V);
+        vec_t o;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const float z = to_f32<T>(g[e]);
+            o[e] = from_f32<T>(z / (1.0f + expf(-z)) * to_f32<T>(u[e]));
+        }
+        *reinterpret_cast<vec_t *>(out + t * I + c * V) = o;
+    }
+}
+
+hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int rows, int I, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    const int V = dtype == 0 ? 4 : 8;
+    const size_t n_vec = (size_t)rows * (I / V);
+    const int blocks = (int)((n_vec + 255) / 256 < 4096 ? (n_vec + 255) / 256 : 4096);
+    if (dtype == 0)
+        hipLaunchKernelGGL(silu_mul_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)gu, (float *)out, I,
+                           n_vec);
+    else
+        hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)gu,
+                           (bf16_t *)out, I, n_vec);
+    return hipGetLastError();
+}
+
+}  // namespace dyn

@@ -1,0 +1,82 @@
+"""GPU parity: the HIP path through the C-ABI against the CPU oracle, and every legal
+schedule against the sequential one, bit for bit."""
+import numpy as np
+import pytest
+import torch
+
+from paper_2605_21603_amd import binding as B
+from workloads import gen
+
+from gpu_util import GpuRun, check_against_oracle, say
+
+pytestmark = pytest.mark.gpu
+
+SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small"]
+
+
+def schedules_for(w):
+    rows = w.nano_rows
+    k = len(rows) - 1
+    T = w.n_tokens
+    out = {
+        "split": B.nano_schedule(rows),
+        "split_stagger2": B.nano_schedule(rows, stagger=2),
+        "split_one_stream": B.nano_schedule(rows, streams=[0] * k),
+        "mlp_merged": B.nano_schedule(rows, merged_ops=[B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN], stagger=1),
+        "gemms_merged": B.nano_schedule(rows, merged_ops=[B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP, B.DYN_OP_DOWN],
+                                        stagger=1),
+        "with_empty_nano": B.nano_schedule((0,) + tuple(rows) if rows[1] != 0 else rows),
+    }
+    return out
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_sequential_matches_oracle(name):
+    say("case %s sequential" % name)
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y, kc, vc = run.run(B.sequential())
+    err = check_against_oracle(w, data, y, kc, vc)
+    say("case %s max rel err %.3e" % (name, err))
+
+
+@pytest.mark.parametrize("name", SMALL)
+def test_every_schedule_is_bit_exact_against_sequential(name):
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    for label, sched in schedules_for(w).items():
+        say("case %s schedule %s" % (name, label))
+        y, kc, vc = run.run(sched)
+        assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
+        assert torch.equal(kc.view(torch.uint8), k0.view(torch.uint8)), label
+        assert torch.equal(vc.view(torch.uint8), v0.view(torch.uint8)), label
+
+
+def test_empty_batch_is_a_no_op():
+    w = gen.config("c2_small")
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    step = B.DeviceStep(run.layer, data)
+    step.batch.n_tokens = 0
+    step.batch.n_seqs = 0
+    run.layer.forward(step.batch, B.sequential(), torch.cuda.Stream())
+    torch.cuda.synchronize()
+
+
+def test_forward_rejects_small_workspace_and_aliasing():
+    w = gen.config("c2_small")
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    step = B.DeviceStep(run.layer, data)
+    step.batch.workspace_bytes = 1024
+    with pytest.raises(B.DynError) as e:
+        run.layer.forward(step.batch, B.sequential(), torch.cuda.Stream())
+    assert e.value.status == B.DYN_ERR_WORKSPACE
+    step = B.DeviceStep(run.layer, data)
+    step.batch.y = step.batch.x
+    with pytest.raises(B.DynError) as e:
+        run.layer.forward(step.batch, B.sequential(), torch.cuda.Stream())
+    assert e.value.status == B.DYN_ERR_INVALID_ARG
