@@ -159,7 +159,10 @@ dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn
  * the last forward, one record per dispatch in issue order (layer-major). */
 typedef struct {
     int layer, op, nano, n_nano, stream, partition;
-    float start_ms, stop_ms;   /* relative to the fork point of that forward */
+    float start_ms;            /* times relative to the fork point of that forward */
+    float main_stop_ms;        /* end of the operator's main kernel (the contraction or the attention chunk
+                                  kernel) where a second kernel follows (split-K reduce, split-KV combine) */
+    float stop_ms;
 } dyn_slot_time;
 dyn_status dyn_layer_set_profiling(dyn_layer *layer, int on);
 dyn_status dyn_layer_get_slot_times(dyn_layer *layer, dyn_slot_time *out, int capacity, int *n_out);

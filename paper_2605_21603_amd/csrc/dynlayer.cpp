@@ -48,7 +48,8 @@ struct Dispatch {
 };
 
 struct WsLayout {
-    size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, total;
+    size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, plan, total;
+    int ld_h, ld_attn, ld_act;   // padded row strides (elements) of the buffers the projections read
     size_t gemm_partial[4];   // split-K planes of the qkv, o, gate/up and down projections: operators of
                               // different micro-batches run concurrently, so each has its own
     int max_chunks;
@@ -75,7 +76,7 @@ struct dyn_layer {
     hipEvent_t fork_event = nullptr;
     std::vector<GraphEntry> graphs;
     bool profiling = false;
-    std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, stop) per dispatch
+    std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, main stop, stop) per dispatch
     std::vector<Dispatch> prof_plan;
 };
 
@@ -94,12 +95,19 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     size_t off = 0;
     auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     const int pairs = c.n_experts ? c.top_k : 1;
-    w.h = take(t * c.hidden * e);
+    // Rows of a GEMM input are read 64 bytes at a time by 16 lanes on 16 different rows; with a
+    // power-of-two row pitch those land in one L2 channel.  256 bytes of padding per row walks
+    // consecutive rows across the channels.
+    const int pad = (int)(256 / e);
+    w.ld_h = c.hidden + pad;
+    w.ld_attn = c.n_q_heads * c.head_dim + pad;
+    w.ld_act = c.mlp_inter + pad;
+    w.h = take(t * w.ld_h * e);
     w.qkv = take(t * qkv_width(c) * e);
-    w.attn = take(t * c.n_q_heads * c.head_dim * e);
+    w.attn = take(t * w.ld_attn * e);
     w.x2 = take(t * c.hidden * e);
     w.gu = take(t * pairs * 2 * c.mlp_inter * e);
-    w.act = take(t * pairs * c.mlp_inter * e);
+    w.act = take(t * pairs * w.ld_act * e);
     w.xa = take(c.n_layers > 1 ? t * c.hidden * e : 0);
     w.xb = take(c.n_layers > 2 ? t * c.hidden * e : 0);
     const int widths[4][2] = {{qkv_width(c), c.hidden}, {c.hidden, c.n_q_heads * c.head_dim},
@@ -111,6 +119,7 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
     w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
     w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
+    w.plan = take((t * w.max_chunks + t) * 2 * sizeof(int32_t));   // per dispatch: 2 header words + 2 per entry
     w.total = off;
     return w;
 }
@@ -254,7 +263,8 @@ dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream
     return DYN_OK;
 }
 
-dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws, const Dispatch &d, hipStream_t st) {
+dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws, const Dispatch &d, hipStream_t st,
+                     hipEvent_t mid) {
     const dyn_layer_config &c = L->cfg;
     const dyn_layer_weights &w = L->w[d.layer];
     const size_t e = esize(c);
@@ -274,11 +284,11 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
     hipError_t err = hipSuccess;
     switch (d.op) {
         case DYN_OP_NORM1:
-            err = dyn::launch_rmsnorm(c.dtype, rowp(x_in, H), w.g_norm1, (void *)rowp(base + ws.h, H), rows, H, c.rms_eps, st);
+            err = dyn::launch_rmsnorm(c.dtype, rowp(x_in, H), w.g_norm1, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
             break;
         case DYN_OP_QKV:
-            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, H), w.w_qkv, nullptr, (void *)rowp(base + ws.qkv, NQKV),
-                                   partial(0, NQKV), T * NQKV, rows, NQKV, H, st);
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_qkv, nullptr, (void *)rowp(base + ws.qkv, NQKV),
+                                   partial(0, NQKV), T * NQKV, rows, NQKV, H, st, mid);
             break;
         case DYN_OP_ROPE_KV:
             err = dyn::launch_rope_kv(c.dtype, (void *)rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0,
@@ -286,28 +296,28 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
             break;
         case DYN_OP_ATTN:
             err = dyn::launch_attention(c.dtype, rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0, b->pos_of_token + d.r0,
-                                        b->block_table, kc, vc, (void *)rowp(base + ws.attn, NQ),
+                                        b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
                                         (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
-                                        (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2, sh,
-                                        rows, st);
+                                        (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
+                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 2, sh, rows, st, mid);
             break;
         case DYN_OP_OPROJ:
-            err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, NQ), w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
-                                   partial(1, H), T * H, rows, H, NQ, st);
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
+                                   partial(1, H), T * H, rows, H, NQ, st, mid);
             break;
         case DYN_OP_NORM2:
-            err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, H), rows, H, c.rms_eps, st);
+            err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
             break;
         case DYN_OP_GATE_UP:
-            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, H), w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
-                                   partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st);
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
+                                   partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st, mid);
             break;
         case DYN_OP_SILU:
-            err = dyn::launch_silu_mul(c.dtype, rowp(base + ws.gu, 2 * I), (void *)rowp(base + ws.act, I), rows, I, st);
+            err = dyn::launch_silu_mul(c.dtype, rowp(base + ws.gu, 2 * I), (void *)rowp(base + ws.act, ws.ld_act), ws.ld_act, rows, I, st);
             break;
         case DYN_OP_DOWN:
-            err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, I), w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
-                                   partial(3, H), T * H, rows, H, I, st);
+            err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, ws.ld_act), ws.ld_act, w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
+                                   partial(3, H), T * H, rows, H, I, st, mid);
             break;
         default:
             return fail(DYN_ERR_UNSUPPORTED, "operator %s has no kernel", op_name(d.op));
@@ -327,7 +337,7 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
     }
     if (!L->fork_event) HIP_TRY(hipEventCreateWithFlags(&L->fork_event, hipEventDisableTiming));
     if (profile) {
-        while (L->prof_events.size() < 1 + 2 * plan.size()) {
+        while (L->prof_events.size() < 1 + 3 * plan.size()) {
             hipEvent_t ev;
             HIP_TRY(hipEventCreate(&ev));
             L->prof_events.push_back(ev);
@@ -352,10 +362,13 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
         st_of[i] = st;
         for (int dep : d.deps)
             if (st_of[dep] != st) HIP_TRY(hipStreamWaitEvent(st, L->events[dep], 0));
-        if (profile) HIP_TRY(hipEventRecord(L->prof_events[1 + 2 * i], st));
-        dyn_status rc = launch_op(L, b, ws, d, st);
+        if (profile) {
+            HIP_TRY(hipEventRecord(L->prof_events[1 + 3 * i], st));
+            HIP_TRY(hipEventRecord(L->prof_events[2 + 3 * i], st));   // stays here unless the operator has two kernels
+        }
+        dyn_status rc = launch_op(L, b, ws, d, st, profile && d.r1 > d.r0 ? L->prof_events[2 + 3 * i] : nullptr);
         if (rc != DYN_OK) return rc;
-        if (profile) HIP_TRY(hipEventRecord(L->prof_events[2 + 2 * i], st));
+        if (profile) HIP_TRY(hipEventRecord(L->prof_events[3 + 3 * i], st));
         HIP_TRY(hipEventRecord(L->events[i], st));
         last_on[key] = (int)i;
     }
@@ -403,7 +416,7 @@ dyn_status check_config(const dyn_layer_config *c) {
                           {2 * c->mlp_inter, c->hidden}, {c->hidden, c->mlp_inter}};
     for (auto &p : nk)
         if (!dyn::gemm_supported(c->dtype, p[0], p[1]))
-            return fail(DYN_ERR_UNSUPPORTED, "projection %d x %d: bf16 needs widths that are multiples of 128 and depths of 64", p[0], p[1]);
+            return fail(DYN_ERR_UNSUPPORTED, "projection %d x %d: bf16 needs widths that are multiples of 128 and depths that are multiples of 256", p[0], p[1]);
     if (c->n_experts > 0) return fail(DYN_ERR_UNSUPPORTED, "mixture-of-experts layers are not built yet");
     return DYN_OK;
 }
@@ -528,9 +541,11 @@ dyn_status dyn_layer_get_slot_times(dyn_layer *L, dyn_slot_time *out, int capaci
     *n_out = n;
     for (int i = 0; i < n && i < capacity; ++i) {
         const Dispatch &d = L->prof_plan[i];
-        out[i] = dyn_slot_time{d.layer, d.op, d.nano, d.n_nano, d.stream, d.partition, 0.f, 0.f};
-        HIP_TRY(hipEventElapsedTime(&out[i].start_ms, L->prof_events[0], L->prof_events[1 + 2 * i]));
-        HIP_TRY(hipEventElapsedTime(&out[i].stop_ms, L->prof_events[0], L->prof_events[2 + 2 * i]));
+        out[i] = dyn_slot_time{d.layer, d.op, d.nano, d.n_nano, d.stream, d.partition, 0.f, 0.f, 0.f};
+        HIP_TRY(hipEventElapsedTime(&out[i].start_ms, L->prof_events[0], L->prof_events[1 + 3 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].main_stop_ms, L->prof_events[0], L->prof_events[2 + 3 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].stop_ms, L->prof_events[0], L->prof_events[3 + 3 * i]));
+        if (out[i].main_stop_ms <= out[i].start_ms) out[i].main_stop_ms = out[i].stop_ms;   // one-kernel operator
     }
     return DYN_OK;
 }

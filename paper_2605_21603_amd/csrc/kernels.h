@@ -26,13 +26,15 @@ struct AttnShape {
 int gemm_split_k(int dtype, int N, int K);
 bool gemm_supported(int dtype, int N, int K);
 
-hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H, float eps,
+// ld_out: elements between output rows (>= H).
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int ld_out, int rows, int H, float eps,
                           hipStream_t s);
 
-// Y[rows,N] = X[rows,K] W[N,K]^T (+ R[rows,N]).  partial: fp32 scratch for split-K planes,
+// Y[rows,N] = X[rows,K] W[N,K]^T (+ R[rows,N]); ldx = elements between rows of X (>= K).  partial: fp32 scratch for split-K planes,
 // plane p at partial + p * plane_stride (elements); unused when the split factor is 1.
-hipError_t launch_gemm(int dtype, const void *X, const void *W, const void *R, void *Y, float *partial,
-                       size_t plane_stride, int rows, int N, int K, hipStream_t s);
+// If mid is not NULL it is recorded after the contraction kernel, before the split-K reduce.
+hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
+                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid = nullptr);
 
 // Rotary on the q and k heads of qkv rows (in place for q) and cache append of k', v.
 hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
@@ -40,12 +42,14 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
                           const AttnShape &sh, int rows, hipStream_t s);
 
 // Causal paged attention for token rows; part_o / part_ml are the split-KV partial arrays
-// ([rows, n_q, max_chunks, head_dim] and [rows, n_q, max_chunks, 2]).
+// ([rows, n_q, max_chunks, head_dim] and [rows, n_q, max_chunks, 2]); plan is scratch for the
+// device-built work list (2 + 2 * rows * max_chunks int32).
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
-                            const int32_t *block_table, const void *k_cache, const void *v_cache, void *out,
-                            float *part_o, float *part_ml, const AttnShape &sh, int rows, hipStream_t s);
+                            const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
+                            float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
+                            hipStream_t s, hipEvent_t mid = nullptr);   // mid: recorded between the chunk kernel and the combine
 
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
-hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int rows, int I, hipStream_t s);
+hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s);
 
 }  // namespace dyn

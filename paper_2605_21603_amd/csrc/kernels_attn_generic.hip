@@ -73,50 +73,91 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const T *__restrict__ 
     }
 }
 
-// One workgroup per (token, q head); thread i < head_dim.  Partials are merged in chunk
-// order: M = max m_c, out = sum_c e(m_c - M) o_c / sum_c e(m_c - M) l_c, where e is exp or
-// exp2 according to the domain the producing kernel kept m in.
+// 32 lanes per (token, q head), 8 pairs per 256-thread workgroup; a lane owns 4 consecutive
+// head-dim indices.  Partials are merged in chunk order: M = max m_c,
+// out = sum_c e(m_c - M) o_c / sum_c e(m_c - M) l_c, where e is exp or exp2 according to the
+// domain the producing kernel kept m in.
 template <typename T, bool BASE2>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml,
                                                            const int32_t *__restrict__ pos_of_token,
-                                                           T *__restrict__ out, AttnShape sh) {
-    const int h = blockIdx.x % sh.n_q, t = blockIdx.x / sh.n_q;
+                                                           T *__restrict__ out, int ld_out, AttnShape sh, int n_pairs) {
+    const int pair = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    if (pair >= n_pairs) return;
+    const int t = pair / sh.n_q;
     const int d = sh.head_dim, ct = sh.chunk_pages * sh.page_size;
     const int n_chunks = (pos_of_token[t] + ct) / ct;     // ceil((pos + 1) / ct)
-    const size_t base = ((size_t)t * sh.n_q + h) * sh.max_chunks;
+    const float *ml = part_ml + (size_t)pair * sh.max_chunks * 2;
+    const float *po = part_o + (size_t)pair * sh.max_chunks * d;
     float M = -INFINITY;
-    for (int c = 0; c < n_chunks; ++c) M = fmaxf(M, part_ml[(base + c) * 2]);
+    for (int c = sub; c < n_chunks; c += 32) M = fmaxf(M, ml[c * 2]);
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 32));
+    // Lane `sub` weighs chunk cb + sub; the weights travel by shuffle so that the value loads
+    // of a block of chunks are independent of one another and can all be in flight together.
     float L = 0.f;
-    const int i = threadIdx.x;
-    float acc = 0.f;
-    for (int c = 0; c < n_chunks; ++c) {
-        const float dm = part_ml[(base + c) * 2] - M;
-        const float w = BASE2 ? exp2f(dm) : expf(dm);
-        L += w * part_ml[(base + c) * 2 + 1];
-        if (i < d) acc += w * part_o[(base + c) * d + i];
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};   // head_dim <= 256: two float4 per lane
+    for (int cb = 0; cb < n_chunks; cb += 32) {
+        const int c = cb + sub;
+        float wgt = 0.f, wl = 0.f;
+        if (c < n_chunks) {
+            const float dm = ml[c * 2] - M;
+            wgt = BASE2 ? exp2f(dm) : expf(dm);
+            wl = wgt * ml[c * 2 + 1];
+        }
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 32);
+        L += wl;
+        const int nb = min(32, n_chunks - cb);
+        for (int j0 = 0; j0 < nb; j0 += 4) {
+            f32x4 v[4][2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int i = sub * 4 + q * 128;
+                    v[j][q] = (j0 + j < nb && i < d) ? *reinterpret_cast<const f32x4 *>(po + (size_t)(cb + j0 + j) * d + i)
+                                                      : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float wj = __shfl(wgt, j0 + j, 32);      // 0 beyond the last chunk
+#pragma unroll
+                for (int q = 0; q < 2; ++q) acc[q] += v[j][q] * wj;
+            }
+        }
     }
-    if (i < d) out[((size_t)t * sh.n_q + h) * d + i] = from_f32<T>(acc / L);
+    const float inv = 1.0f / L;
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int i = sub * 4 + q * 128;
+        if (i < d) {
+            T *o = out + (size_t)t * ld_out + (pair - t * sh.n_q) * d + i;
+#pragma unroll
+            for (int r = 0; r < 4; ++r) o[r] = from_f32<T>(acc[q][r] * inv);
+        }
+    }
 }
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
-                                    const int32_t *pos_of_token, void *out, const AttnShape &sh, int rows,
+                                    const int32_t *pos_of_token, void *out, int ld_out, const AttnShape &sh, int rows,
                                     hipStream_t s) {
-    const dim3 grid(rows * sh.n_q), block(sh.head_dim <= 64 ? 64 : (sh.head_dim <= 128 ? 128 : 256));
+    const int n_pairs = rows * sh.n_q;
+    const dim3 grid((n_pairs + 7) / 8), block(256);
     if (dtype == 0) {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, sh);
-        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, sh);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, ld_out, sh, n_pairs);
+        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, ld_out, sh, n_pairs);
     } else {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, sh);
-        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, sh);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
+        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
     }
     return hipGetLastError();
 }
 
 hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *seq_of_token,
                                     const int32_t *pos_of_token, const int32_t *block_table, const void *k_cache,
-                                    const void *v_cache, void *out, float *part_o, float *part_ml,
-                                    const AttnShape &sh, int rows, hipStream_t s) {
+                                    const void *v_cache, void *out, int ld_out, float *part_o, float *part_ml,
+                                    const AttnShape &sh, int rows, hipStream_t s, hipEvent_t mid) {
     if (rows <= 0) return hipSuccess;
     const dim3 grid((unsigned)((size_t)rows * sh.n_q * sh.max_chunks));
     if (dtype == 0)
@@ -126,8 +167,9 @@ hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *s
         hipLaunchKernelGGL(attn_generic_kernel<bf16_t>, grid, dim3(64), 0, s, (const bf16_t *)qkv, seq_of_token,
                            pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, out, sh, rows, s);
+    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, out, ld_out, sh, rows, s);
 }
 
 }  // namespace dyn

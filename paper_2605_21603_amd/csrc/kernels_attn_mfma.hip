@@ -21,37 +21,83 @@
 namespace dyn {
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
-                                    const int32_t *pos_of_token, void *out, const AttnShape &sh, int rows,
+                                    const int32_t *pos_of_token, void *out, int ld_out, const AttnShape &sh, int rows,
                                     hipStream_t s);
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
+constexpr int kPersistentGroups = 256;   // one 8-wave workgroup for each of the 256 CUs
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
+// Work list: one entry per (token, chunk) that really exists, built on the device from the
+// positions (contexts differ by 8x inside a batch, so a dense token x max_chunks grid would
+// be mostly empty workgroups).  plan[0] = number of entries, entry i at plan[2 + 2 i].
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ pos_of_token, int rows, int ct,
+                                                        int32_t *__restrict__ plan) {
+    __shared__ int scan[256];
+    __shared__ int base;
+    if (threadIdx.x == 0) base = 0;
+    __syncthreads();
+    for (int t0 = 0; t0 < rows; t0 += 256) {
+        const int t = t0 + threadIdx.x;
+        const int nc = t < rows ? (pos_of_token[t] + ct) / ct : 0;
+        scan[threadIdx.x] = nc;
+        __syncthreads();
+        for (int off = 1; off < 256; off <<= 1) {           // inclusive Hillis-Steele scan
+            const int v = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
+            __syncthreads();
+            scan[threadIdx.x] += v;
+            __syncthreads();
+        }
+        const int start = base + scan[threadIdx.x] - nc;
+        for (int c = 0; c < nc; ++c) {
+            plan[2 + 2 * (start + c)] = t;
+            plan[3 + 2 * (start + c)] = c;
+        }
+        __syncthreads();
+        if (threadIdx.x == 255) base += scan[255];
+        __syncthreads();
+    }
+    if (threadIdx.x == 0) plan[0] = base;
+}
+
+// Persistent workgroups of 8 waves, one per CU.  Workgroup b owns the (entry, kv head) pairs
+// b, b + gridDim.x, ...; its waves take them from an LDS counter as they become free, which
+// evens out the ragged last chunks.  Which wave computes a pair has no influence on its
+// result.
+__global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
                                                            const int32_t *__restrict__ seq_of_token,
                                                            const int32_t *__restrict__ pos_of_token,
                                                            const int32_t *__restrict__ block_table,
                                                            const bf16_t *__restrict__ k_cache,
                                                            const bf16_t *__restrict__ v_cache,
                                                            float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                           AttnShape sh, int n_items) {
+                                                           AttnShape sh, const int32_t *__restrict__ plan) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-    const int item = blockIdx.x * 4 + wave;
-    if (item >= n_items) return;
-    const int c = item % sh.max_chunks;
-    const int g = (item / sh.max_chunks) % sh.n_kv;
-    const int t = item / (sh.max_chunks * sh.n_kv);
-    const int n_keys = pos_of_token[t] + 1;
+    const int n_items = plan[0] * sh.n_kv;
     const int ct = sh.chunk_pages * PS;
+    const int G = sh.n_q / sh.n_kv;
+    const int lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+    const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
+    (void)wave;
+    __shared__ int next_slot;
+    if (threadIdx.x == 0) next_slot = 0;
+    __syncthreads();
+    auto claim = [&]() {
+        int v = 0;
+        if (lane == 0) v = atomicAdd(&next_slot, 1);
+        return blockIdx.x + __builtin_amdgcn_readfirstlane(v) * gridDim.x;
+    };
+    int item = claim();
+  while (item < n_items) {
+    const int g = item % sh.n_kv;
+    const int t = plan[2 + 2 * (item / sh.n_kv)], c = plan[3 + 2 * (item / sh.n_kv)];
+    const int n_keys = pos_of_token[t] + 1;
     const int j0 = c * ct;
-    if (j0 >= n_keys) return;
     const int seq_pages = (n_keys + PS - 1) / PS;                 // pages this token may read
     const int lp0 = c * sh.chunk_pages;                           // first logical page of the chunk
     const int n_pg = min(sh.chunk_pages, seq_pages - lp0);
     const int n_tiles = (n_pg + TILE_PAGES - 1) / TILE_PAGES;
-    const int G = sh.n_q / sh.n_kv;
-    const int lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
     const int32_t *bt = block_table + (size_t)seq_of_token[t] * sh.max_pages_per_seq;
 
     // B operands of the score product: q of head g*G + lr (zero for lr >= G)
@@ -65,7 +111,6 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
             qb[ks] = __builtin_bit_cast(bf16x8, v);
         }
     }
-    const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
 
     u32x4 kreg[2][TILE_PAGES][4];
     u32x2 vreg[2][TILE_PAGES][8];
@@ -131,14 +176,29 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
         }                                                                                                         \
     }
 
+    // Two register buffers; the steady-state loop has no conditional loads, so the compiler
+    // counts the loads still in flight exactly and a tile is multiplied while the next one
+    // is on its way.
     DYN_ATTN_LOAD(0, 0)
-    for (int tl = 0; tl < n_tiles; tl += 2) {
-        if (tl + 1 < n_tiles) DYN_ATTN_LOAD(1, tl + 1)
+    int tl = 0;
+    for (; tl + 2 < n_tiles; tl += 2) {
+        // scheduling barriers: keep each prefetch ahead of the multiply it overlaps
+        DYN_ATTN_LOAD(1, tl + 1)
+        __builtin_amdgcn_sched_barrier(0);
         DYN_ATTN_COMPUTE(0, tl)
-        if (tl + 1 < n_tiles) {
-            if (tl + 2 < n_tiles) DYN_ATTN_LOAD(0, tl + 2)
-            DYN_ATTN_COMPUTE(1, tl + 1)
-        }
+        __builtin_amdgcn_sched_barrier(0);
+        DYN_ATTN_LOAD(0, tl + 2)
+        __builtin_amdgcn_sched_barrier(0);
+        DYN_ATTN_COMPUTE(1, tl + 1)
+        __builtin_amdgcn_sched_barrier(0);
+    }
+    if (tl + 2 == n_tiles) {
+        DYN_ATTN_LOAD(1, tl + 1)
+        __builtin_amdgcn_sched_barrier(0);
+        DYN_ATTN_COMPUTE(0, tl)
+        DYN_ATTN_COMPUTE(1, tl + 1)
+    } else {
+        DYN_ATTN_COMPUTE(0, tl)
     }
 #undef DYN_ATTN_LOAD
 #undef DYN_ATTN_COMPUTE
@@ -155,31 +215,39 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
             part_ml[pidx * 2 + 1] = l_run;
         }
     }
+    item = claim();
+  }   // item loop
 }
 
 hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *seq_of_token,
                                     const int32_t *pos_of_token, const int32_t *block_table, const void *k_cache,
-                                    const void *v_cache, void *out, float *part_o, float *part_ml,
-                                    const AttnShape &sh, int rows, hipStream_t s);
+                                    const void *v_cache, void *out, int ld_out, float *part_o, float *part_ml,
+                                    const AttnShape &sh, int rows, hipStream_t s, hipEvent_t mid);
 
 bool attention_mfma_supported(int dtype, const AttnShape &sh) {
     return dtype == 1 && sh.head_dim == HD && sh.page_size == PS && sh.n_q % sh.n_kv == 0 && sh.n_q / sh.n_kv <= 16;
 }
 
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
-                            const int32_t *block_table, const void *k_cache, const void *v_cache, void *out,
-                            float *part_o, float *part_ml, const AttnShape &sh, int rows, hipStream_t s) {
+                            const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
+                            float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
+                            hipStream_t s, hipEvent_t mid) {
     if (rows <= 0) return hipSuccess;
     if (!attention_mfma_supported(dtype, sh))
-        return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out,
-                                        part_o, part_ml, sh, rows, s);
-    const int n_items = rows * sh.n_kv * sh.max_chunks;
-    hipLaunchKernelGGL(attn_mfma_kernel, dim3((n_items + 3) / 4), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
-                       pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
-                       n_items);
+        return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
+                                        part_o, part_ml, sh, rows, s, mid);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, pos_of_token, rows, sh.chunk_pages * PS, plan);
     hipError_t e = hipGetLastError();
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, out, sh, rows, s);
+    const long max_items = (long)rows * sh.n_kv * sh.max_chunks;
+    const int grid = (int)((max_items + 7) / 8 < kPersistentGroups ? (max_items + 7) / 8 : kPersistentGroups);
+    hipLaunchKernelGGL(attn_mfma_kernel, dim3(grid), dim3(512), 0, s, (const bf16_t *)qkv, seq_of_token,
+                       pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
+                       plan);
+    e = hipGetLastError();
+    if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
+    if (e != hipSuccess) return e;
+    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, out, ld_out, sh, rows, s);
 }
 
 }  // namespace dyn

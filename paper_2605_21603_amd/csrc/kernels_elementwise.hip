@@ -11,13 +11,13 @@ namespace dyn {
 // One 256-thread workgroup per row.  out = x * g / sqrt(mean(x^2) + eps).
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ x, const T *__restrict__ g,
-                                                      T *__restrict__ out, int H, float eps) {
+                                                      T *__restrict__ out, int ld_out, int H, float eps) {
     constexpr int V = 16 / sizeof(T);
     typedef T vec_t __attribute__((ext_vector_type(V)));
     const size_t row = blockIdx.x;
     const vec_t *xr = reinterpret_cast<const vec_t *>(x + row * H);
     const vec_t *gr = reinterpret_cast<const vec_t *>(g);
-    vec_t *orow = reinterpret_cast<vec_t *>(out + row * H);
+    vec_t *orow = reinterpret_cast<vec_t *>(out + row * ld_out);
     const int nv = H / V;
     float ss = 0.f;
     for (int i = threadIdx.x; i < nv; i += 256) {
@@ -39,54 +39,60 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const T *__restrict__ x, c
     }
 }
 
-hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int rows, int H, float eps,
+hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int ld_out, int rows, int H, float eps,
                           hipStream_t s) {
     if (rows <= 0) return hipSuccess;
     if (dtype == 0)
         hipLaunchKernelGGL(rmsnorm_kernel<float>, dim3(rows), dim3(256), 0, s, (const float *)x, (const float *)g,
-                           (float *)out, H, eps);
+                           (float *)out, ld_out, H, eps);
     else
         hipLaunchKernelGGL(rmsnorm_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (const bf16_t *)x,
-                           (const bf16_t *)g, (bf16_t *)out, H, eps);
+                           (const bf16_t *)g, (bf16_t *)out, ld_out, H, eps);
     return hipGetLastError();
 }
 
 // ------------------------------------------------------------------ rotary + cache append
-// One 128-thread workgroup per token.  Thread (i, hg): pair index i < d/2, head group hg.
-// The angle pos * theta_i and its sine/cosine are formed in fp64 so that the rotation is
-// exact to fp32 rounding at any position.
+// One thread per (token, head, pair index i < d/2); heads are the q heads, then the k heads,
+// then the v heads (a v "pair" is just two elements to copy).  The angle pos * theta_i is
+// formed and reduced to [-pi, pi] in fp64, then sine and cosine are taken in fp32, so the
+// rotation is good to fp32 rounding at any position.
 template <typename T>
-__global__ __launch_bounds__(128) void rope_kv_kernel(T *__restrict__ qkv, const int32_t *__restrict__ seq_of_token,
+__global__ __launch_bounds__(256) void rope_kv_kernel(T *__restrict__ qkv, const int32_t *__restrict__ seq_of_token,
                                                       const int32_t *__restrict__ pos_of_token,
                                                       const int32_t *__restrict__ block_table,
                                                       T *__restrict__ k_cache, T *__restrict__ v_cache,
                                                       RopeTable tab, AttnShape sh) {
     const int t = blockIdx.x;
     const int d = sh.head_dim, half = d >> 1;
-    const int i = threadIdx.x % half, hg = threadIdx.x / half, n_hg = 128 / half;
+    const int item = blockIdx.y * 256 + threadIdx.x;
+    const int hh = item / half, i = item % half;
+    if (hh >= sh.n_q + 2 * sh.n_kv) return;
     const int pos = pos_of_token[t];
-    const int page = block_table[(size_t)seq_of_token[t] * sh.max_pages_per_seq + pos / sh.page_size];
-    const int slot = pos % sh.page_size;
-    double sn, cs;
-    sincos((double)pos * tab.inv_freq[i], &sn, &cs);
-    const float c = (float)cs, s = (float)sn;
-    T *row = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * d);
-    for (int h = hg; h < sh.n_q; h += n_hg) {            // q heads, in place
-        T *z = row + h * d;
-        const float a = to_f32<T>(z[i]), b = to_f32<T>(z[i + half]);
-        z[i] = from_f32<T>(a * c - b * s);
-        z[i + half] = from_f32<T>(b * c + a * s);
+    T *z = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * d) + hh * d;
+    const float a = to_f32<T>(z[i]), b = to_f32<T>(z[i + half]);
+    if (hh >= sh.n_q + sh.n_kv) {                        // v head -> V page [kvh][d][slot]
+        const int g = hh - sh.n_q - sh.n_kv;
+        const int page = block_table[(size_t)seq_of_token[t] * sh.max_pages_per_seq + pos / sh.page_size];
+        T *vp = v_cache + ((size_t)page * sh.n_kv + g) * d * sh.page_size + pos % sh.page_size;
+        vp[(size_t)i * sh.page_size] = z[i];
+        vp[(size_t)(i + half) * sh.page_size] = z[i + half];
+        return;
     }
-    for (int g = hg; g < sh.n_kv; g += n_hg) {           // k heads -> K page [kvh][slot][d]
-        const T *z = row + (sh.n_q + g) * d;
-        const float a = to_f32<T>(z[i]), b = to_f32<T>(z[i + half]);
-        T *kp = k_cache + (((size_t)page * sh.n_kv + g) * sh.page_size + slot) * d;
-        kp[i] = from_f32<T>(a * c - b * s);
-        kp[i + half] = from_f32<T>(b * c + a * s);
-        const T *v = row + (sh.n_q + sh.n_kv + g) * d;   // v heads -> V page [kvh][d][slot]
-        T *vp = v_cache + ((size_t)page * sh.n_kv + g) * d * sh.page_size + slot;
-        vp[(size_t)i * sh.page_size] = v[i];
-        vp[(size_t)(i + half) * sh.page_size] = v[i + half];
+    const double ang = (double)pos * tab.inv_freq[i];
+    const double turns = rint(ang * 0.15915494309189535);              // 1 / (2 pi)
+    const float red = (float)fma(-turns, 6.283185307179586, ang);
+    float s, c;
+    sincosf(red, &s, &c);
+    const T lo = from_f32<T>(a * c - b * s), hi = from_f32<T>(b * c + a * s);
+    if (hh < sh.n_q) {                                   // q head, in place
+        z[i] = lo;
+        z[i + half] = hi;
+    } else {                                             // k head -> K page [kvh][slot][d]
+        const int g = hh - sh.n_q;
+        const int page = block_table[(size_t)seq_of_token[t] * sh.max_pages_per_seq + pos / sh.page_size];
+        T *kp = k_cache + (((size_t)page * sh.n_kv + g) * sh.page_size + pos % sh.page_size) * d;
+        kp[i] = lo;
+        kp[i + half] = hi;
     }
 }
 
@@ -94,11 +100,13 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
                           const int32_t *block_table, void *k_cache, void *v_cache, const RopeTable &tab,
                           const AttnShape &sh, int rows, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    const int items = (sh.n_q + 2 * sh.n_kv) * (sh.head_dim / 2);
+    const dim3 grid(rows, (items + 255) / 256);
     if (dtype == 0)
-        hipLaunchKernelGGL(rope_kv_kernel<float>, dim3(rows), dim3(128), 0, s, (float *)qkv, seq_of_token,
+        hipLaunchKernelGGL(rope_kv_kernel<float>, grid, dim3(256), 0, s, (float *)qkv, seq_of_token,
                            pos_of_token, block_table, (float *)k_cache, (float *)v_cache, tab, sh);
     else
-        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, dim3(rows), dim3(128), 0, s, (bf16_t *)qkv, seq_of_token,
+        hipLaunchKernelGGL(rope_kv_kernel<bf16_t>, grid, dim3(256), 0, s, (bf16_t *)qkv, seq_of_token,
                            pos_of_token, block_table, (bf16_t *)k_cache, (bf16_t *)v_cache, tab, sh);
     return hipGetLastError();
 }
@@ -106,8 +114,8 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
 // ------------------------------------------------------------------ SiLU gate
 // out[t, i] = g / (1 + exp(-g)) * u with g = gu[t, i], u = gu[t, I + i].
 template <typename T>
-__global__ __launch_bounds__(256) void silu_mul_kernel(const T *__restrict__ gu, T *__restrict__ out, int I,
-                                                       size_t n_vec) {
+__global__ __launch_bounds__(256) void silu_mul_kernel(const T *__restrict__ gu, T *__restrict__ out, int ld_out,
+                                                       int I, size_t n_vec) {
     constexpr int V = 16 / sizeof(T);
     typedef T vec_t __attribute__((ext_vector_type(V)));
     const int vec_per_row = I / V;
@@ -121,21 +129,21 @@ __global__ __launch_bounds__(256) void silu_mul_kernel(const T *__restrict__ gu,
             const float z = to_f32<T>(g[e]);
             o[e] = from_f32<T>(z / (1.0f + expf(-z)) * to_f32<T>(u[e]));
         }
-        *reinterpret_cast<vec_t *>(out + t * I + c * V) = o;
+        *reinterpret_cast<vec_t *>(out + t * ld_out + c * V) = o;
     }
 }
 
-hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int rows, int I, hipStream_t s) {
+hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
     const int V = dtype == 0 ? 4 : 8;
     const size_t n_vec = (size_t)rows * (I / V);
     const int blocks = (int)((n_vec + 255) / 256 < 4096 ? (n_vec + 255) / 256 : 4096);
     if (dtype == 0)
-        hipLaunchKernelGGL(silu_mul_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)gu, (float *)out, I,
-                           n_vec);
+        hipLaunchKernelGGL(silu_mul_kernel<float>, dim3(blocks), dim3(256), 0, s, (const float *)gu, (float *)out, ld_out,
+                           I, n_vec);
     else
         hipLaunchKernelGGL(silu_mul_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, (const bf16_t *)gu,
-                           (bf16_t *)out, I, n_vec);
+                           (bf16_t *)out, ld_out, I, n_vec);
     return hipGetLastError();
 }
 

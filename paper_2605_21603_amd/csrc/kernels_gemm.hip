@@ -4,10 +4,12 @@
 // shaped for.
 //
 // Summation order of one output element is a function of (N, K) only: K is cut into
-// S = gemm_split_k(N, K) equal chunks, each chunk is accumulated in ascending k by the
-// same 16x16x32 MFMA into an fp32 accumulator starting from zero, and the chunk sums are
-// added in ascending chunk order, then the residual.  Rows never mix, so a row computed in
-// a 64-row micro-batch has the same bits as in the merged batch.
+// S = gemm_split_k(N, K) equal planes, each plane is accumulated in ascending k by the same
+// 16x16x32 MFMA into an fp32 accumulator starting from zero, and the plane sums are added
+// in ascending plane order, then the residual.  Rows never mix, so a row computed in a
+// 64-row micro-batch has the same bits as in the merged batch.
+#include <cstdlib>
+
 #include "common.h"
 #include "kernels.h"
 
@@ -16,7 +18,7 @@ namespace dyn {
 // ------------------------------------------------------------------ fp32 (plain FMA) path
 // 64x64 output tile per 256-thread workgroup, 4x4 outputs per thread, K staged 16 at a time
 // through LDS.  Each output is one fp32 FMA chain in ascending k.
-__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ X, const float *__restrict__ W,
+__global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ X, int ldx, const float *__restrict__ W,
                                                        const float *__restrict__ R, float *__restrict__ Y, int M,
                                                        int N, int K) {
     __shared__ float xs[16][64 + 4];
@@ -27,7 +29,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
     for (int k0 = 0; k0 < K; k0 += 16) {
         for (int e = threadIdx.x; e < 64 * 16; e += 256) {
             const int r = e / 16, kk = e % 16;
-            xs[kk][r] = (m0 + r < M && k0 + kk < K) ? X[(size_t)(m0 + r) * K + k0 + kk] : 0.f;
+            xs[kk][r] = (m0 + r < M && k0 + kk < K) ? X[(size_t)(m0 + r) * ldx + k0 + kk] : 0.f;
             ws[kk][r] = (n0 + r < N && k0 + kk < K) ? W[(size_t)(n0 + r) * K + k0 + kk] : 0.f;
         }
         __syncthreads();
@@ -53,139 +55,130 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 }
 
 // ------------------------------------------------------------------ bf16 MFMA path
-// Workgroup = 4 waves, tile = 64 rows of X by 128 rows of W, one K chunk.  Wave w owns 32
-// rows of W as two MFMA "A" operands which it loads straight from global memory in operand
-// layout (lane l: row l%16, 8 consecutive k at 8*(l/16): 64 contiguous bytes per row and
-// instruction), PF stages ahead.  The 64x64 X tile of a stage goes through LDS (rows padded
-// to 144 bytes so the four 16-lane groups of a ds_read_b128 hit disjoint banks) and feeds
-// the "B" operands of all four waves.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
-constexpr int GN = 128, GM = 64, GK = 64, PF = 3;
-constexpr int XROW = GK * 2 + 16;              // bytes per X row in LDS
-constexpr int XBUF = GM * XROW;                // bytes per stage buffer
+// Workgroup = 4 waves on a 128 (W rows) x MT (X rows, 64 or 128) output tile and one K
+// plane.  What bounds this kernel below a few hundred rows is not the matrix cores and not
+// even HBM alone but the L2 -> CU path: every byte of W must cross it once and the X tile
+// crosses it once per W tile, so both operands are fetched exactly once per workgroup with
+// fully coalesced 128-byte row segments (8 lanes per row), parked in registers for three
+// stages (a stage is 64 k), and handed to the waves through LDS.  LDS rows are padded to
+// 144 bytes so the 16-lane groups of a ds_read_b128 in MFMA operand layout (lane l: row
+// l%16, 8 consecutive k at 8*(l/16)) touch disjoint banks.  Waves sit 2 x 2 on the tile:
+// 64 W rows x MT/2 X rows each.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
+constexpr int BN = 128, BK = 64, ROWB = BK * 2 + 16, RING = 4;
 
-__global__ __launch_bounds__(256, 2) void gemm_bf16_kernel(const bf16_t *__restrict__ X, const bf16_t *__restrict__ W,
-                                                           const bf16_t *__restrict__ R, bf16_t *__restrict__ Y,
-                                                           float *__restrict__ P, size_t plane_stride, int M, int N,
-                                                           int K, int S) {
-    __shared__ __attribute__((aligned(16))) unsigned char xl[2 * XBUF];
-    const int m_tiles = (M + GM - 1) / GM;
+template <int MT>
+__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, int ldx,
+                                                        const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
+                                                        bf16_t *__restrict__ Y, float *__restrict__ P,
+                                                        size_t plane_stride, int M, int N, int K, int S) {
+    constexpr int XP = MT / 32;                     // 16-byte X pieces per thread and stage
+    constexpr int NB = MT / 32;                     // B tiles (16 X rows) per wave
+    __shared__ __attribute__((aligned(16))) unsigned char lw[2][BN * ROWB];
+    __shared__ __attribute__((aligned(16))) unsigned char lx[2][MT * ROWB];
+    const int m_tiles = (M + MT - 1) / MT;
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
-    // m tiles of one (n tile, chunk)) get ids 8 apart: same XCD, same L2, adjacent in time.
+    // m tiles of one (n tile, plane)) get ids 8 apart: same XCD, same L2, adjacent in time.
     const int u = blockIdx.x % 8, v = blockIdx.x / 8;
     const int m_tile = v % m_tiles, ns = (v / m_tiles) * 8 + u;
-    if (ns >= (N / GN) * S) return;
+    if (ns >= (N / BN) * S) return;
     const int n_tile = ns / S, sp = ns % S;
-    const int Kc = K / S, kbase = sp * Kc, n_stage = Kc / GK;
-    const int m0 = m_tile * GM;
+    const int Kp = K / S, kbase = sp * Kp, n_stage = Kp / BK;
+    const int n0 = n_tile * BN, m0 = m_tile * MT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-    const int lr = lane & 15, lq = lane >> 4;
+    const int lr = lane & 15, lq = lane >> 4, wn = wave & 1, wm = wave >> 1;
 
-    const bf16_t *wp[2];
+    const int prow = tid >> 3, pcol = tid & 7;      // piece p = tid + 256 u: row prow + 32 u, 16-byte column pcol
+    const bf16_t *wg[4], *xg[XP];
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
-        wp[a] = W + (size_t)(n_tile * GN + wave * 32 + a * 16 + lr) * K + kbase + 8 * lq;
-    // X staging: two 16-byte pieces per thread and stage
-    const bf16_t *xp[2];
-    int xoff[2];
+    for (int q = 0; q < 4; ++q) wg[q] = W + (size_t)(n0 + prow + 32 * q) * K + kbase + pcol * 8;
 #pragma unroll
-    for (int p = 0; p < 2; ++p) {
-        const int piece = tid + 256 * p, row = piece >> 3, col = piece & 7;
-        const int m = min(m0 + row, M - 1);
-        xp[p] = X + (size_t)m * K + kbase + col * 8;
-        xoff[p] = row * XROW + col * 16;
+    for (int q = 0; q < XP; ++q) xg[q] = X + (size_t)min(m0 + prow + 32 * q, M - 1) * ldx + kbase + pcol * 8;
+    const int loff = prow * ROWB + pcol * 16;
+
+    u32x4 rw[RING][4], rx[RING][XP];
+    f32x4 acc[4][NB];
+#pragma unroll
+    for (int a = 0; a < 4; ++a)
+#pragma unroll
+        for (int b = 0; b < NB; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+
+#define DYN_GEMM_FETCH(SLOT, ST)                                                                         \
+    {                                                                                                    \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                    \
+            rw[SLOT][q] = *reinterpret_cast<const u32x4 *>(wg[q] + (size_t)(ST) * BK);                   \
+        _Pragma("unroll") for (int q = 0; q < XP; ++q)                                                   \
+            rx[SLOT][q] = *reinterpret_cast<const u32x4 *>(xg[q] + (size_t)(ST) * BK);                   \
     }
-
-    u32x4 wr[PF + 1][2][2];
-    u32x4 xr[2][2];
-    f32x4 acc[2][4];
-#pragma unroll
-    for (int a = 0; a < 2; ++a)
-#pragma unroll
-        for (int b = 0; b < 4; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-
-#pragma unroll
-    for (int p = 0; p < PF; ++p)
-        if (p < n_stage) {
-#pragma unroll
-            for (int ks = 0; ks < 2; ++ks)
-#pragma unroll
-                for (int a = 0; a < 2; ++a)
-                    wr[p][ks][a] = *reinterpret_cast<const u32x4 *>(wp[a] + p * GK + ks * 32);
-        }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) xr[0][p] = *reinterpret_cast<const u32x4 *>(xp[p]);
-    if (n_stage > 1) {
-#pragma unroll
-        for (int p = 0; p < 2; ++p) xr[1][p] = *reinterpret_cast<const u32x4 *>(xp[p] + GK);
+#define DYN_GEMM_PARK(SLOT, BUF)                                                                         \
+    {                                                                                                    \
+        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                    \
+            *reinterpret_cast<u32x4 *>(&lw[BUF][loff + 32 * q * ROWB]) = rw[SLOT][q];                    \
+        _Pragma("unroll") for (int q = 0; q < XP; ++q)                                                   \
+            *reinterpret_cast<u32x4 *>(&lx[BUF][loff + 32 * q * ROWB]) = rx[SLOT][q];                    \
     }
-#pragma unroll
-    for (int p = 0; p < 2; ++p) *reinterpret_cast<u32x4 *>(xl + xoff[p]) = xr[0][p];
+#define DYN_GEMM_MMA(BUF)                                                                                \
+    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                   \
+        bf16x8 av[4], bv[NB];                                                                            \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a) av[a] = *reinterpret_cast<const bf16x8 *>(         \
+            &lw[BUF][(wn * 64 + a * 16 + lr) * ROWB + ks * 64 + lq * 16]);                               \
+        _Pragma("unroll") for (int b = 0; b < NB; ++b) bv[b] = *reinterpret_cast<const bf16x8 *>(        \
+            &lx[BUF][(wm * (MT / 2) + b * 16 + lr) * ROWB + ks * 64 + lq * 16]);                         \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a) _Pragma("unroll") for (int b = 0; b < NB; ++b)     \
+            acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);       \
+    }
+    // Stage i: fetch stage i+3 into the ring, multiply stage i out of LDS buffer i%2, park
+    // stage i+1 in the other buffer, barrier.  J = i mod 4 is a literal so that every ring
+    // index is static; n_stage is a multiple of 4 (gemm_supported / gemm_split_k), and the
+    // steady-state loop has no conditional loads so that outstanding loads are counted exactly.
+#define DYN_GEMM_STAGE(J, FETCH, PARK)                                                                   \
+    {                                                                                                    \
+        if (FETCH) DYN_GEMM_FETCH(((J) + 3) % RING, st0 + (J) + 3)                                       \
+        DYN_GEMM_MMA((J) % 2)                                                                            \
+        if (PARK) DYN_GEMM_PARK(((J) + 1) % RING, ((J) + 1) % 2)                                         \
+        __syncthreads();                                                                                 \
+    }
+    static_assert(RING == 4, "stages are written out four at a time");
+    DYN_GEMM_FETCH(0, 0)
+    DYN_GEMM_FETCH(1, 1)
+    DYN_GEMM_FETCH(2, 2)
+    DYN_GEMM_PARK(0, 0)
     __syncthreads();
-
-    // One stage: prefetch W for stage st+PF and X for stage st+2, multiply stage st, hand the
-    // X tile of stage st+1 to LDS.  J = st mod (PF+1) is a literal so that every register
-    // array index is a compile-time constant.
-#define DYN_GEMM_STAGE(J)                                                                                         \
-    {                                                                                                             \
-        const int st = st0 + (J);                                                                                 \
-        if (st < n_stage) {                                                                                       \
-            if (st + PF < n_stage) {                                                                              \
-                _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) _Pragma("unroll") for (int a = 0; a < 2; ++a)    \
-                    wr[((J) + PF) % (PF + 1)][ks][a] =                                                            \
-                        *reinterpret_cast<const u32x4 *>(wp[a] + (size_t)(st + PF) * GK + ks * 32);               \
-            }                                                                                                     \
-            if (st + 2 < n_stage) {                                                                               \
-                _Pragma("unroll") for (int p = 0; p < 2; ++p)                                                     \
-                    xr[(J) % 2][p] = *reinterpret_cast<const u32x4 *>(xp[p] + (size_t)(st + 2) * GK);             \
-            }                                                                                                     \
-            const unsigned char *xb = xl + ((J) % 2) * XBUF;                                                      \
-            _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                    \
-                const bf16x8 a0 = __builtin_bit_cast(bf16x8, wr[(J)][ks][0]);                                     \
-                const bf16x8 a1 = __builtin_bit_cast(bf16x8, wr[(J)][ks][1]);                                     \
-                _Pragma("unroll") for (int b = 0; b < 4; ++b) {                                                   \
-                    const bf16x8 bv =                                                                             \
-                        *reinterpret_cast<const bf16x8 *>(xb + (b * 16 + lr) * XROW + ks * 64 + lq * 16);         \
-                    acc[0][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a0, bv, acc[0][b], 0, 0, 0);              \
-                    acc[1][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(a1, bv, acc[1][b], 0, 0, 0);              \
-                }                                                                                                 \
-            }                                                                                                     \
-            if (st + 1 < n_stage) {                                                                               \
-                unsigned char *xn = xl + (((J) + 1) % 2) * XBUF;                                                  \
-                _Pragma("unroll") for (int p = 0; p < 2; ++p)                                                     \
-                    *reinterpret_cast<u32x4 *>(xn + xoff[p]) = xr[((J) + 1) % 2][p];                              \
-            }                                                                                                     \
-            __syncthreads();                                                                                      \
-        }                                                                                                         \
+    int st0 = 0;
+    for (; st0 < n_stage - RING; st0 += RING) {
+        DYN_GEMM_STAGE(0, true, true)
+        DYN_GEMM_STAGE(1, true, true)
+        DYN_GEMM_STAGE(2, true, true)
+        DYN_GEMM_STAGE(3, true, true)
     }
-    static_assert(PF == 3, "the stage macro is expanded PF + 1 = 4 times below");
-    for (int st0 = 0; st0 < n_stage; st0 += PF + 1) {
-        DYN_GEMM_STAGE(0)
-        DYN_GEMM_STAGE(1)
-        DYN_GEMM_STAGE(2)
-        DYN_GEMM_STAGE(3)
-    }
+    DYN_GEMM_STAGE(0, true, true)
+    DYN_GEMM_STAGE(1, false, true)
+    DYN_GEMM_STAGE(2, false, true)
+    DYN_GEMM_STAGE(3, false, false)
 #undef DYN_GEMM_STAGE
+#undef DYN_GEMM_MMA
+#undef DYN_GEMM_PARK
+#undef DYN_GEMM_FETCH
 
 #pragma unroll
-    for (int a = 0; a < 2; ++a)
+    for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < 4; ++b) {
-            const int m = m0 + b * 16 + lr;
-            const int n = n_tile * GN + wave * 32 + a * 16 + 4 * lq;
+        for (int b = 0; b < NB; ++b) {
+            const int m = m0 + wm * (MT / 2) + b * 16 + lr;
+            const int n = n0 + wn * 64 + a * 16 + 4 * lq;
             if (m >= M) continue;
+            f32x4 o = acc[a][b];
             if (S == 1) {
-                f32x4 o = acc[a][b];
                 if (R) {
-                    const uint2 rv = *reinterpret_cast<const uint2 *>(R + (size_t)m * N + n);
-                    o[0] += bf2f(rv.x & 0xffff); o[1] += bf2f(rv.x >> 16);
-                    o[2] += bf2f(rv.y & 0xffff); o[3] += bf2f(rv.y >> 16);
+                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(R + (size_t)m * N + n);
+                    o[0] += bf2f(rv[0] & 0xffff); o[1] += bf2f(rv[0] >> 16);
+                    o[2] += bf2f(rv[1] & 0xffff); o[3] += bf2f(rv[1] >> 16);
                 }
-                uint2 ov;
-                ov.x = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
-                ov.y = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
-                *reinterpret_cast<uint2 *>(Y + (size_t)m * N + n) = ov;
+                u32x2 ov;
+                ov[0] = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
+                ov[1] = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
+                *reinterpret_cast<u32x2 *>(Y + (size_t)m * N + n) = ov;
             } else {
-                *reinterpret_cast<f32x4 *>(P + (size_t)sp * plane_stride + (size_t)m * N + n) = acc[a][b];
+                *reinterpret_cast<f32x4 *>(P + (size_t)sp * plane_stride + (size_t)m * N + n) = o;
             }
         }
 }
@@ -214,31 +207,44 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float *__restric
 
 bool gemm_supported(int dtype, int N, int K) {
     if (dtype == 0) return N > 0 && K > 0;
-    return N > 0 && K > 0 && N % GN == 0 && K % GK == 0;
+    return N > 0 && K > 0 && N % BN == 0 && K % (BK * RING) == 0;
 }
 
 int gemm_split_k(int dtype, int N, int K) {
     if (dtype == 0) return 1;
+    // enough workgroups to occupy 256 CUs twice over, chunks of at least 8 k-steps
+    static int forced = -1;
+    if (forced < 0) { const char *e = getenv("DYN_GEMM_SPLIT"); forced = e ? atoi(e) : 0; }
+    const int unit = BK * RING;                       // a plane is a multiple of RING stages
     int S = 1;
-    while ((N / GN) * S < 192 && S < 8 && K % (S * 2 * GK) == 0 && K / (S * 2) >= 256) S *= 2;
+    while ((N / BN) * S < 192 && K % (S * 2 * unit) == 0 && K / (S * 2) >= 2 * unit) S *= 2;
+    if (forced > 0 && K % (forced * unit) == 0) S = forced;
     return S;
 }
 
-hipError_t launch_gemm(int dtype, const void *X, const void *W, const void *R, void *Y, float *partial,
-                       size_t plane_stride, int rows, int N, int K, hipStream_t s) {
+hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
+                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid) {
     if (rows <= 0) return hipSuccess;
     if (dtype == 0) {
-        hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, (const float *)X,
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, (const float *)X, ldx,
                            (const float *)W, (const float *)R, (float *)Y, rows, N, K);
-        return hipGetLastError();
+        hipError_t e0 = hipGetLastError();
+        if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
+        return e0;
     }
     const int S = gemm_split_k(dtype, N, K);
-    const int m_tiles = (rows + GM - 1) / GM;
-    const int ns = (N / GN) * S;
+    const int MT = rows <= 64 ? 64 : 128;
+    const int m_tiles = (rows + MT - 1) / MT;
+    const int ns = (N / BN) * S;
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
-    hipLaunchKernelGGL(gemm_bf16_kernel, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, (const bf16_t *)W,
-                       (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S);
+    if (MT == 64)
+        hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S);
+    else
+        hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1) return e;
     const size_t n_vec = (size_t)rows * N / 4;
     const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);

@@ -117,7 +117,7 @@ def config(name: str) -> Workload:
         seqs = ((150, 150), (1, 77), (37, 90), (1, 300), (1, 1))
         return Workload("c3_small", sh, seqs, 2, (0, 150, 190))
     if name == "c4_small":
-        sh = LayerShape("bf16", 512, 8, 2, 128, 768, n_experts=8, top_k=2)
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024, n_experts=8, top_k=2)
         ctx = _uniform_ctx(3, 40, 1, 200)
         return Workload("c4_small", sh, tuple((1, c) for c in ctx), 3, (0, 17, 40))
     if name == "c5_small":
