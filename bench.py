@@ -113,6 +113,8 @@ def main():
     ap.add_argument("--schedules", default="all",
                     help="comma-separated overlapped schedules to time beside sequential ('all', or 'none')")
     ap.add_argument("--no-event-profile", action="store_true", help="skip the per-operator HIP-event pass")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="only copy 1 GiB device-to-device five times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
@@ -120,6 +122,16 @@ def main():
     import torch
     from paper_2605_21603_amd import binding as B
     from workloads import gen
+
+    if args.copy_probe:
+        a = torch.full((1 << 30,), 7, dtype=torch.uint8, device="cuda:0")
+        b = torch.empty_like(a)
+        torch.cuda.synchronize()
+        for _ in range(5):
+            b.copy_(a)
+        torch.cuda.synchronize()
+        print(json.dumps({"copy_probe_bytes_read": 1 << 30, "copy_probe_bytes_written": 1 << 30, "copies": 5}))
+        return
 
     w = gen.config(args.workload)
     log("generating %s (seed %d) ..." % (w.name, w.seed))
@@ -156,7 +168,7 @@ def main():
             for rec in layer.slot_times():
                 op_ms.setdefault(B.OP_NAMES[rec["op"]], []).append(rec["stop_ms"] - rec["start_ms"])
                 if rec["op"] == B.DYN_OP_ATTN:
-                    attn_ms.append(rec["main_stop_ms"] - rec["start_ms"])
+                    attn_ms.append(rec["main_stop_ms"] - rec["main_start_ms"])
     layer.set_profiling(False)
     attn_avg_ms = sum(attn_ms) / len(attn_ms) if attn_ms else float("nan")
     attn_gb = attention_bytes(w) / 1e9

@@ -160,8 +160,9 @@ dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn
 typedef struct {
     int layer, op, nano, n_nano, stream, partition;
     float start_ms;            /* times relative to the fork point of that forward */
-    float main_stop_ms;        /* end of the operator's main kernel (the contraction or the attention chunk
-                                  kernel) where a second kernel follows (split-K reduce, split-KV combine) */
+    float main_start_ms;       /* start and end of the operator's main kernel (the contraction, the attention */
+    float main_stop_ms;        /* chunk kernel) where helper kernels surround it (work list, split-K reduce,
+                                  split-KV combine); otherwise start_ms and stop_ms */
     float stop_ms;
 } dyn_slot_time;
 dyn_status dyn_layer_set_profiling(dyn_layer *layer, int on);

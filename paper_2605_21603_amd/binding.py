@@ -57,7 +57,8 @@ class dyn_schedule(C.Structure):
 
 class dyn_slot_time(C.Structure):
     _fields_ = [("layer", C.c_int), ("op", C.c_int), ("nano", C.c_int), ("n_nano", C.c_int), ("stream", C.c_int),
-                ("partition", C.c_int), ("start_ms", C.c_float), ("main_stop_ms", C.c_float), ("stop_ms", C.c_float)]
+                ("partition", C.c_int), ("start_ms", C.c_float), ("main_start_ms", C.c_float), ("main_stop_ms", C.c_float),
+                ("stop_ms", C.c_float)]
 
 
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
@@ -215,7 +216,8 @@ class DynLayer:
         arr = (dyn_slot_time * max(1, n.value))()
         _check(lib().dyn_layer_get_slot_times(self.handle, C.cast(arr, C.c_void_p), n.value, C.addressof(n)))
         return [dict(layer=a.layer, op=a.op, nano=a.nano, n_nano=a.n_nano, stream=a.stream, partition=a.partition,
-                     start_ms=a.start_ms, main_stop_ms=a.main_stop_ms, stop_ms=a.stop_ms) for a in arr[:n.value]]
+                     start_ms=a.start_ms, main_start_ms=a.main_start_ms, main_stop_ms=a.main_stop_ms,
+                     stop_ms=a.stop_ms) for a in arr[:n.value]]
 
 
 def make_config(sh) -> dyn_layer_config:

@@ -49,6 +49,7 @@ struct Dispatch {
 
 struct WsLayout {
     size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, plan, total;
+    size_t sel, wgt, lists_gu, lists_down, moe_planes;   // MoE: routing, per-dispatch expert lists, down-projection planes
     int ld_h, ld_attn, ld_act;   // padded row strides (elements) of the buffers the projections read
     size_t gemm_partial[4];   // split-K planes of the qkv, o, gate/up and down projections: operators of
                               // different micro-batches run concurrently, so each has its own
@@ -76,7 +77,7 @@ struct dyn_layer {
     hipEvent_t fork_event = nullptr;
     std::vector<GraphEntry> graphs;
     bool profiling = false;
-    std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, main stop, stop) per dispatch
+    std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, main start, main stop, stop) per dispatch
     std::vector<Dispatch> prof_plan;
 };
 
@@ -114,12 +115,22 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
                               {2 * c.mlp_inter, c.hidden}, {c.hidden, c.mlp_inter}};
     for (int i = 0; i < 4; ++i) {
         const int S = dyn::gemm_split_k(c.dtype, widths[i][0], widths[i][1]);
-        w.gemm_partial[i] = take(S > 1 ? (size_t)S * t * widths[i][0] * sizeof(float) : 0);
+        const size_t prow = (i == 2 ? (size_t)pairs : 1) * t;     // the MoE gate/up projection has a row per (token, expert)
+        w.gemm_partial[i] = take(S > 1 ? (size_t)S * prow * widths[i][0] * sizeof(float) : 0);
     }
     w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
     w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
     w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
     w.plan = take((t * w.max_chunks + t) * 2 * sizeof(int32_t));   // per dispatch: 2 header words + 2 per entry
+    if (c.n_experts) {
+        const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter);
+        w.sel = take(t * c.top_k * sizeof(int32_t));
+        w.wgt = take(t * c.top_k * sizeof(float));
+        // a dispatch over rows r0.. uses ints [r0 * top_k * 2E, ...): E counts + E lists of up to rows * top_k pairs
+        w.lists_gu = take(t * c.top_k * 2 * c.n_experts * sizeof(int32_t));
+        w.lists_down = take(t * c.top_k * 2 * c.n_experts * sizeof(int32_t));
+        w.moe_planes = take((size_t)Sd * t * c.top_k * c.hidden * sizeof(float));
+    }
     w.total = off;
     return w;
 }
@@ -264,7 +275,7 @@ dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream
 }
 
 dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws, const Dispatch &d, hipStream_t st,
-                     hipEvent_t mid) {
+                     hipEvent_t mid, hipEvent_t pre) {
     const dyn_layer_config &c = L->cfg;
     const dyn_layer_weights &w = L->w[d.layer];
     const size_t e = esize(c);
@@ -299,7 +310,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
                                         (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
                                         (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
-                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 2, sh, rows, st, mid);
+                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 2, sh, rows, st, mid, pre);
             break;
         case DYN_OP_OPROJ:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
@@ -308,14 +319,55 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
         case DYN_OP_NORM2:
             err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
             break;
+        case DYN_OP_ROUTE:
+            err = dyn::launch_route(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_router,
+                                    (int32_t *)(base + ws.sel) + (size_t)d.r0 * c.top_k,
+                                    (float *)(base + ws.wgt) + (size_t)d.r0 * c.top_k, rows, H, c.n_experts, c.top_k, st);
+            break;
         case DYN_OP_GATE_UP:
+            if (c.n_experts) {
+                // rows of the grouped projections are (token, rank) pairs p = t * top_k + rank
+                const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
+                int32_t *counts = (int32_t *)(base + ws.lists_gu) + (size_t)pair0 * 2 * c.n_experts;
+                int32_t *lists = counts + c.n_experts;
+                err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
+                if (err != hipSuccess) break;
+                dyn::GemmGroups gr{counts, lists, n_pairs, c.top_k, c.n_experts, (size_t)2 * I * H, 0};
+                err = dyn::launch_gemm_grouped(c.dtype, base + ws.h, ws.ld_h, w.w_gate_up, base + ws.gu,
+                                               (float *)(base + ws.gemm_partial[2]), T * c.top_k * 2 * I, gr, rows, pair0,
+                                               n_pairs, 2 * I, H, st, mid);
+                break;
+            }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
                                    partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st, mid);
             break;
         case DYN_OP_SILU:
+            if (c.n_experts) {
+                const size_t pair0 = (size_t)d.r0 * c.top_k;
+                err = dyn::launch_silu_mul(c.dtype, base + ws.gu + pair0 * 2 * I * e, base + ws.act + pair0 * ws.ld_act * e,
+                                           ws.ld_act, rows * c.top_k, I, st);
+                break;
+            }
             err = dyn::launch_silu_mul(c.dtype, rowp(base + ws.gu, 2 * I), (void *)rowp(base + ws.act, ws.ld_act), ws.ld_act, rows, I, st);
             break;
         case DYN_OP_DOWN:
+            if (c.n_experts) {
+                const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
+                int32_t *counts = (int32_t *)(base + ws.lists_down) + (size_t)pair0 * 2 * c.n_experts;
+                int32_t *lists = counts + c.n_experts;
+                err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
+                if (err != hipSuccess) break;
+                const int Sd = dyn::gemm_split_k(c.dtype, H, I);
+                const size_t plane = T * c.top_k * H;
+                dyn::GemmGroups gr{counts, lists, n_pairs, 1, c.n_experts, (size_t)H * I, 1};
+                err = dyn::launch_gemm_grouped(c.dtype, base + ws.act, ws.ld_act, w.w_down, nullptr,
+                                               (float *)(base + ws.moe_planes), plane, gr, rows, pair0, n_pairs, H, I, st, mid);
+                if (err != hipSuccess) break;
+                err = dyn::launch_moe_combine(c.dtype, (const float *)(base + ws.moe_planes) + (size_t)pair0 * H, plane, Sd,
+                                              (const float *)(base + ws.wgt) + pair0, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
+                                              rows, H, c.top_k, st);
+                break;
+            }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, ws.ld_act), ws.ld_act, w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
                                    partial(3, H), T * H, rows, H, I, st, mid);
             break;
@@ -337,7 +389,7 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
     }
     if (!L->fork_event) HIP_TRY(hipEventCreateWithFlags(&L->fork_event, hipEventDisableTiming));
     if (profile) {
-        while (L->prof_events.size() < 1 + 3 * plan.size()) {
+        while (L->prof_events.size() < 1 + 4 * plan.size()) {
             hipEvent_t ev;
             HIP_TRY(hipEventCreate(&ev));
             L->prof_events.push_back(ev);
@@ -363,12 +415,14 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
         for (int dep : d.deps)
             if (st_of[dep] != st) HIP_TRY(hipStreamWaitEvent(st, L->events[dep], 0));
         if (profile) {
-            HIP_TRY(hipEventRecord(L->prof_events[1 + 3 * i], st));
-            HIP_TRY(hipEventRecord(L->prof_events[2 + 3 * i], st));   // stays here unless the operator has two kernels
+            // the two middle events stay here unless the operator records them around its main kernel
+            for (int j = 1; j <= 3; ++j) HIP_TRY(hipEventRecord(L->prof_events[j + 4 * i], st));
         }
-        dyn_status rc = launch_op(L, b, ws, d, st, profile && d.r1 > d.r0 ? L->prof_events[2 + 3 * i] : nullptr);
+        const bool mark = profile && d.r1 > d.r0;
+        dyn_status rc = launch_op(L, b, ws, d, st, mark ? L->prof_events[3 + 4 * i] : nullptr,
+                                  mark ? L->prof_events[2 + 4 * i] : nullptr);
         if (rc != DYN_OK) return rc;
-        if (profile) HIP_TRY(hipEventRecord(L->prof_events[3 + 3 * i], st));
+        if (profile) HIP_TRY(hipEventRecord(L->prof_events[4 + 4 * i], st));
         HIP_TRY(hipEventRecord(L->events[i], st));
         last_on[key] = (int)i;
     }
@@ -417,7 +471,7 @@ dyn_status check_config(const dyn_layer_config *c) {
     for (auto &p : nk)
         if (!dyn::gemm_supported(c->dtype, p[0], p[1]))
             return fail(DYN_ERR_UNSUPPORTED, "projection %d x %d: bf16 needs widths that are multiples of 128 and depths that are multiples of 256", p[0], p[1]);
-    if (c->n_experts > 0) return fail(DYN_ERR_UNSUPPORTED, "mixture-of-experts layers are not built yet");
+    if (c->n_experts > 16) return fail(DYN_ERR_UNSUPPORTED, "at most 16 experts");
     return DYN_OK;
 }
 
@@ -541,11 +595,15 @@ dyn_status dyn_layer_get_slot_times(dyn_layer *L, dyn_slot_time *out, int capaci
     *n_out = n;
     for (int i = 0; i < n && i < capacity; ++i) {
         const Dispatch &d = L->prof_plan[i];
-        out[i] = dyn_slot_time{d.layer, d.op, d.nano, d.n_nano, d.stream, d.partition, 0.f, 0.f, 0.f};
-        HIP_TRY(hipEventElapsedTime(&out[i].start_ms, L->prof_events[0], L->prof_events[1 + 3 * i]));
-        HIP_TRY(hipEventElapsedTime(&out[i].main_stop_ms, L->prof_events[0], L->prof_events[2 + 3 * i]));
-        HIP_TRY(hipEventElapsedTime(&out[i].stop_ms, L->prof_events[0], L->prof_events[3 + 3 * i]));
-        if (out[i].main_stop_ms <= out[i].start_ms) out[i].main_stop_ms = out[i].stop_ms;   // one-kernel operator
+        out[i] = dyn_slot_time{d.layer, d.op, d.nano, d.n_nano, d.stream, d.partition, 0.f, 0.f, 0.f, 0.f};
+        HIP_TRY(hipEventElapsedTime(&out[i].start_ms, L->prof_events[0], L->prof_events[1 + 4 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].main_start_ms, L->prof_events[0], L->prof_events[2 + 4 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].main_stop_ms, L->prof_events[0], L->prof_events[3 + 4 * i]));
+        HIP_TRY(hipEventElapsedTime(&out[i].stop_ms, L->prof_events[0], L->prof_events[4 + 4 * i]));
+        if (out[i].main_stop_ms <= out[i].main_start_ms) {   // one-kernel operator: no inner marks
+            out[i].main_start_ms = out[i].start_ms;
+            out[i].main_stop_ms = out[i].stop_ms;
+        }
     }
     return DYN_OK;
 }

@@ -21,6 +21,17 @@ struct AttnShape {
     int max_chunks;                // chunks that fit max_pages_per_seq: stride of the partial arrays
 };
 
+// Expert grouping of a projection (all fields zero: plain GEMM).  Group e has counts[e] rows;
+// row i of the group reads X row lists[e * cap + i] / x_div and writes output row
+// lists[e * cap + i]; its weights start w_stride elements after the previous group's.
+struct GemmGroups {
+    const int32_t *counts;
+    const int32_t *lists;
+    int cap, x_div, n_groups;
+    size_t w_stride;
+    int force_planes;
+};
+
 // Split-K factor of a GEMM with output width N and depth K.  A function of (N, K) alone so
 // that a row's summation order never depends on how many rows are in flight.
 int gemm_split_k(int dtype, int N, int K);
@@ -36,6 +47,24 @@ hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, in
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
                        size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid = nullptr);
 
+hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W, void *Y, float *partial,
+                               size_t plane_stride, const GemmGroups &gr, int max_rows, int row0, int n_rows, int N, int K,
+                               hipStream_t s, hipEvent_t mid = nullptr);
+
+// MoE router for token rows: logits = h W_r^T in fp32, top_k largest (ties to the lower index),
+// softmax over the selected logits.  sel / wgt are [rows, top_k], largest logit first.
+hipError_t launch_route(int dtype, const void *h, int ldh, const float *w_router, int32_t *sel, float *wgt, int rows,
+                        int H, int E, int top_k, hipStream_t s);
+
+// Per-expert lists of (token, rank) pairs p = t * top_k + j in ascending p, for the rows of one
+// dispatch: counts[E], lists[E, cap].  pair_base = first pair id of the dispatch.
+hipError_t launch_expert_lists(const int32_t *sel, int n_pairs, int pair_base, int E, int cap, int32_t *counts,
+                               int32_t *lists, hipStream_t s);
+
+// y[t] = x2[t] + sum_j wgt[t, j] * (sum_p planes[p][t * top_k + j]) in rank order j, planes in order p.
+hipError_t launch_moe_combine(int dtype, const float *planes, size_t plane_stride, int S, const float *wgt,
+                              const void *x2, void *y, int rows, int H, int top_k, hipStream_t s);
+
 // Rotary on the q and k heads of qkv rows (in place for q) and cache append of k', v.
 hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                           const int32_t *block_table, void *k_cache, void *v_cache, const RopeTable &tab,
@@ -47,7 +76,8 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
                             float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
-                            hipStream_t s, hipEvent_t mid = nullptr);   // mid: recorded between the chunk kernel and the combine
+                            hipStream_t s, hipEvent_t mid = nullptr,    // mid: recorded between the chunk kernel and the combine
+                            hipEvent_t pre = nullptr);  // pre: recorded after the work-list kernel, before the chunk kernel
 
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
 hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s);

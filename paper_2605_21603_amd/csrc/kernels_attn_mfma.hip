@@ -231,13 +231,14 @@ bool attention_mfma_supported(int dtype, const AttnShape &sh) {
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
                             float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
-                            hipStream_t s, hipEvent_t mid) {
+                            hipStream_t s, hipEvent_t mid, hipEvent_t pre) {
     if (rows <= 0) return hipSuccess;
     if (!attention_mfma_supported(dtype, sh))
         return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
                                         part_o, part_ml, sh, rows, s, mid);
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, pos_of_token, rows, sh.chunk_pages * PS, plan);
     hipError_t e = hipGetLastError();
+    if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
     const long max_items = (long)rows * sh.n_kv * sh.max_chunks;
     const int grid = (int)((max_items + 7) / 8 < kPersistentGroups ? (max_items + 7) / 8 : kPersistentGroups);

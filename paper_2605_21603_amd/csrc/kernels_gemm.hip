@@ -20,16 +20,25 @@ namespace dyn {
 // through LDS.  Each output is one fp32 FMA chain in ascending k.
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__ X, int ldx, const float *__restrict__ W,
                                                        const float *__restrict__ R, float *__restrict__ Y, int M,
-                                                       int N, int K) {
+                                                       int N, int K, GemmGroups gr) {
     __shared__ float xs[16][64 + 4];
     __shared__ float ws[16][64 + 4];
+    const int32_t *list = nullptr;
+    if (gr.n_groups) {                                 // blockIdx.z = expert: its rows come from a list
+        M = gr.counts[blockIdx.z];
+        list = gr.lists + (size_t)blockIdx.z * gr.cap;
+        W += (size_t)blockIdx.z * gr.w_stride;
+    }
     const int m0 = blockIdx.y * 64, n0 = blockIdx.x * 64;
+    if (m0 >= M) return;
     const int tx = threadIdx.x % 16, ty = threadIdx.x / 16;
     float acc[4][4] = {};
     for (int k0 = 0; k0 < K; k0 += 16) {
         for (int e = threadIdx.x; e < 64 * 16; e += 256) {
             const int r = e / 16, kk = e % 16;
-            xs[kk][r] = (m0 + r < M && k0 + kk < K) ? X[(size_t)(m0 + r) * ldx + k0 + kk] : 0.f;
+            const bool in = m0 + r < M && k0 + kk < K;
+            const size_t xrow = in ? (list ? list[m0 + r] / gr.x_div : m0 + r) : 0;
+            xs[kk][r] = in ? X[xrow * ldx + k0 + kk] : 0.f;
             ws[kk][r] = (n0 + r < N && k0 + kk < K) ? W[(size_t)(n0 + r) * K + k0 + kk] : 0.f;
         }
         __syncthreads();
@@ -50,7 +59,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 #pragma unroll
         for (int j = 0; j < 4; ++j) {
             const int m = m0 + ty * 4 + i, n = n0 + tx * 4 + j;
-            if (m < M && n < N) Y[(size_t)m * N + n] = acc[i][j] + (R ? R[(size_t)m * N + n] : 0.f);
+            if (m < M && n < N) {
+                const size_t orow = list ? list[m] : m;
+                Y[orow * N + n] = acc[i][j] + (R ? R[orow * N + n] : 0.f);
+            }
         }
 }
 
@@ -70,7 +82,7 @@ template <int MT>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, int ldx,
                                                         const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
                                                         bf16_t *__restrict__ Y, float *__restrict__ P,
-                                                        size_t plane_stride, int M, int N, int K, int S) {
+                                                        size_t plane_stride, int M, int N, int K, int S, GemmGroups gr) {
     constexpr int XP = MT / 32;                     // 16-byte X pieces per thread and stage
     constexpr int NB = MT / 32;                     // B tiles (16 X rows) per wave
     __shared__ __attribute__((aligned(16))) unsigned char lw[2][BN * ROWB];
@@ -79,8 +91,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
     // m tiles of one (n tile, plane)) get ids 8 apart: same XCD, same L2, adjacent in time.
     const int u = blockIdx.x % 8, v = blockIdx.x / 8;
-    const int m_tile = v % m_tiles, ns = (v / m_tiles) * 8 + u;
-    if (ns >= (N / BN) * S) return;
+    const int m_tile = v % m_tiles;
+    int ns = (v / m_tiles) * 8 + u;
+    const int32_t *list = nullptr;
+    if (gr.n_groups) {                                 // grouped: (expert, n tile, plane); rows come from the expert's list
+        const int per_group = (N / BN) * S;
+        if (ns >= per_group * gr.n_groups) return;
+        const int e = ns / per_group;
+        ns -= e * per_group;
+        M = gr.counts[e];
+        if (m_tile * MT >= M) return;
+        list = gr.lists + (size_t)e * gr.cap;
+        W += (size_t)e * gr.w_stride;
+    } else if (ns >= (N / BN) * S) {
+        return;
+    }
     const int n_tile = ns / S, sp = ns % S;
     const int Kp = K / S, kbase = sp * Kp, n_stage = Kp / BK;
     const int n0 = n_tile * BN, m0 = m_tile * MT;
@@ -92,7 +117,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
 #pragma unroll
     for (int q = 0; q < 4; ++q) wg[q] = W + (size_t)(n0 + prow + 32 * q) * K + kbase + pcol * 8;
 #pragma unroll
-    for (int q = 0; q < XP; ++q) xg[q] = X + (size_t)min(m0 + prow + 32 * q, M - 1) * ldx + kbase + pcol * 8;
+    for (int q = 0; q < XP; ++q) {
+        const int mr = min(m0 + prow + 32 * q, M - 1);
+        xg[q] = X + (size_t)(list ? list[mr] / gr.x_div : mr) * ldx + kbase + pcol * 8;
+    }
     const int loff = prow * ROWB + pcol * 16;
 
     u32x4 rw[RING][4], rx[RING][XP];
@@ -166,19 +194,20 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
             const int m = m0 + wm * (MT / 2) + b * 16 + lr;
             const int n = n0 + wn * 64 + a * 16 + 4 * lq;
             if (m >= M) continue;
+            const size_t orow = list ? list[m] : m;
             f32x4 o = acc[a][b];
-            if (S == 1) {
+            if (S == 1 && !gr.force_planes) {
                 if (R) {
-                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(R + (size_t)m * N + n);
+                    const u32x2 rv = *reinterpret_cast<const u32x2 *>(R + orow * N + n);
                     o[0] += bf2f(rv[0] & 0xffff); o[1] += bf2f(rv[0] >> 16);
                     o[2] += bf2f(rv[1] & 0xffff); o[3] += bf2f(rv[1] >> 16);
                 }
                 u32x2 ov;
                 ov[0] = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
                 ov[1] = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
-                *reinterpret_cast<u32x2 *>(Y + (size_t)m * N + n) = ov;
+                *reinterpret_cast<u32x2 *>(Y + orow * N + n) = ov;
             } else {
-                *reinterpret_cast<f32x4 *>(P + (size_t)sp * plane_stride + (size_t)m * N + n) = o;
+                *reinterpret_cast<f32x4 *>(P + (size_t)sp * plane_stride + orow * N + n) = o;
             }
         }
 }
@@ -225,9 +254,10 @@ int gemm_split_k(int dtype, int N, int K) {
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
                        size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid) {
     if (rows <= 0) return hipSuccess;
+    const GemmGroups none{};
     if (dtype == 0) {
         hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, (const float *)X, ldx,
-                           (const float *)W, (const float *)R, (float *)Y, rows, N, K);
+                           (const float *)W, (const float *)R, (float *)Y, rows, N, K, none);
         hipError_t e0 = hipGetLastError();
         if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
         return e0;
@@ -239,10 +269,10 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
     if (MT == 64)
         hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S);
+                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none);
     else
         hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S);
+                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1) return e;
@@ -250,6 +280,46 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
     hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
                        (bf16_t *)Y, n_vec, S);
+    return hipGetLastError();
+}
+
+// Expert-grouped form: group e multiplies the rows named by its list with its own weight
+// matrix W + e * w_stride.  max_rows bounds any group's row count (it sizes the grid; tiles
+// past a group's count exit at once).  X, Y and partial are indexed by the lists' row ids (not
+// relative to the dispatch); the dispatch's output rows are row0 .. row0 + n_rows - 1.  With
+// gr.force_planes the fp32 plane sums go to `partial` for every split factor, including 1, and
+// nothing is written to Y.
+hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W, void *Y, float *partial,
+                               size_t plane_stride, const GemmGroups &gr, int max_rows, int row0, int n_rows, int N, int K,
+                               hipStream_t s, hipEvent_t mid) {
+    if (max_rows <= 0 || gr.n_groups <= 0) return hipSuccess;
+    if (dtype == 0) {
+        hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (max_rows + 63) / 64, gr.n_groups), dim3(256), 0, s,
+                           (const float *)X, ldx, (const float *)W, (const float *)nullptr,
+                           gr.force_planes ? partial : (float *)Y, max_rows, N, K, gr);
+        hipError_t e0 = hipGetLastError();
+        if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
+        return e0;
+    }
+    const int S = gemm_split_k(dtype, N, K);
+    const int MT = max_rows <= 64 ? 64 : 128;
+    const int m_tiles = (max_rows + MT - 1) / MT;
+    const int ns = (N / BN) * S * gr.n_groups;
+    const int grid = ((ns + 7) / 8) * 8 * m_tiles;
+    if (MT == 64)
+        hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+                           (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
+    else
+        hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+                           (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
+    hipError_t e = hipGetLastError();
+    if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
+    if (e != hipSuccess || S == 1 || gr.force_planes) return e;
+    // output rows row0 .. row0 + n_rows - 1 are exactly the rows the groups wrote
+    const size_t n_vec = (size_t)n_rows * N / 4;
+    const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
+    hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial + (size_t)row0 * N, plane_stride,
+                       (const bf16_t *)nullptr, (bf16_t *)Y + (size_t)row0 * N, n_vec, S);
     return hipGetLastError();
 }
 

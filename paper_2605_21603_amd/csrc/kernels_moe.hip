@@ -1,0 +1,119 @@
+// Mixture-of-experts pieces around the grouped projections: router, per-expert row lists,
+// weighted combine.  Every token's routing and output depend on that token alone, and every
+// sum has a fixed order (experts by router rank, split-K planes ascending), so results do
+// not depend on how the batch is cut.
+#include "common.h"
+#include "kernels.h"
+
+namespace dyn {
+
+constexpr int kMaxExperts = 16;
+
+// One wave per token.  Lane l accumulates its slice of every expert's dot product in fp32,
+// a butterfly adds the slices, lane 0 picks the top_k largest logits (ties to the lower
+// index) and normalises exp(logit - max) over the picked ones.
+template <typename T>
+__global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ h, int ldh, const float *__restrict__ w_router,
+                                                    int32_t *__restrict__ sel, float *__restrict__ wgt, int rows,
+                                                    int H, int E, int top_k) {
+    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+    if (t >= rows) return;
+    float acc[kMaxExperts];
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e) acc[e] = 0.f;
+    for (int k = lane; k < H; k += 64) {
+        const float x = to_f32<T>(h[(size_t)t * ldh + k]);
+#pragma unroll
+        for (int e = 0; e < kMaxExperts; ++e)
+            if (e < E) acc[e] = fmaf(x, w_router[(size_t)e * H + k], acc[e]);
+    }
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e) acc[e] = wave_sum(acc[e]);
+    if (lane != 0) return;
+    bool used[kMaxExperts] = {};
+    int pick[kMaxExperts];
+    float mx = -INFINITY;
+    for (int j = 0; j < top_k; ++j) {
+        int best = -1;
+#pragma unroll
+        for (int e = 0; e < kMaxExperts; ++e)
+            if (e < E && !used[e] && (best < 0 || acc[e] > acc[best])) best = e;
+        used[best] = true;
+        pick[j] = best;
+        mx = fmaxf(mx, acc[best]);
+    }
+    float denom = 0.f;
+    for (int j = 0; j < top_k; ++j) denom += expf(acc[pick[j]] - mx);
+    for (int j = 0; j < top_k; ++j) {
+        sel[(size_t)t * top_k + j] = pick[j];
+        wgt[(size_t)t * top_k + j] = expf(acc[pick[j]] - mx) / denom;
+    }
+}
+
+hipError_t launch_route(int dtype, const void *h, int ldh, const float *w_router, int32_t *sel, float *wgt, int rows,
+                        int H, int E, int top_k, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    const dim3 grid((rows + 3) / 4);
+    if (dtype == 0)
+        hipLaunchKernelGGL(route_kernel<float>, grid, dim3(256), 0, s, (const float *)h, ldh, w_router, sel, wgt, rows, H, E, top_k);
+    else
+        hipLaunchKernelGGL(route_kernel<bf16_t>, grid, dim3(256), 0, s, (const bf16_t *)h, ldh, w_router, sel, wgt, rows, H, E, top_k);
+    return hipGetLastError();
+}
+
+// One wave per expert scans the dispatch's pairs in ascending order and appends its own.
+__global__ void expert_lists_kernel(const int32_t *__restrict__ sel, int n_pairs, int pair_base, int cap,
+                                    int32_t *__restrict__ counts, int32_t *__restrict__ lists) {
+    const int e = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    int count = 0;
+    for (int base = 0; base < n_pairs; base += 64) {
+        const int p = base + lane;
+        const bool mine = p < n_pairs && sel[pair_base + p] == e;
+        const unsigned long long mask = __ballot(mine);
+        if (mine) lists[(size_t)e * cap + count + __popcll(mask & ((1ull << lane) - 1ull))] = pair_base + p;
+        count += __popcll(mask);
+    }
+    if (lane == 0) counts[e] = count;
+}
+
+hipError_t launch_expert_lists(const int32_t *sel, int n_pairs, int pair_base, int E, int cap, int32_t *counts,
+                               int32_t *lists, hipStream_t s) {
+    if (n_pairs <= 0) return hipSuccess;
+    hipLaunchKernelGGL(expert_lists_kernel, dim3(1), dim3(64 * E), 0, s, sel, n_pairs, pair_base, cap, counts, lists);
+    return hipGetLastError();
+}
+
+// Four outputs per thread.
+template <typename T>
+__global__ __launch_bounds__(256) void moe_combine_kernel(const float *__restrict__ planes, size_t plane_stride, int S,
+                                                          const float *__restrict__ wgt, const T *__restrict__ x2,
+                                                          T *__restrict__ y, size_t n_vec, int H, int top_k) {
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += (size_t)gridDim.x * 256) {
+        const size_t t = i / (H / 4), c = (i % (H / 4)) * 4;
+        f32x4 m = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int j = 0; j < top_k; ++j) {
+            const size_t row = t * top_k + j;
+            f32x4 o = *reinterpret_cast<const f32x4 *>(planes + row * H + c);
+            for (int p = 1; p < S; ++p) o += *reinterpret_cast<const f32x4 *>(planes + (size_t)p * plane_stride + row * H + c);
+            m += o * wgt[row];
+        }
+#pragma unroll
+        for (int r = 0; r < 4; ++r) y[t * H + c + r] = from_f32<T>(to_f32<T>(x2[t * H + c + r]) + m[r]);
+    }
+}
+
+hipError_t launch_moe_combine(int dtype, const float *planes, size_t plane_stride, int S, const float *wgt,
+                              const void *x2, void *y, int rows, int H, int top_k, hipStream_t s) {
+    if (rows <= 0) return hipSuccess;
+    const size_t n_vec = (size_t)rows * H / 4;
+    const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
+    if (dtype == 0)
+        hipLaunchKernelGGL(moe_combine_kernel<float>, dim3(blocks), dim3(256), 0, s, planes, plane_stride, S, wgt,
+                           (const float *)x2, (float *)y, n_vec, H, top_k);
+    else
+        hipLaunchKernelGGL(moe_combine_kernel<bf16_t>, dim3(blocks), dim3(256), 0, s, planes, plane_stride, S, wgt,
+                           (const bf16_t *)x2, (bf16_t *)y, n_vec, H, top_k);
+    return hipGetLastError();
+}
+
+}  // namespace dyn

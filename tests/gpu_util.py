@@ -55,9 +55,24 @@ def as_f64(t: torch.Tensor) -> np.ndarray:
 
 def check_against_oracle(w, data, y, kc, vc, rows=None):
     """y / caches from the GPU against the oracle on the same inputs.  Returns the error."""
-    y_ref, kcs, vcs = orc.forward(w, data)
+    routing = [] if w.shape.n_experts else None
+    y_ref, kcs, vcs = orc.forward(w, data, routing_out=routing)
     dt = orc.dtype_code(w.shape.dtype)
-    err = row_rel_err(as_f64(y), y_ref)
+    y_got = as_f64(y)
+    if routing and w.shape.n_layers == 1:
+        # Two routings are both correct where the router's k-th and (k+1)-th logits nearly tie.
+        # Rows that miss the tolerance with such a tie are re-checked against the other selection.
+        bad = np.abs(y_got - y_ref).max(axis=1) / np.abs(y_ref).max(axis=1) > TOL[w.shape.dtype]
+        logits, sel = routing[0]["logits"], routing[0]["sel"]
+        srt = np.sort(logits, axis=1)[:, ::-1]
+        margin = srt[:, w.shape.top_k - 1] - srt[:, w.shape.top_k]
+        for t in np.nonzero(bad)[0]:
+            assert margin[t] < 1e-3, "row %d misses tolerance without a near tie (margin %.3e)" % (t, margin[t])
+            forced = sel.copy()
+            forced[t, -1] = np.argsort(-logits[t])[w.shape.top_k]
+            y_alt, _, _ = orc.forward(w, data, forced_sel=[forced])
+            y_ref[t] = y_alt[t]
+    err = row_rel_err(y_got, y_ref)
     assert err <= TOL[w.shape.dtype], "max rel err %.3e" % err
     ps = w.shape.page_size
     for l in range(w.shape.n_layers):

@@ -47,7 +47,7 @@ def host_batch(w):
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.dyn_slot) == 5
     assert C.sizeof(B.dyn_layer_config) == 12 * 4
-    assert C.sizeof(B.dyn_slot_time) == 9 * 4
+    assert C.sizeof(B.dyn_slot_time) == 10 * 4
 
 
 def test_create_rejects_bad_configs():

@@ -11,22 +11,25 @@ from gpu_util import GpuRun, check_against_oracle, say
 
 pytestmark = pytest.mark.gpu
 
-SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small"]
+SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small", "c4_small", "f32_moe_small"]
 
 
 def schedules_for(w):
     rows = w.nano_rows
     k = len(rows) - 1
-    T = w.n_tokens
+    chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
     out = {
-        "split": B.nano_schedule(rows),
-        "split_stagger2": B.nano_schedule(rows, stagger=2),
-        "split_one_stream": B.nano_schedule(rows, streams=[0] * k),
-        "mlp_merged": B.nano_schedule(rows, merged_ops=[B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN], stagger=1),
-        "gemms_merged": B.nano_schedule(rows, merged_ops=[B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP, B.DYN_OP_DOWN],
-                                        stagger=1),
-        "with_empty_nano": B.nano_schedule((0,) + tuple(rows) if rows[1] != 0 else rows),
+        "split": B.nano_schedule(rows, chain),
+        "split_stagger2": B.nano_schedule(rows, chain, stagger=2),
+        "split_one_stream": B.nano_schedule(rows, chain, streams=[0] * k),
+        "mlp_merged": B.nano_schedule(rows, chain, merged_ops=[B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN], stagger=1),
+        "gemms_merged": B.nano_schedule(rows, chain, stagger=1,
+                                        merged_ops=[B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP, B.DYN_OP_DOWN]),
+        "route_merged_experts_split": B.nano_schedule(rows, chain, merged_ops=[B.DYN_OP_ROUTE, B.DYN_OP_NORM2], stagger=1),
+        "with_empty_nano": B.nano_schedule((0,) + tuple(rows) if rows[1] != 0 else rows, chain),
     }
+    if not w.shape.n_experts:
+        del out["route_merged_experts_split"]
     return out
 
 
