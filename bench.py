@@ -29,13 +29,14 @@ def log(msg):
 
 def candidate_schedules(B, w, use_graph):
     rows = w.nano_rows
+    chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
     mlp = [B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN]
     gemms = [B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP, B.DYN_OP_DOWN]
     return {
-        "k2_split_stagger0": B.nano_schedule(rows, stagger=0, use_graph=use_graph),
-        "k2_split_stagger2": B.nano_schedule(rows, stagger=2, use_graph=use_graph),
-        "k2_mlp_merged_stagger2": B.nano_schedule(rows, merged_ops=mlp, stagger=2, use_graph=use_graph),
-        "k2_gemms_merged_stagger1": B.nano_schedule(rows, merged_ops=gemms, stagger=1, use_graph=use_graph),
+        "k2_split_stagger0": B.nano_schedule(rows, chain, stagger=0, use_graph=use_graph),
+        "k2_split_stagger2": B.nano_schedule(rows, chain, stagger=2, use_graph=use_graph),
+        "k2_mlp_merged_stagger2": B.nano_schedule(rows, chain, merged_ops=mlp, stagger=2, use_graph=use_graph),
+        "k2_gemms_merged_stagger1": B.nano_schedule(rows, chain, merged_ops=gemms, stagger=1, use_graph=use_graph),
     }
 
 
@@ -58,20 +59,21 @@ def attention_bytes(w):
     read once, K and V (4096 B per position for the Llama-3-8B shape), plus q in and o out."""
     sh = w.shape
     e = 2 if sh.dtype == "bf16" else 4
-    kv = sum(c * (c - q + 1 + c) // 2 if q > 1 else c for q, c in w.seqs)  # causal prefill reads a triangle
-    kv = sum(c for q, c in w.seqs if q == 1) + sum((2 * c - q + 1) * q // 2 for q, c in w.seqs if q > 1)
+    kv = sum(c for _, c in w.seqs)          # a prefill chunk's keys are also read once, not once per query
     return kv * 2 * sh.n_kv * sh.head_dim * e + 2 * w.n_tokens * sh.n_q * sh.head_dim * e
 
 
 def layer_bytes_flops(w):
     sh = w.shape
     e = 2 if sh.dtype == "bf16" else 4
-    params = sh.qkv_rows * sh.hidden + sh.hidden * sh.n_q * sh.head_dim + 3 * sh.inter * sh.hidden
+    attn_params = sh.qkv_rows * sh.hidden + sh.hidden * sh.n_q * sh.head_dim
+    mlp_params = 3 * sh.inter * sh.hidden
     T = w.n_tokens
-    act = T * e * (2 * sh.hidden * 4 + 2 * sh.qkv_rows + 2 * sh.n_q * sh.head_dim + 3 * 2 * sh.inter)
-    kv_pos = sum((2 * c - q + 1) * q // 2 for q, c in w.seqs)
-    byts = params * e + attention_bytes(w) + act
-    flops = 2 * params * T + 4 * sh.n_q * sh.head_dim * kv_pos
+    pairs = sh.top_k if sh.n_experts else 1
+    act = T * e * (2 * sh.hidden * 4 + 2 * sh.qkv_rows + 2 * sh.n_q * sh.head_dim + pairs * 3 * 2 * sh.inter)
+    kv_pos = sum((2 * c - q + 1) * q // 2 for q, c in w.seqs)           # (query, key) pairs
+    byts = (attn_params + mlp_params * max(1, sh.n_experts)) * e + attention_bytes(w) + act   # every expert is read once
+    flops = 2 * (attn_params + mlp_params * pairs) * T + 4 * sh.n_q * sh.head_dim * kv_pos
     return byts * sh.n_layers, flops * sh.n_layers
 
 

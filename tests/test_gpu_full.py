@@ -10,7 +10,7 @@ from oracle import oracle as orc
 from paper_2605_21603_amd import binding as B
 from workloads import gen
 
-from gpu_util import TOL, GpuRun, as_f64, row_rel_err, say
+from gpu_util import TOL, GpuRun, as_f64, row_rel_err, say, stack_tol
 
 pytestmark = pytest.mark.gpu
 
@@ -119,3 +119,54 @@ def test_prefill_decode_mix_full_size():
     pages = data["block_table"][0, :128]
     scale = np.abs(k_ref[pages]).max()
     assert np.abs(k_got[pages] - k_ref[pages]).max() <= TOL[sh.dtype] * scale
+
+
+def test_32_layer_decode_step_full_size():
+    """c5: 32 layers, batch 256, contexts up to 8192 (about 155 GB of cache, generated in
+    device memory).  Sequential, 2 and 4 micro-batches on CU-partitioned streams, all as HIP
+    graphs; outputs and appended cache entries bit for bit; the oracle runs 4 sampled
+    sequences through all 32 layers."""
+    free, total = torch.cuda.mem_get_info()
+    if total < 200 * 2 ** 30:
+        pytest.skip("needs a 288 GB device")
+    say("case c5: generating on the device")
+    w = gen.config("c5")
+    data = gen.generate(w, device="cuda:0", stacked=True)
+    layer = B.DynLayer(B.make_config(w.shape), data["weights"])
+    step = B.DeviceStep(layer, data)
+    st = torch.cuda.Stream()
+    ps = w.shape.page_size
+    tok_page = torch.as_tensor([int(data["block_table"][s, (c - 1) // ps]) for s, (_, c) in enumerate(w.seqs)], device="cuda:0")
+    tok_slot = torch.as_tensor([(c - 1) % ps for _, c in w.seqs], device="cuda:0")
+
+    def run(sched, label):
+        say("case c5: schedule %s" % label)
+        step.y.zero_()
+        torch.cuda.synchronize()
+        with torch.cuda.stream(st):
+            for _ in range(2):
+                layer.forward(step.batch, sched, st)
+        st.synchronize()
+        new_k = step.k_cache[:, tok_page, :, tok_slot, :].cpu()
+        new_v = step.v_cache[:, tok_page, :, :, tok_slot].cpu()
+        return step.y.cpu(), new_k, new_v
+
+    lo, hi = [0x0000FFFF] * 8, [0xFFFF0000] * 8
+    y0, k0, v0 = run(B.sequential(use_graph=True), "sequential")
+    mlp = [B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN]
+    scheds = {"k2 partitioned": B.nano_schedule((0, 128, 256), stagger=2, partitions=[1, 2], cu_masks=[lo, hi], use_graph=True),
+              "k4 partitioned, mlp merged": B.nano_schedule((0, 64, 128, 192, 256), merged_ops=mlp, stagger=1, partitions=[1, 2, 1, 2],
+                                                            streams=[0, 1, 2, 3], cu_masks=[lo, hi], use_graph=True)}
+    for label, sched in scheds.items():
+        y, kk, vv = run(sched, label)
+        assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
+        assert torch.equal(kk.view(torch.uint8), k0.view(torch.uint8)), label
+        assert torch.equal(vv.view(torch.uint8), v0.view(torch.uint8)), label
+    ids = sample_ids(w, 4)
+    say("case c5: oracle on sequences %s through 32 layers" % ids)
+    # the step has already appended this token's keys; the oracle overwrites them with its own
+    w2, d2 = gen.extract_sequences(w, data, ids)
+    y_ref, _, _ = orc.forward(w2, d2)
+    err = row_rel_err(as_f64(y0)[d2["rows"]], y_ref)
+    say("case c5: max rel err %.3e on %d sampled rows" % (err, len(ids)))
+    assert err <= stack_tol(w.shape.dtype, w.shape.n_layers)

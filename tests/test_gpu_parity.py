@@ -83,3 +83,64 @@ def test_forward_rejects_small_workspace_and_aliasing():
     with pytest.raises(B.DynError) as e:
         run.layer.forward(step.batch, B.sequential(), torch.cuda.Stream())
     assert e.value.status == B.DYN_ERR_INVALID_ARG
+
+
+def cu_masks_halves():
+    """Two CU masks that split every XCD's CUs in half (bit i of the mask is CU i of the
+    device-wide enumeration; 256 CUs -> 8 words)."""
+    lo = [0x0000FFFF] * 8
+    hi = [0xFFFF0000] * 8
+    return [lo, hi]
+
+
+@pytest.mark.parametrize("name", ["c2_small", "c5_small"])
+def test_cu_partitioned_streams_and_graph_replay(name):
+    """Micro-batches on CU-masked streams, eager and captured into a HIP graph; the graph is
+    replayed several times with eager forwards and synchronisations in between and every
+    replay must reproduce the sequential bits."""
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    k = len(w.nano_rows) - 1
+    parts = [1 + (b % 2) for b in range(k)]
+    for use_graph in (False, True):
+        sched = B.nano_schedule(w.nano_rows, stagger=1, partitions=parts, cu_masks=cu_masks_halves(), use_graph=use_graph)
+        say("case %s masked partitions graph=%s" % (name, use_graph))
+        step = B.DeviceStep(run.layer, data)
+        st = torch.cuda.Stream()
+        for rep in range(4):
+            step.y.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(st):
+                run.layer.forward(step.batch, sched, st)
+            st.synchronize()
+            assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8)), (use_graph, rep)
+            # eager work of the program itself between replays
+            y1, _, _ = run.run(B.sequential())
+            assert torch.equal(y1.view(torch.uint8), y0.view(torch.uint8))
+        assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8))
+    seq_graph = B.sequential(use_graph=True)
+    y2, k2, _ = run.run(seq_graph, repeat=3)
+    assert torch.equal(y2.view(torch.uint8), y0.view(torch.uint8))
+
+
+def test_profiling_reports_every_dispatch():
+    w = gen.config("c2_small")
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    run.layer.set_profiling(True)
+    sched = B.nano_schedule(w.nano_rows, stagger=1)
+    run.run(sched)
+    recs = run.layer.slot_times()
+    run.layer.set_profiling(False)
+    assert len(recs) == len(sched.slots)
+    for r, s in zip(recs, sched.slots):
+        assert (r["op"], r["nano"], r["n_nano"], r["stream"]) == tuple(s[:4])
+        assert r["start_ms"] <= r["main_start_ms"] <= r["main_stop_ms"] <= r["stop_ms"]
+    with pytest.raises(B.DynError):          # profiling is for eager schedules
+        run.layer.set_profiling(True)
+        try:
+            run.run(B.sequential(use_graph=True))
+        finally:
+            run.layer.set_profiling(False)

@@ -194,12 +194,13 @@ def layer_weights(sh: LayerShape, gen: torch.Generator, device="cpu") -> Dict[st
     return wts
 
 
-def generate(w: Workload, device="cpu") -> Dict[str, object]:
+def generate(w: Workload, device="cpu", stacked: bool = False) -> Dict[str, object]:
     """All tensors of one step: per-layer weights, per-layer caches, x and the metadata.
 
     With device="cpu" the torch CPU generator is used; a GPU device draws directly in
     device memory (needed only for the 32-layer configuration whose caches exceed host
-    memory); the two do not produce the same numbers."""
+    memory); the two do not produce the same numbers.  stacked=True returns each cache as
+    one [n_layers, ...] tensor filled layer by layer instead of a list of layer tensors."""
     sh = w.shape
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
@@ -207,12 +208,50 @@ def generate(w: Workload, device="cpu") -> Dict[str, object]:
     out: Dict[str, object] = dict(md)
     out["weights"] = [layer_weights(sh, gen, device) for _ in range(sh.n_layers)]
     out["x"] = _normal(gen, (w.n_tokens, sh.hidden), 1.0, sh.dtype, device)
-    kc, vc = [], []
-    for _ in range(sh.n_layers):
-        kc.append(_normal(gen, (md["n_pages"], sh.n_kv, sh.page_size, sh.head_dim), 1.0, sh.dtype, device))
-        vc.append(_normal(gen, (md["n_pages"], sh.n_kv, sh.head_dim, sh.page_size), 1.0, sh.dtype, device))
+    k_shape = (md["n_pages"], sh.n_kv, sh.page_size, sh.head_dim)
+    v_shape = (md["n_pages"], sh.n_kv, sh.head_dim, sh.page_size)
+    if stacked:
+        kc = torch.empty((sh.n_layers,) + k_shape, dtype=sh.torch_dtype, device=device)
+        vc = torch.empty((sh.n_layers,) + v_shape, dtype=sh.torch_dtype, device=device)
+        chunk = max(1, md["n_pages"] // 8)          # keeps the fp32 staging buffers small
+        for l in range(sh.n_layers):
+            for p0 in range(0, md["n_pages"], chunk):
+                p1 = min(md["n_pages"], p0 + chunk)
+                kc[l, p0:p1] = _normal(gen, (p1 - p0,) + k_shape[1:], 1.0, sh.dtype, device)
+                vc[l, p0:p1] = _normal(gen, (p1 - p0,) + v_shape[1:], 1.0, sh.dtype, device)
+    else:
+        kc, vc = [], []
+        for _ in range(sh.n_layers):
+            kc.append(_normal(gen, k_shape, 1.0, sh.dtype, device))
+            vc.append(_normal(gen, v_shape, 1.0, sh.dtype, device))
     out["k_cache"], out["v_cache"] = kc, vc
     return out
+
+
+def extract_sequences(w: Workload, data: Dict[str, object], seq_ids: List[int]) -> Tuple[Workload, Dict[str, object]]:
+    """Host copy of the same step restricted to some sequences, with their cache pages
+    gathered into small per-layer caches and the block table renumbered.  For workloads
+    generated in device memory whose caches do not fit on the host."""
+    ps = w.shape.page_size
+    w2 = dataclasses.replace(w, name=w.name + "_sub", seqs=tuple(w.seqs[s] for s in seq_ids), nano_rows=())
+    md = metadata(w2)
+    q_start = data["q_start"]
+    rows = np.concatenate([np.arange(q_start[s], q_start[s + 1]) for s in seq_ids])
+    pages, bt = [], np.zeros((len(seq_ids), md["max_pages_per_seq"]), dtype=np.int32)
+    for i, s in enumerate(seq_ids):
+        n = (w.seqs[s][1] + ps - 1) // ps
+        bt[i, :n] = np.arange(len(pages), len(pages) + n)
+        pages.extend(int(p) for p in data["block_table"][s, :n])
+    idx = torch.as_tensor(pages, dtype=torch.long, device=data["x"].device)
+    d2: Dict[str, object] = dict(md)
+    d2["block_table"] = bt
+    d2["n_pages"] = len(pages)
+    d2["rows"] = rows
+    d2["x"] = data["x"][torch.as_tensor(rows, dtype=torch.long, device=data["x"].device)].cpu().contiguous()
+    d2["weights"] = [{k: v.cpu() for k, v in lw.items()} for lw in data["weights"]]
+    d2["k_cache"] = [data["k_cache"][l][idx].cpu().contiguous() for l in range(w.shape.n_layers)]
+    d2["v_cache"] = [data["v_cache"][l][idx].cpu().contiguous() for l in range(w.shape.n_layers)]
+    return w2, d2
 
 
 def sub_batch(w: Workload, data: Dict[str, object], seq_ids: List[int]) -> Tuple[Workload, Dict[str, object]]:
