@@ -27,7 +27,7 @@ hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
-constexpr int kPersistentGroups = 256;   // one 8-wave workgroup for each of the 256 CUs
+constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of the 256 CUs
 
 // Work list: one entry per (token, chunk) that really exists, built on the device from the
 // positions (contexts differ by 8x inside a batch, so a dense token x max_chunks grid would
@@ -61,11 +61,20 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
     if (threadIdx.x == 0) plan[0] = base;
 }
 
-// Persistent workgroups of 8 waves, one per CU.  Workgroup b owns the (entry, kv head) pairs
-// b, b + gridDim.x, ...; its waves take them from an LDS counter as they become free, which
-// evens out the ragged last chunks.  Which wave computes a pair has no influence on its
-// result.
-__global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
+// Persistent waves, eight per CU: wave w of the launch takes (entry, kv head) pairs w,
+// w + n_waves, ...  A pair is walked two tiles (four pages) at a time through two register
+// buffers, and when a pair runs out of tiles the free buffer is refilled with the first tile
+// of the wave's next pair - whose indices were fetched while this pair was being multiplied -
+// so the stream of loads never drains at a pair boundary and the three dependent lookups
+// (work list -> position / sequence -> block table) are off the critical path.
+struct AttnItem {
+    int t, n_keys, lp_first, seq_pages, n_pair;   // token row, keys it attends, first logical page of the chunk,
+                                                  // pages of the sequence, tile pairs to walk
+    const int32_t *bt;                            // block-table row of the token's sequence
+    size_t pidx;                                  // partial slot of head g*G: (t * n_q + g * G) * max_chunks + c
+};
+
+__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
                                                            const int32_t *__restrict__ seq_of_token,
                                                            const int32_t *__restrict__ pos_of_token,
                                                            const int32_t *__restrict__ block_table,
@@ -75,55 +84,41 @@ __global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restr
                                                            AttnShape sh, const int32_t *__restrict__ plan) {
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_items = plan[0] * sh.n_kv;
-    const int ct = sh.chunk_pages * PS;
+    const int n_waves = gridDim.x * 4;
     const int G = sh.n_q / sh.n_kv;
     const int lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
     const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
-    (void)wave;
-    __shared__ int next_slot;
-    if (threadIdx.x == 0) next_slot = 0;
-    __syncthreads();
-    auto claim = [&]() {
-        int v = 0;
-        if (lane == 0) v = atomicAdd(&next_slot, 1);
-        return blockIdx.x + __builtin_amdgcn_readfirstlane(v) * gridDim.x;
-    };
-    int item = claim();
-  while (item < n_items) {
-    const int g = item % sh.n_kv;
-    const int t = plan[2 + 2 * (item / sh.n_kv)], c = plan[3 + 2 * (item / sh.n_kv)];
-    const int n_keys = pos_of_token[t] + 1;
-    const int j0 = c * ct;
-    const int seq_pages = (n_keys + PS - 1) / PS;                 // pages this token may read
-    const int lp0 = c * sh.chunk_pages;                           // first logical page of the chunk
-    const int n_pg = min(sh.chunk_pages, seq_pages - lp0);
-    const int n_tiles = (n_pg + TILE_PAGES - 1) / TILE_PAGES;
-    const int32_t *bt = block_table + (size_t)seq_of_token[t] * sh.max_pages_per_seq;
 
-    // B operands of the score product: q of head g*G + lr (zero for lr >= G)
-    bf16x8 qb[4];
-    {
-        const bf16_t *q = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * HD) + (g * G + min(lr, G - 1)) * HD + 8 * lq;
-#pragma unroll
-        for (int ks = 0; ks < 4; ++ks) {
-            u32x4 v = *reinterpret_cast<const u32x4 *>(q + ks * 32);
-            if (lr >= G) v = u32x4{0u, 0u, 0u, 0u};
-            qb[ks] = __builtin_bit_cast(bf16x8, v);
-        }
-    }
+    int item = blockIdx.x * 4 + wave;
+    if (item >= n_items) return;
+
+    auto fetch_item = [&](int it, int &g_out) {
+        AttnItem m;
+        const int g = it % sh.n_kv, e = it / sh.n_kv;
+        const int c = plan[3 + 2 * e];
+        m.t = plan[2 + 2 * e];
+        m.n_keys = pos_of_token[m.t] + 1;
+        m.seq_pages = (m.n_keys + PS - 1) / PS;
+        m.lp_first = c * sh.chunk_pages;
+        const int n_pg = min(sh.chunk_pages, m.seq_pages - m.lp_first);
+        m.n_pair = (n_pg + 2 * TILE_PAGES - 1) / (2 * TILE_PAGES);          // a trailing odd tile is walked masked
+        m.bt = block_table + (size_t)seq_of_token[m.t] * sh.max_pages_per_seq;
+        m.pidx = ((size_t)m.t * sh.n_q + g * G) * sh.max_chunks + c;
+        g_out = g;
+        return m;
+    };
 
     u32x4 kreg[2][TILE_PAGES][4];
     u32x2 vreg[2][TILE_PAGES][8];
-    f32x4 acc[8];
-#pragma unroll
-    for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-    float m_run = -INFINITY, l_run = 0.f;
+    bf16x8 qb[4], qn[4];
 
-#define DYN_ATTN_LOAD(B, TL)                                                                                      \
+    // tile TL of item M into register buffer B; page indices past the sequence's last page
+    // are clamped (their scores are masked, the loads hit L2)
+#define DYN_ATTN_LOAD(B, M, GG, TL)                                                                               \
     {                                                                                                             \
         _Pragma("unroll") for (int pi = 0; pi < TILE_PAGES; ++pi) {                                               \
-            const int lp = min(lp0 + (TL) * TILE_PAGES + pi, seq_pages - 1);                                      \
-            const size_t pg = (size_t)bt[lp] * sh.n_kv + g;                                                       \
+            const int lp = min((M).lp_first + (TL) * TILE_PAGES + pi, (M).seq_pages - 1);                         \
+            const size_t pg = (size_t)(M).bt[lp] * sh.n_kv + (GG);                                                \
             const bf16_t *kp = k_cache + (pg * PS + lr) * HD + 8 * lq;                                            \
             const bf16_t *vp = v_cache + (pg * HD + lr) * PS + 4 * lq;                                            \
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                      \
@@ -132,7 +127,16 @@ __global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restr
                 vreg[B][pi][dt] = *reinterpret_cast<const u32x2 *>(vp + dt * 16 * PS);                            \
         }                                                                                                         \
     }
-
+    // B operands of the score product: q of head g*G + lr (zero for lr >= G)
+#define DYN_ATTN_LOAD_Q(DST, M, GG)                                                                               \
+    {                                                                                                             \
+        const bf16_t *q = qkv + (size_t)(M).t * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + min(lr, G - 1)) * HD + 8 * lq; \
+        _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                        \
+            u32x4 v = *reinterpret_cast<const u32x4 *>(q + ks * 32);                                              \
+            if (lr >= G) v = u32x4{0u, 0u, 0u, 0u};                                                               \
+            DST[ks] = __builtin_bit_cast(bf16x8, v);                                                              \
+        }                                                                                                         \
+    }
 #define DYN_ATTN_COMPUTE(B, TL)                                                                                   \
     {                                                                                                             \
         f32x4 sv[TILE_PAGES];                                                                                     \
@@ -142,16 +146,16 @@ __global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restr
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                      \
                 s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[B][pi][ks]), qb[ks],  \
                                                             s, 0, 0, 0);                                          \
-            const int jb = j0 + ((TL) * TILE_PAGES + pi) * PS + 4 * lq;                                           \
+            const int jb = (cur.lp_first + (TL) * TILE_PAGES + pi) * PS + 4 * lq;                                 \
             _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                                       \
-                s[r] = (jb + r < n_keys) ? s[r] * sscale : -INFINITY;                                             \
+                s[r] = (jb + r < cur.n_keys) ? s[r] * sscale : -INFINITY;                                         \
                 mx = fmaxf(mx, s[r]);                                                                             \
             }                                                                                                     \
             sv[pi] = s;                                                                                           \
         }                                                                                                         \
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                                                   \
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                   \
-        const float m_new = fmaxf(m_run, mx);                                                                     \
+        const float m_new = fmaxf(m_run, mx);          /* finite: a pair's first tile has a valid position */      \
         const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);                                                \
         m_run = m_new;                                                                                            \
         l_run *= alpha;                                                                                           \
@@ -163,7 +167,7 @@ __global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restr
             const u32x2 pw = __builtin_bit_cast(u32x2, pb);                                                       \
             l_run += (__uint_as_float(pw[0] << 16) + __uint_as_float(pw[0] & 0xffff0000u)) +                      \
                      (__uint_as_float(pw[1] << 16) + __uint_as_float(pw[1] & 0xffff0000u));                       \
-            const int nvalid = n_keys - (j0 + ((TL) * TILE_PAGES + pi) * PS) - 4 * lq;                            \
+            const int nvalid = cur.n_keys - (cur.lp_first + (TL) * TILE_PAGES + pi) * PS - 4 * lq;                \
             _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) {                                                    \
                 u32x2 vv = vreg[B][pi][dt];                                                                       \
                 if (nvalid < 4) { /* positions past the token's own: keep stale cache bits out of 0 * x */      \
@@ -176,47 +180,61 @@ __global__ __launch_bounds__(512, 1) void attn_mfma_kernel(const bf16_t *__restr
         }                                                                                                         \
     }
 
-    // Two register buffers; the steady-state loop has no conditional loads, so the compiler
-    // counts the loads still in flight exactly and a tile is multiplied while the next one
-    // is on its way.
-    DYN_ATTN_LOAD(0, 0)
-    int tl = 0;
-    for (; tl + 2 < n_tiles; tl += 2) {
-        // scheduling barriers: keep each prefetch ahead of the multiply it overlaps
-        DYN_ATTN_LOAD(1, tl + 1)
-        __builtin_amdgcn_sched_barrier(0);
-        DYN_ATTN_COMPUTE(0, tl)
-        __builtin_amdgcn_sched_barrier(0);
-        DYN_ATTN_LOAD(0, tl + 2)
-        __builtin_amdgcn_sched_barrier(0);
-        DYN_ATTN_COMPUTE(1, tl + 1)
-        __builtin_amdgcn_sched_barrier(0);
-    }
-    if (tl + 2 == n_tiles) {
-        DYN_ATTN_LOAD(1, tl + 1)
-        __builtin_amdgcn_sched_barrier(0);
-        DYN_ATTN_COMPUTE(0, tl)
-        DYN_ATTN_COMPUTE(1, tl + 1)
-    } else {
-        DYN_ATTN_COMPUTE(0, tl)
+    int g_cur = 0, g_nxt = 0;
+    AttnItem cur = fetch_item(item, g_cur);
+    DYN_ATTN_LOAD_Q(qb, cur, g_cur)
+    DYN_ATTN_LOAD(0, cur, g_cur, 0)
+    while (true) {
+        const int next_item = item + n_waves;
+        const bool more = next_item < n_items;
+        // the wave's last pair "prefetches" itself again: harmless loads instead of a conditional branch
+        AttnItem nxt = fetch_item(more ? next_item : item, g_nxt);
+        f32x4 acc[8];
+#pragma unroll
+        for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        float m_run = -INFINITY, l_run = 0.f;
+
+        for (int pr = 0; pr < cur.n_pair; ++pr) {
+            const bool last = pr + 1 == cur.n_pair;
+            // buffer 0 holds tile 2 pr (loaded or in flight); scheduling barriers keep each
+            // prefetch ahead of the multiply it overlaps
+            DYN_ATTN_LOAD(1, cur, g_cur, 2 * pr + 1)
+            __builtin_amdgcn_sched_barrier(0);
+            DYN_ATTN_COMPUTE(0, 2 * pr)
+            __builtin_amdgcn_sched_barrier(0);
+            {   // refill buffer 0: this pair's next tile, or tile 0 of the wave's next pair
+                const AttnItem src = last ? nxt : cur;
+                const int gg = last ? g_nxt : g_cur, tile = last ? 0 : 2 * pr + 2;
+                DYN_ATTN_LOAD_Q(qn, nxt, g_nxt)
+                DYN_ATTN_LOAD(0, src, gg, tile)
+            }
+            __builtin_amdgcn_sched_barrier(0);
+            DYN_ATTN_COMPUTE(1, 2 * pr + 1)
+            __builtin_amdgcn_sched_barrier(0);
+        }
+
+        l_run += __shfl_xor(l_run, 16, 64);
+        l_run += __shfl_xor(l_run, 32, 64);
+        if (lr < G) {
+            const size_t pidx = cur.pidx + (size_t)lr * sh.max_chunks;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt)
+                *reinterpret_cast<f32x4 *>(part_o + pidx * HD + dt * 16 + 4 * lq) = acc[dt];
+            if (lq == 0) {
+                part_ml[pidx * 2] = m_run;
+                part_ml[pidx * 2 + 1] = l_run;
+            }
+        }
+        if (!more) break;
+        item = next_item;
+        cur = nxt;
+        g_cur = g_nxt;
+#pragma unroll
+        for (int ks = 0; ks < 4; ++ks) qb[ks] = qn[ks];
     }
 #undef DYN_ATTN_LOAD
+#undef DYN_ATTN_LOAD_Q
 #undef DYN_ATTN_COMPUTE
-
-    l_run += __shfl_xor(l_run, 16, 64);
-    l_run += __shfl_xor(l_run, 32, 64);
-    if (lr < G) {
-        const size_t pidx = ((size_t)t * sh.n_q + g * G + lr) * sh.max_chunks + c;
-#pragma unroll
-        for (int dt = 0; dt < 8; ++dt)
-            *reinterpret_cast<f32x4 *>(part_o + pidx * HD + dt * 16 + 4 * lq) = acc[dt];
-        if (lq == 0) {
-            part_ml[pidx * 2] = m_run;
-            part_ml[pidx * 2 + 1] = l_run;
-        }
-    }
-    item = claim();
-  }   // item loop
 }
 
 hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *seq_of_token,
@@ -241,8 +259,8 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
     const long max_items = (long)rows * sh.n_kv * sh.max_chunks;
-    const int grid = (int)((max_items + 7) / 8 < kPersistentGroups ? (max_items + 7) / 8 : kPersistentGroups);
-    hipLaunchKernelGGL(attn_mfma_kernel, dim3(grid), dim3(512), 0, s, (const bf16_t *)qkv, seq_of_token,
+    const int grid = (int)((max_items + 3) / 4 < kPersistentGroups ? (max_items + 3) / 4 : kPersistentGroups);
+    hipLaunchKernelGGL(attn_mfma_kernel, dim3(grid), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
                        plan);
     e = hipGetLastError();
