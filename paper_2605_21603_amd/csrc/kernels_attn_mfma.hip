@@ -29,18 +29,33 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
 constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of the 256 CUs
 
-// Work list: one entry per (token, chunk) that really exists, built on the device from the
-// positions (contexts differ by 8x inside a batch, so a dense token x max_chunks grid would
-// be mostly empty workgroups).  plan[0] = number of entries, entry i at plan[2 + 2 i].
-__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ pos_of_token, int rows, int ct,
-                                                        int32_t *__restrict__ plan) {
+// Work list, built on the device from the positions (contexts differ by 8x inside a batch, so
+// a dense token x max_chunks grid would be mostly empty workgroups).  Tokens of one sequence
+// whose positions fall in the same aligned block of TG = 16 / G positions form a query group
+// (a decode token is a group of one; a prefill chunk yields groups of TG): a wave serves all
+// G * TG (token, head) columns of a group from one pass over the keys.  One entry per
+// (group, chunk) that exists: plan[0] = number of entries, entry i = (first token row,
+// chunk | tokens << 20) at plan[2 + 2 i].
+__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
+                                                        const int32_t *__restrict__ pos_of_token, int rows, int ct,
+                                                        int tg, int32_t *__restrict__ plan) {
     __shared__ int scan[256];
     __shared__ int base;
     if (threadIdx.x == 0) base = 0;
     __syncthreads();
     for (int t0 = 0; t0 < rows; t0 += 256) {
         const int t = t0 + threadIdx.x;
-        const int nc = t < rows ? (pos_of_token[t] + ct) / ct : 0;
+        int nc = 0, n_tok = 0;
+        if (t < rows) {
+            const int s = seq_of_token[t], blk = pos_of_token[t] / tg;
+            const bool leader = t == 0 || seq_of_token[t - 1] != s || pos_of_token[t - 1] / tg != blk;
+            if (leader) {
+                n_tok = 1;
+                while (n_tok < tg && t + n_tok < rows && seq_of_token[t + n_tok] == s && pos_of_token[t + n_tok] / tg == blk)
+                    ++n_tok;
+                nc = (pos_of_token[t + n_tok - 1] + ct) / ct;        // chunks the group's last token reaches
+            }
+        }
         scan[threadIdx.x] = nc;
         __syncthreads();
         for (int off = 1; off < 256; off <<= 1) {           // inclusive Hillis-Steele scan
@@ -52,7 +67,7 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
         const int start = base + scan[threadIdx.x] - nc;
         for (int c = 0; c < nc; ++c) {
             plan[2 + 2 * (start + c)] = t;
-            plan[3 + 2 * (start + c)] = c;
+            plan[3 + 2 * (start + c)] = c | (n_tok << 20);
         }
         __syncthreads();
         if (threadIdx.x == 255) base += scan[255];
@@ -68,10 +83,10 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
 // so the stream of loads never drains at a pair boundary and the three dependent lookups
 // (work list -> position / sequence -> block table) are off the critical path.
 struct AttnItem {
-    int t, n_keys, lp_first, seq_pages, n_pair;   // token row, keys it attends, first logical page of the chunk,
-                                                  // pages of the sequence, tile pairs to walk
-    const int32_t *bt;                            // block-table row of the token's sequence
-    size_t pidx;                                  // partial slot of head g*G: (t * n_q + g * G) * max_chunks + c
+    int t, c, n_tok;                  // first token row of the query group, chunk, tokens in the group
+    int n_keys, lp_first, seq_pages;  // keys the group's last token attends, first logical page of the chunk, its pages
+    int n_pair;                       // tile pairs to walk
+    const int32_t *bt;                // block-table row of the group's sequence
 };
 
 __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
@@ -87,6 +102,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
     const int n_waves = gridDim.x * 4;
     const int G = sh.n_q / sh.n_kv;
     const int lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
+    const int col_tok = lr / G, col_head = lr % G;   // MFMA column lr = (token col_tok of the group, q head col_head)
     const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
 
     int item = blockIdx.x * 4 + wave;
@@ -95,15 +111,16 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
     auto fetch_item = [&](int it, int &g_out) {
         AttnItem m;
         const int g = it % sh.n_kv, e = it / sh.n_kv;
-        const int c = plan[3 + 2 * e];
+        const int packed = plan[3 + 2 * e];
+        m.c = packed & 0xfffff;
+        m.n_tok = packed >> 20;
         m.t = plan[2 + 2 * e];
-        m.n_keys = pos_of_token[m.t] + 1;
+        m.n_keys = pos_of_token[m.t + m.n_tok - 1] + 1;
         m.seq_pages = (m.n_keys + PS - 1) / PS;
-        m.lp_first = c * sh.chunk_pages;
+        m.lp_first = m.c * sh.chunk_pages;
         const int n_pg = min(sh.chunk_pages, m.seq_pages - m.lp_first);
         m.n_pair = (n_pg + 2 * TILE_PAGES - 1) / (2 * TILE_PAGES);          // a trailing odd tile is walked masked
         m.bt = block_table + (size_t)seq_of_token[m.t] * sh.max_pages_per_seq;
-        m.pidx = ((size_t)m.t * sh.n_q + g * G) * sh.max_chunks + c;
         g_out = g;
         return m;
     };
@@ -127,13 +144,17 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
                 vreg[B][pi][dt] = *reinterpret_cast<const u32x2 *>(vp + dt * 16 * PS);                            \
         }                                                                                                         \
     }
-    // B operands of the score product: q of head g*G + lr (zero for lr >= G)
-#define DYN_ATTN_LOAD_Q(DST, M, GG)                                                                               \
+    // B operands of the score product: column lr = q of token t + col_tok, head g*G + col_head
+    // (zero for columns past the group); NK = keys that column attends (0 for a dead column)
+#define DYN_ATTN_LOAD_Q(DST, NK, M, GG)                                                                           \
     {                                                                                                             \
-        const bf16_t *q = qkv + (size_t)(M).t * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + min(lr, G - 1)) * HD + 8 * lq; \
+        const bool live = col_tok < (M).n_tok;                                                                    \
+        const int tq = (M).t + (live ? col_tok : 0);                                                              \
+        NK = live ? pos_of_token[tq] + 1 : 0;                                                                     \
+        const bf16_t *q = qkv + (size_t)tq * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + col_head) * HD + 8 * lq; \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                        \
             u32x4 v = *reinterpret_cast<const u32x4 *>(q + ks * 32);                                              \
-            if (lr >= G) v = u32x4{0u, 0u, 0u, 0u};                                                               \
+            if (!live) v = u32x4{0u, 0u, 0u, 0u};                                                                 \
             DST[ks] = __builtin_bit_cast(bf16x8, v);                                                              \
         }                                                                                                         \
     }
@@ -148,21 +169,22 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
                                                             s, 0, 0, 0);                                          \
             const int jb = (cur.lp_first + (TL) * TILE_PAGES + pi) * PS + 4 * lq;                                 \
             _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                                       \
-                s[r] = (jb + r < cur.n_keys) ? s[r] * sscale : -INFINITY;                                         \
+                s[r] = (jb + r < nk_cur) ? s[r] * sscale : -INFINITY;                                             \
                 mx = fmaxf(mx, s[r]);                                                                             \
             }                                                                                                     \
             sv[pi] = s;                                                                                           \
         }                                                                                                         \
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                                                   \
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                   \
-        const float m_new = fmaxf(m_run, mx);          /* finite: a pair's first tile has a valid position */      \
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_new);                                                \
+        const float m_new = fmaxf(m_run, mx);                                                                     \
+        const float m_ref = m_new == -INFINITY ? 0.f : m_new;   /* a column with no key yet stays empty */        \
+        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);                                                \
         m_run = m_new;                                                                                            \
         l_run *= alpha;                                                                                           \
         _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;                                        \
         _Pragma("unroll") for (int pi = 0; pi < TILE_PAGES; ++pi) {                                               \
             f32x4 p;                                                                                              \
-            _Pragma("unroll") for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(sv[pi][r] - m_new);       \
+            _Pragma("unroll") for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(sv[pi][r] - m_ref);       \
             const bf16x4 pb = __builtin_convertvector(p, bf16x4);                                                 \
             const u32x2 pw = __builtin_bit_cast(u32x2, pb);                                                       \
             l_run += (__uint_as_float(pw[0] << 16) + __uint_as_float(pw[0] & 0xffff0000u)) +                      \
@@ -180,9 +202,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
         }                                                                                                         \
     }
 
-    int g_cur = 0, g_nxt = 0;
+    int g_cur = 0, g_nxt = 0, nk_cur = 0, nk_nxt = 0;
     AttnItem cur = fetch_item(item, g_cur);
-    DYN_ATTN_LOAD_Q(qb, cur, g_cur)
+    DYN_ATTN_LOAD_Q(qb, nk_cur, cur, g_cur)
     DYN_ATTN_LOAD(0, cur, g_cur, 0)
     while (true) {
         const int next_item = item + n_waves;
@@ -205,7 +227,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
             {   // refill buffer 0: this pair's next tile, or tile 0 of the wave's next pair
                 const AttnItem src = last ? nxt : cur;
                 const int gg = last ? g_nxt : g_cur, tile = last ? 0 : 2 * pr + 2;
-                DYN_ATTN_LOAD_Q(qn, nxt, g_nxt)
+                DYN_ATTN_LOAD_Q(qn, nk_nxt, nxt, g_nxt)
                 DYN_ATTN_LOAD(0, src, gg, tile)
             }
             __builtin_amdgcn_sched_barrier(0);
@@ -215,8 +237,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
 
         l_run += __shfl_xor(l_run, 16, 64);
         l_run += __shfl_xor(l_run, 32, 64);
-        if (lr < G) {
-            const size_t pidx = cur.pidx + (size_t)lr * sh.max_chunks;
+        if (nk_cur > cur.c * sh.chunk_pages * PS) {       // the chunk exists for this column's token
+            const size_t pidx = ((size_t)(cur.t + col_tok) * sh.n_q + g_cur * G + col_head) * sh.max_chunks + cur.c;
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt)
                 *reinterpret_cast<f32x4 *>(part_o + pidx * HD + dt * 16 + 4 * lq) = acc[dt];
@@ -229,6 +251,7 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
         item = next_item;
         cur = nxt;
         g_cur = g_nxt;
+        nk_cur = nk_nxt;
 #pragma unroll
         for (int ks = 0; ks < 4; ++ks) qb[ks] = qn[ks];
     }
@@ -254,7 +277,8 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     if (!attention_mfma_supported(dtype, sh))
         return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
                                         part_o, part_ml, sh, rows, s, mid);
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, pos_of_token, rows, sh.chunk_pages * PS, plan);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
+                       16 / (sh.n_q / sh.n_kv), plan);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;

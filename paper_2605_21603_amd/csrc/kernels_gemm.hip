@@ -77,9 +77,18 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // l%16, 8 consecutive k at 8*(l/16)) touch disjoint banks.  Waves sit 2 x 2 on the tile:
 // 64 W rows x MT/2 X rows each.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
 constexpr int BN = 128, BK = 64, ROWB = BK * 2 + 16, RING = 4;
+#ifndef DYN_OCC2_TILES
+#define DYN_OCC2_TILES 2     // row tiles from which the two-workgroups-per-CU build is used
+#endif
 
-template <int MT>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict__ X, int ldx,
+// INREG: one workgroup walks all S planes of its tile and adds the plane sums in registers
+// (same order, same bits as the plane buffers + gemm_reduce_kernel) - for many-row launches,
+// where there are enough tiles to fill the chip without spreading planes over workgroups and
+// the fp32 plane traffic would cost more than the weights.
+// OCC2: compile for two workgroups per CU (256 VGPRs) - pays when the launch is bound by
+// the matrix cores (many row tiles), costs a few spills that hurt when it is bound by memory.
+template <int MT, bool INREG, bool OCC2>
+__global__ __launch_bounds__(256, OCC2 ? 2 : 1) void gemm_bf16_kernel(const bf16_t *__restrict__ X, int ldx,
                                                         const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
                                                         bf16_t *__restrict__ Y, float *__restrict__ P,
                                                         size_t plane_stride, int M, int N, int K, int S, GemmGroups gr) {
@@ -94,8 +103,9 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     const int m_tile = v % m_tiles;
     int ns = (v / m_tiles) * 8 + u;
     const int32_t *list = nullptr;
+    const int SG = INREG ? 1 : S;                      // planes spread over the grid
     if (gr.n_groups) {                                 // grouped: (expert, n tile, plane); rows come from the expert's list
-        const int per_group = (N / BN) * S;
+        const int per_group = (N / BN) * SG;
         if (ns >= per_group * gr.n_groups) return;
         const int e = ns / per_group;
         ns -= e * per_group;
@@ -103,11 +113,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
         if (m_tile * MT >= M) return;
         list = gr.lists + (size_t)e * gr.cap;
         W += (size_t)e * gr.w_stride;
-    } else if (ns >= (N / BN) * S) {
+    } else if (ns >= (N / BN) * SG) {
         return;
     }
-    const int n_tile = ns / S, sp = ns % S;
-    const int Kp = K / S, kbase = sp * Kp, n_stage = Kp / BK;
+    const int n_tile = ns / SG, sp = ns % SG;
+    const int Kp = K / S, kbase = INREG ? 0 : sp * Kp, n_stage = (INREG ? K : Kp) / BK;
+    const int plane_stages = Kp / BK;
     const int n0 = n_tile * BN, m0 = m_tile * MT;
     const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
     const int lr = lane & 15, lq = lane >> 4, wn = wave & 1, wm = wave >> 1;
@@ -124,11 +135,22 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
     const int loff = prow * ROWB + pcol * 16;
 
     u32x4 rw[RING][4], rx[RING][XP];
-    f32x4 acc[4][NB];
+    f32x4 acc[4][NB], total[INREG ? 4 : 1][INREG ? NB : 1];
 #pragma unroll
     for (int a = 0; a < 4; ++a)
 #pragma unroll
-        for (int b = 0; b < NB; ++b) acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        for (int b = 0; b < NB; ++b) {
+            acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+            if (INREG) total[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
+    // a plane ends on a multiple of RING stages: fold its sum into the total, start the next from zero
+#define DYN_GEMM_PLANE_END(ST_DONE)                                                                      \
+    if (INREG && (ST_DONE) % plane_stages == 0) {                                                        \
+        _Pragma("unroll") for (int a = 0; a < 4; ++a) _Pragma("unroll") for (int b = 0; b < NB; ++b) {   \
+            total[a][b] += acc[a][b];                                                                    \
+            acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};                                                       \
+        }                                                                                                \
+    }
 
 #define DYN_GEMM_FETCH(SLOT, ST)                                                                         \
     {                                                                                                    \
@@ -177,11 +199,14 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
         DYN_GEMM_STAGE(1, true, true)
         DYN_GEMM_STAGE(2, true, true)
         DYN_GEMM_STAGE(3, true, true)
+        DYN_GEMM_PLANE_END(st0 + RING)
     }
     DYN_GEMM_STAGE(0, true, true)
     DYN_GEMM_STAGE(1, false, true)
     DYN_GEMM_STAGE(2, false, true)
     DYN_GEMM_STAGE(3, false, false)
+    DYN_GEMM_PLANE_END(st0 + RING)
+#undef DYN_GEMM_PLANE_END
 #undef DYN_GEMM_STAGE
 #undef DYN_GEMM_MMA
 #undef DYN_GEMM_PARK
@@ -195,8 +220,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t *__restrict
             const int n = n0 + wn * 64 + a * 16 + 4 * lq;
             if (m >= M) continue;
             const size_t orow = list ? list[m] : m;
-            f32x4 o = acc[a][b];
-            if (S == 1 && !gr.force_planes) {
+            f32x4 o = INREG ? total[a][b] : acc[a][b];
+            if ((S == 1 || INREG) && !gr.force_planes) {
                 if (R) {
                     const u32x2 rv = *reinterpret_cast<const u32x2 *>(R + orow * N + n);
                     o[0] += bf2f(rv[0] & 0xffff); o[1] += bf2f(rv[0] >> 16);
@@ -265,17 +290,20 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     const int S = gemm_split_k(dtype, N, K);
     const int MT = rows <= 64 ? 64 : 128;
     const int m_tiles = (rows + MT - 1) / MT;
-    const int ns = (N / BN) * S;
+    const bool inreg = S > 1 && (N / BN) * m_tiles >= 256;      // enough tiles without spreading the planes
+    const int ns = (N / BN) * (inreg ? 1 : S);
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
-    if (MT == 64)
-        hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none);
-    else
-        hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none);
+#define DYN_GEMM_LAUNCH(...)                                                                                        \
+    hipLaunchKernelGGL((gemm_bf16_kernel<__VA_ARGS__>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx,        \
+                       (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none)
+    if (inreg) DYN_GEMM_LAUNCH(128, true, false);
+    else if (MT == 64) DYN_GEMM_LAUNCH(64, false, false);
+    else if (m_tiles >= DYN_OCC2_TILES) DYN_GEMM_LAUNCH(128, false, true);
+    else DYN_GEMM_LAUNCH(128, false, false);
+#undef DYN_GEMM_LAUNCH
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
-    if (e != hipSuccess || S == 1) return e;
+    if (e != hipSuccess || S == 1 || inreg) return e;
     const size_t n_vec = (size_t)rows * N / 4;
     const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
     hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
@@ -307,10 +335,10 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
     const int ns = (N / BN) * S * gr.n_groups;
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
     if (MT == 64)
-        hipLaunchKernelGGL(gemm_bf16_kernel<64>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+        hipLaunchKernelGGL((gemm_bf16_kernel<64, false, false>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
                            (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
     else
-        hipLaunchKernelGGL(gemm_bf16_kernel<128>, dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
+        hipLaunchKernelGGL((gemm_bf16_kernel<128, false, false>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
                            (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);

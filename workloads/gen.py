@@ -116,6 +116,10 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
         seqs = ((150, 150), (1, 77), (37, 90), (1, 300), (1, 1))
         return Workload("c3_small", sh, seqs, 2, (0, 150, 190))
+    if name == "c3_mid":        # enough rows for the many-row GEMM path, a long prefill chunk next to decodes
+        sh = LayerShape("bf16", 1024, 8, 2, 128, 2048)
+        seqs = ((2700, 2700),) + tuple((1, c) for c in _uniform_ctx(8, 20, 1, 600)) + ((96, 130),)
+        return Workload("c3_mid", sh, seqs, 8, (0, 2700, 2816))
     if name == "c4_small":
         sh = LayerShape("bf16", 512, 8, 2, 128, 1024, n_experts=8, top_k=2)
         ctx = _uniform_ctx(3, 40, 1, 200)
