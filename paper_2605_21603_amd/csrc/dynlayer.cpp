@@ -43,6 +43,7 @@ dyn_status fail(dyn_status st, const char *fmt, ...) {
 
 struct Dispatch {
     int layer, op, nano, n_nano, r0, r1, stream, partition;
+    bool any_multi;          // some sequence contributes more than one token to rows r0..r1
     std::vector<int> deps;   // dispatches (indices into the plan) whose output rows this one reads
     int key() const { return partition * DYN_MAX_STREAMS + stream; }
 };
@@ -121,7 +122,7 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
     w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
     w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
-    w.plan = take((t * w.max_chunks + t) * 2 * sizeof(int32_t));   // per dispatch: 2 header words + 2 per entry
+    w.plan = take((t * w.max_chunks + t) * 4 * sizeof(int32_t));   // per dispatch: two lists of 2 header words + 2 per entry
     if (c.n_experts) {
         const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter);
         w.sel = take(t * c.top_k * sizeof(int32_t));
@@ -239,7 +240,13 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
     for (int l = 0; l < L->cfg.n_layers; ++l)
         for (int i = 0; i < n_slots; ++i) {
             const dyn_slot &sl = slots[i];
-            Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, {}};
+            Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, false, {}};
+            {   // sequences inside [r0, r1): cut points are sequence boundaries
+                const int32_t *q = b->q_start_host;
+                const int s0 = (int)(std::lower_bound(q, q + b->n_seqs + 1, d.r0) - q);
+                const int s1 = (int)(std::lower_bound(q, q + b->n_seqs + 1, d.r1) - q);
+                d.any_multi = d.r1 - d.r0 > s1 - s0;
+            }
             const int pos = chain_pos[sl.op];
             for (int nb = sl.nano; nb < sl.nano + sl.n_nano; ++nb) {
                 int dep = -1;
@@ -264,9 +271,12 @@ dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream
         L->streams[key] = nullptr;
     }
     if (!L->streams[key]) {
-        if (partition > 0)
+        if (partition > 0) {
+            // A CU-masked stream is a hardware queue of its own whose mask is set through the
+            // driver; do that on an idle device, never while kernels of a forward are in flight.
+            HIP_TRY(hipDeviceSynchronize());
             HIP_TRY(hipExtStreamCreateWithCUMask(&L->streams[key], (uint32_t)mask.size(), mask.data()));
-        else
+        } else
             HIP_TRY(hipStreamCreateWithFlags(&L->streams[key], hipStreamNonBlocking));
         L->stream_mask[key] = mask;
     }
@@ -310,7 +320,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
                                         (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
                                         (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
-                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 2, sh, rows, st, mid, pre);
+                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 4, d.any_multi, sh, rows, st, mid, pre);
             break;
         case DYN_OP_OPROJ:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
@@ -538,6 +548,13 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
         return fail(DYN_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", b->workspace_bytes, ws.total);
     hipStream_t origin = (hipStream_t)hip_stream;
 
+    // every stream the schedule names exists before the first kernel of the forward is issued
+    for (const Dispatch &d : plan)
+        if (d.key() != 0) {
+            hipStream_t tmp;
+            rc = ensure_stream(L, s, d.key(), &tmp);
+            if (rc != DYN_OK) return rc;
+        }
     if (!s->use_graph) {
         rc = run_plan(L, b, s, ws, plan, origin, L->profiling);
         if (rc == DYN_OK && L->profiling) L->prof_plan = plan;
@@ -551,13 +568,7 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
             return DYN_OK;
         }
     if (!L->capture_stream) HIP_TRY(hipStreamCreateWithFlags(&L->capture_stream, hipStreamNonBlocking));
-    // create every stream and event before capture starts
-    for (const Dispatch &d : plan)
-        if (d.key() != 0) {
-            hipStream_t tmp;
-            rc = ensure_stream(L, s, d.key(), &tmp);
-            if (rc != DYN_OK) return rc;
-        }
+    // create every event before capture starts (the streams exist already)
     while (L->events.size() < plan.size()) {
         hipEvent_t ev;
         HIP_TRY(hipEventCreateWithFlags(&ev, hipEventDisableTiming));

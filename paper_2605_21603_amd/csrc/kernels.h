@@ -72,11 +72,12 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
 
 // Causal paged attention for token rows; part_o / part_ml are the split-KV partial arrays
 // ([rows, n_q, max_chunks, head_dim] and [rows, n_q, max_chunks, 2]); plan is scratch for the
-// device-built work list (2 + 2 * rows * max_chunks int32).
+// device-built work lists (2 * (2 + 2 * rows * max_chunks) int32); any_multi: some sequence has more
+// than one token in these rows (host knowledge; enables the wide-group launch).
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
-                            float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
-                            hipStream_t s, hipEvent_t mid = nullptr,    // mid: recorded between the chunk kernel and the combine
+                            float *part_o, float *part_ml, int32_t *plan, bool any_multi, const AttnShape &sh,
+                            int rows, hipStream_t s, hipEvent_t mid = nullptr,    // mid: recorded between the chunk kernel and the combine
                             hipEvent_t pre = nullptr);  // pre: recorded after the work-list kernel, before the chunk kernel
 
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]

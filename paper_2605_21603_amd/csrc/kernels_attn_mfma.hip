@@ -28,27 +28,32 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
 constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of the 256 CUs
+constexpr int kPrefillSets = 4;          // sets of 16 MFMA columns per wave for multi-token sequences
 
-// Work list, built on the device from the positions (contexts differ by 8x inside a batch, so
-// a dense token x max_chunks grid would be mostly empty workgroups).  Tokens of one sequence
-// whose positions fall in the same aligned block of TG = 16 / G positions form a query group
-// (a decode token is a group of one; a prefill chunk yields groups of TG): a wave serves all
-// G * TG (token, head) columns of a group from one pass over the keys.  One entry per
-// (group, chunk) that exists: plan[0] = number of entries, entry i = (first token row,
-// chunk | tokens << 20) at plan[2 + 2 i].
+// Work lists, built on the device from the positions (contexts differ by 8x inside a batch, so
+// a dense token x max_chunks grid would be mostly empty workgroups).  A wave serves a query
+// group: tokens of one sequence whose positions fall in the same aligned block of `tg`
+// positions, all of them against one pass over the keys.  List 0 holds the tokens that are
+// alone in their sequence this step (decode: groups of one, 4 of 16 MFMA columns live), list 1
+// the tokens of multi-token sequences (prefill chunks) in groups of up to tg1 = NQG * 16 / G.
+// One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
+// (first token row, chunk | tokens << 20) at list[2 + 2 i].
 __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
                                                         const int32_t *__restrict__ pos_of_token, int rows, int ct,
-                                                        int tg, int32_t *__restrict__ plan) {
-    __shared__ int scan[256];
-    __shared__ int base;
-    if (threadIdx.x == 0) base = 0;
+                                                        int tg1, int32_t *__restrict__ plan0, int32_t *__restrict__ plan1) {
+    __shared__ int scan[2][256];
+    __shared__ int base[2];
+    if (threadIdx.x < 2) base[threadIdx.x] = 0;
     __syncthreads();
     for (int t0 = 0; t0 < rows; t0 += 256) {
         const int t = t0 + threadIdx.x;
-        int nc = 0, n_tok = 0;
+        int nc = 0, n_tok = 0, which = 0;
         if (t < rows) {
-            const int s = seq_of_token[t], blk = pos_of_token[t] / tg;
-            const bool leader = t == 0 || seq_of_token[t - 1] != s || pos_of_token[t - 1] / tg != blk;
+            const int s = seq_of_token[t];
+            const bool prev_same = t > 0 && seq_of_token[t - 1] == s, next_same = t + 1 < rows && seq_of_token[t + 1] == s;
+            which = prev_same || next_same;
+            const int tg = which ? tg1 : 1, blk = pos_of_token[t] / tg;
+            const bool leader = !prev_same || pos_of_token[t - 1] / tg != blk;
             if (leader) {
                 n_tok = 1;
                 while (n_tok < tg && t + n_tok < rows && seq_of_token[t + n_tok] == s && pos_of_token[t + n_tok] / tg == blk)
@@ -56,32 +61,39 @@ __global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restric
                 nc = (pos_of_token[t + n_tok - 1] + ct) / ct;        // chunks the group's last token reaches
             }
         }
-        scan[threadIdx.x] = nc;
+        scan[0][threadIdx.x] = which ? 0 : nc;
+        scan[1][threadIdx.x] = which ? nc : 0;
         __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {           // inclusive Hillis-Steele scan
-            const int v = threadIdx.x >= off ? scan[threadIdx.x - off] : 0;
+        for (int off = 1; off < 256; off <<= 1) {           // inclusive Hillis-Steele scans of both lists
+            const int v0 = threadIdx.x >= off ? scan[0][threadIdx.x - off] : 0;
+            const int v1 = threadIdx.x >= off ? scan[1][threadIdx.x - off] : 0;
             __syncthreads();
-            scan[threadIdx.x] += v;
+            scan[0][threadIdx.x] += v0;
+            scan[1][threadIdx.x] += v1;
             __syncthreads();
         }
-        const int start = base + scan[threadIdx.x] - nc;
+        int32_t *plan = which ? plan1 : plan0;
+        const int start = base[which] + scan[which][threadIdx.x] - nc;
         for (int c = 0; c < nc; ++c) {
             plan[2 + 2 * (start + c)] = t;
             plan[3 + 2 * (start + c)] = c | (n_tok << 20);
         }
         __syncthreads();
-        if (threadIdx.x == 255) base += scan[255];
+        if (threadIdx.x == 255) { base[0] += scan[0][255]; base[1] += scan[1][255]; }
         __syncthreads();
     }
-    if (threadIdx.x == 0) plan[0] = base;
+    if (threadIdx.x == 0) { plan0[0] = base[0]; plan1[0] = base[1]; }
 }
 
-// Persistent waves, eight per CU: wave w of the launch takes (entry, kv head) pairs w,
-// w + n_waves, ...  A pair is walked two tiles (four pages) at a time through two register
-// buffers, and when a pair runs out of tiles the free buffer is refilled with the first tile
-// of the wave's next pair - whose indices were fetched while this pair was being multiplied -
-// so the stream of loads never drains at a pair boundary and the three dependent lookups
-// (work list -> position / sequence -> block table) are off the critical path.
+// Persistent waves: wave w of the launch takes (entry, kv head) pairs w, w + n_waves, ...
+// A pair is walked two tiles (four pages) at a time through two register buffers, and when a
+// pair runs out of tiles the free buffer is refilled with the first tile of the wave's next
+// pair - whose indices were fetched while this pair was being multiplied - so the stream of
+// loads never drains at a pair boundary and the three dependent lookups (work list ->
+// position / sequence -> block table) are off the critical path.
+// NQG = sets of 16 MFMA columns per wave: 1 for decode (eight waves per CU keep HBM busy),
+// 4 for prefill groups of 16 tokens (keys come from L2 and are re-read once per group, so
+// wider groups are what makes it fast; four waves per CU).
 struct AttnItem {
     int t, c, n_tok;                  // first token row of the query group, chunk, tokens in the group
     int n_keys, lp_first, seq_pages;  // keys the group's last token attends, first logical page of the chunk, its pages
@@ -89,7 +101,8 @@ struct AttnItem {
     const int32_t *bt;                // block-table row of the group's sequence
 };
 
-__global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
+template <int NQG>
+__global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const bf16_t *__restrict__ qkv,
                                                            const int32_t *__restrict__ seq_of_token,
                                                            const int32_t *__restrict__ pos_of_token,
                                                            const int32_t *__restrict__ block_table,
@@ -100,9 +113,9 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
     const int wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
     const int n_items = plan[0] * sh.n_kv;
     const int n_waves = gridDim.x * 4;
-    const int G = sh.n_q / sh.n_kv;
+    const int G = sh.n_q / sh.n_kv, TG = 16 / G;
     const int lane = threadIdx.x & 63, lr = lane & 15, lq = lane >> 4;
-    const int col_tok = lr / G, col_head = lr % G;   // MFMA column lr = (token col_tok of the group, q head col_head)
+    const int col_tok = lr / G, col_head = lr % G;   // MFMA column lr of set q = (token q * TG + col_tok, q head col_head)
     const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
 
     int item = blockIdx.x * 4 + wave;
@@ -127,7 +140,8 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
 
     u32x4 kreg[2][TILE_PAGES][4];
     u32x2 vreg[2][TILE_PAGES][8];
-    bf16x8 qb[4], qn[4];
+    bf16x8 qb[NQG][4], qn[NQG][4];
+    int nk_cur[NQG], nk_nxt[NQG];                  // keys each column attends (0 for a dead column)
 
     // tile TL of item M into register buffer B; page indices past the sequence's last page
     // are clamped (their scores are masked, the loads hit L2)
@@ -144,65 +158,65 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
                 vreg[B][pi][dt] = *reinterpret_cast<const u32x2 *>(vp + dt * 16 * PS);                            \
         }                                                                                                         \
     }
-    // B operands of the score product: column lr = q of token t + col_tok, head g*G + col_head
-    // (zero for columns past the group); NK = keys that column attends (0 for a dead column)
+    // B operands of the score product: column lr of set q = q vector of token t + q*TG + col_tok,
+    // head g*G + col_head (zero for columns past the group)
 #define DYN_ATTN_LOAD_Q(DST, NK, M, GG)                                                                           \
-    {                                                                                                             \
-        const bool live = col_tok < (M).n_tok;                                                                    \
-        const int tq = (M).t + (live ? col_tok : 0);                                                              \
-        NK = live ? pos_of_token[tq] + 1 : 0;                                                                     \
-        const bf16_t *q = qkv + (size_t)tq * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + col_head) * HD + 8 * lq; \
+    _Pragma("unroll") for (int q = 0; q < NQG; ++q) {                                                             \
+        const bool live = q * TG + col_tok < (M).n_tok && col_tok < TG;                                           \
+        const int tq = (M).t + (live ? q * TG + col_tok : 0);                                                     \
+        NK[q] = live ? pos_of_token[tq] + 1 : 0;                                                                  \
+        const bf16_t *qp = qkv + (size_t)tq * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + col_head) * HD + 8 * lq; \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                        \
-            u32x4 v = *reinterpret_cast<const u32x4 *>(q + ks * 32);                                              \
+            u32x4 v = *reinterpret_cast<const u32x4 *>(qp + ks * 32);                                             \
             if (!live) v = u32x4{0u, 0u, 0u, 0u};                                                                 \
-            DST[ks] = __builtin_bit_cast(bf16x8, v);                                                              \
+            DST[q][ks] = __builtin_bit_cast(bf16x8, v);                                                           \
         }                                                                                                         \
     }
 #define DYN_ATTN_COMPUTE(B, TL)                                                                                   \
-    {                                                                                                             \
+    _Pragma("unroll") for (int q = 0; q < NQG; ++q) {                                                             \
         f32x4 sv[TILE_PAGES];                                                                                     \
         float mx = -INFINITY;                                                                                     \
         _Pragma("unroll") for (int pi = 0; pi < TILE_PAGES; ++pi) {                                               \
             f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};                                                                  \
             _Pragma("unroll") for (int ks = 0; ks < 4; ++ks)                                                      \
-                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[B][pi][ks]), qb[ks],  \
-                                                            s, 0, 0, 0);                                          \
+                s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kreg[B][pi][ks]),          \
+                                                            qb[q][ks], s, 0, 0, 0);                               \
             const int jb = (cur.lp_first + (TL) * TILE_PAGES + pi) * PS + 4 * lq;                                 \
             _Pragma("unroll") for (int r = 0; r < 4; ++r) {                                                       \
-                s[r] = (jb + r < nk_cur) ? s[r] * sscale : -INFINITY;                                             \
+                s[r] = (jb + r < nk_cur[q]) ? s[r] * sscale : -INFINITY;                                          \
                 mx = fmaxf(mx, s[r]);                                                                             \
             }                                                                                                     \
             sv[pi] = s;                                                                                           \
         }                                                                                                         \
         mx = fmaxf(mx, __shfl_xor(mx, 16, 64));                                                                   \
         mx = fmaxf(mx, __shfl_xor(mx, 32, 64));                                                                   \
-        const float m_new = fmaxf(m_run, mx);                                                                     \
+        const float m_new = fmaxf(m_run[q], mx);                                                                  \
         const float m_ref = m_new == -INFINITY ? 0.f : m_new;   /* a column with no key yet stays empty */        \
-        const float alpha = __builtin_amdgcn_exp2f(m_run - m_ref);                                                \
-        m_run = m_new;                                                                                            \
-        l_run *= alpha;                                                                                           \
-        _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) acc[dt] *= alpha;                                        \
+        const float alpha = __builtin_amdgcn_exp2f(m_run[q] - m_ref);                                             \
+        m_run[q] = m_new;                                                                                         \
+        l_run[q] *= alpha;                                                                                        \
+        _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) acc[q][dt] *= alpha;                                     \
         _Pragma("unroll") for (int pi = 0; pi < TILE_PAGES; ++pi) {                                               \
             f32x4 p;                                                                                              \
             _Pragma("unroll") for (int r = 0; r < 4; ++r) p[r] = __builtin_amdgcn_exp2f(sv[pi][r] - m_ref);       \
             const bf16x4 pb = __builtin_convertvector(p, bf16x4);                                                 \
             const u32x2 pw = __builtin_bit_cast(u32x2, pb);                                                       \
-            l_run += (__uint_as_float(pw[0] << 16) + __uint_as_float(pw[0] & 0xffff0000u)) +                      \
-                     (__uint_as_float(pw[1] << 16) + __uint_as_float(pw[1] & 0xffff0000u));                       \
+            l_run[q] += (__uint_as_float(pw[0] << 16) + __uint_as_float(pw[0] & 0xffff0000u)) +                   \
+                        (__uint_as_float(pw[1] << 16) + __uint_as_float(pw[1] & 0xffff0000u));                    \
             const int nvalid = cur.n_keys - (cur.lp_first + (TL) * TILE_PAGES + pi) * PS - 4 * lq;                \
             _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) {                                                    \
                 u32x2 vv = vreg[B][pi][dt];                                                                       \
-                if (nvalid < 4) { /* positions past the token's own: keep stale cache bits out of 0 * x */      \
+                if (nvalid < 4) { /* positions past the group's last: keep stale cache bits out of 0 * x */     \
                     vv[0] &= (nvalid > 0 ? 0x0000ffffu : 0u) | (nvalid > 1 ? 0xffff0000u : 0u);                   \
                     vv[1] &= (nvalid > 2 ? 0x0000ffffu : 0u);                                                     \
                 }                                                                                                 \
-                acc[dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, vv),                \
-                                                                    __builtin_bit_cast(s16x4, pb), acc[dt], 0, 0, 0); \
+                acc[q][dt] = __builtin_amdgcn_mfma_f32_16x16x16bf16_1k(__builtin_bit_cast(s16x4, vv),             \
+                                                                       __builtin_bit_cast(s16x4, pb), acc[q][dt], 0, 0, 0); \
             }                                                                                                     \
         }                                                                                                         \
     }
 
-    int g_cur = 0, g_nxt = 0, nk_cur = 0, nk_nxt = 0;
+    int g_cur = 0, g_nxt = 0;
     AttnItem cur = fetch_item(item, g_cur);
     DYN_ATTN_LOAD_Q(qb, nk_cur, cur, g_cur)
     DYN_ATTN_LOAD(0, cur, g_cur, 0)
@@ -211,10 +225,15 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
         const bool more = next_item < n_items;
         // the wave's last pair "prefetches" itself again: harmless loads instead of a conditional branch
         AttnItem nxt = fetch_item(more ? next_item : item, g_nxt);
-        f32x4 acc[8];
+        f32x4 acc[NQG][8];
+        float m_run[NQG], l_run[NQG];
 #pragma unroll
-        for (int dt = 0; dt < 8; ++dt) acc[dt] = f32x4{0.f, 0.f, 0.f, 0.f};
-        float m_run = -INFINITY, l_run = 0.f;
+        for (int q = 0; q < NQG; ++q) {
+            m_run[q] = -INFINITY;
+            l_run[q] = 0.f;
+#pragma unroll
+            for (int dt = 0; dt < 8; ++dt) acc[q][dt] = f32x4{0.f, 0.f, 0.f, 0.f};
+        }
 
         for (int pr = 0; pr < cur.n_pair; ++pr) {
             const bool last = pr + 1 == cur.n_pair;
@@ -235,25 +254,33 @@ __global__ __launch_bounds__(256, 2) void attn_mfma_kernel(const bf16_t *__restr
             __builtin_amdgcn_sched_barrier(0);
         }
 
-        l_run += __shfl_xor(l_run, 16, 64);
-        l_run += __shfl_xor(l_run, 32, 64);
-        if (nk_cur > cur.c * sh.chunk_pages * PS) {       // the chunk exists for this column's token
-            const size_t pidx = ((size_t)(cur.t + col_tok) * sh.n_q + g_cur * G + col_head) * sh.max_chunks + cur.c;
 #pragma unroll
-            for (int dt = 0; dt < 8; ++dt)
-                *reinterpret_cast<f32x4 *>(part_o + pidx * HD + dt * 16 + 4 * lq) = acc[dt];
-            if (lq == 0) {
-                part_ml[pidx * 2] = m_run;
-                part_ml[pidx * 2 + 1] = l_run;
+        for (int q = 0; q < NQG; ++q) {
+            float l = l_run[q];
+            l += __shfl_xor(l, 16, 64);
+            l += __shfl_xor(l, 32, 64);
+            if (nk_cur[q] > cur.c * sh.chunk_pages * PS) {       // the chunk exists for this column's token
+                const size_t pidx =
+                    ((size_t)(cur.t + q * TG + col_tok) * sh.n_q + g_cur * G + col_head) * sh.max_chunks + cur.c;
+#pragma unroll
+                for (int dt = 0; dt < 8; ++dt)
+                    *reinterpret_cast<f32x4 *>(part_o + pidx * HD + dt * 16 + 4 * lq) = acc[q][dt];
+                if (lq == 0) {
+                    part_ml[pidx * 2] = m_run[q];
+                    part_ml[pidx * 2 + 1] = l;
+                }
             }
         }
         if (!more) break;
         item = next_item;
         cur = nxt;
         g_cur = g_nxt;
-        nk_cur = nk_nxt;
 #pragma unroll
-        for (int ks = 0; ks < 4; ++ks) qb[ks] = qn[ks];
+        for (int q = 0; q < NQG; ++q) {
+            nk_cur[q] = nk_nxt[q];
+#pragma unroll
+            for (int ks = 0; ks < 4; ++ks) qb[q][ks] = qn[q][ks];
+        }
     }
 #undef DYN_ATTN_LOAD
 #undef DYN_ATTN_LOAD_Q
@@ -271,23 +298,33 @@ bool attention_mfma_supported(int dtype, const AttnShape &sh) {
 
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
-                            float *part_o, float *part_ml, int32_t *plan, const AttnShape &sh, int rows,
+                            float *part_o, float *part_ml, int32_t *plan, bool any_multi, const AttnShape &sh, int rows,
                             hipStream_t s, hipEvent_t mid, hipEvent_t pre) {
     if (rows <= 0) return hipSuccess;
     if (!attention_mfma_supported(dtype, sh))
         return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
                                         part_o, part_ml, sh, rows, s, mid);
+    // two work lists per dispatch: single-token sequences, multi-token sequences
+    const int G = sh.n_q / sh.n_kv, TG = 16 / G;
+    int32_t *plan0 = plan, *plan1 = plan + 2 + 2 * (size_t)rows * sh.max_chunks;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
-                       16 / (sh.n_q / sh.n_kv), plan);
+                       kPrefillSets * TG, plan0, plan1);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
     const long max_items = (long)rows * sh.n_kv * sh.max_chunks;
     const int grid = (int)((max_items + 3) / 4 < kPersistentGroups ? (max_items + 3) / 4 : kPersistentGroups);
-    hipLaunchKernelGGL(attn_mfma_kernel, dim3(grid), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
+    hipLaunchKernelGGL(attn_mfma_kernel<1>, dim3(grid), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
-                       plan);
+                       plan0);
     e = hipGetLastError();
+    if (e == hipSuccess && any_multi) {
+        const int grid1 = (int)((max_items + 3) / 4 < kPersistentGroups / 2 ? (max_items + 3) / 4 : kPersistentGroups / 2);
+        hipLaunchKernelGGL(attn_mfma_kernel<kPrefillSets>, dim3(grid1), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
+                           pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml,
+                           sh, plan1);
+        e = hipGetLastError();
+    }
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
     return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, out, ld_out, sh, rows, s);

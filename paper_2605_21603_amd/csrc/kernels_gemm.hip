@@ -67,35 +67,47 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 }
 
 // ------------------------------------------------------------------ bf16 MFMA path
-// Workgroup = 4 waves on a 128 (W rows) x MT (X rows, 64 or 128) output tile and one K
-// plane.  What bounds this kernel below a few hundred rows is not the matrix cores and not
-// even HBM alone but the L2 -> CU path: every byte of W must cross it once and the X tile
-// crosses it once per W tile, so both operands are fetched exactly once per workgroup with
-// fully coalesced 128-byte row segments (8 lanes per row), parked in registers for three
-// stages (a stage is 64 k), and handed to the waves through LDS.  LDS rows are padded to
-// 144 bytes so the 16-lane groups of a ds_read_b128 in MFMA operand layout (lane l: row
-// l%16, 8 consecutive k at 8*(l/16)) touch disjoint banks.  Waves sit 2 x 2 on the tile:
-// 64 W rows x MT/2 X rows each.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
-constexpr int BN = 128, BK = 64, ROWB = BK * 2 + 16, RING = 4;
-#ifndef DYN_OCC2_TILES
-#define DYN_OCC2_TILES 2     // row tiles from which the two-workgroups-per-CU build is used
-#endif
-
+// Workgroup = 4 waves on a BN (W rows) x MT (X rows) output tile and one K plane (or, INREG,
+// all planes in turn).  What bounds this kernel below a few hundred rows is not the matrix
+// cores and not even HBM alone but the L2 -> CU path: every byte of W must cross it once and
+// the X tile crosses it once per W tile, so both operands are fetched exactly once per
+// workgroup, with fully coalesced 128-byte row segments (8 lanes per row), by direct
+// global -> LDS loads (no registers in between) into a ring of NS stage buffers (a stage is
+// 64 k); NS - 1 stages are in flight while one is multiplied, tracked with exact vmcnt waits
+// and one barrier per stage.  A direct load places lane l's 16 bytes at l * 16 of the wave's
+// 1 KB window, so rows sit at a 128-byte pitch; bank conflicts of the MFMA-layout reads
+// (lane l: row l%16, 8 consecutive k at 8*(l/16)) are avoided by an XOR swizzle of the
+// 16-byte column with bits 1..3 of the row, applied to the global column a lane fetches.
+// Waves sit 2 x 2 on the tile.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
+//
 // INREG: one workgroup walks all S planes of its tile and adds the plane sums in registers
 // (same order, same bits as the plane buffers + gemm_reduce_kernel) - for many-row launches,
 // where there are enough tiles to fill the chip without spreading planes over workgroups and
 // the fp32 plane traffic would cost more than the weights.
-// OCC2: compile for two workgroups per CU (256 VGPRs) - pays when the launch is bound by
-// the matrix cores (many row tiles), costs a few spills that hurt when it is bound by memory.
-template <int MT, bool INREG, bool OCC2>
-__global__ __launch_bounds__(256, OCC2 ? 2 : 1) void gemm_bf16_kernel(const bf16_t *__restrict__ X, int ldx,
-                                                        const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
-                                                        bf16_t *__restrict__ Y, float *__restrict__ P,
-                                                        size_t plane_stride, int M, int N, int K, int S, GemmGroups gr) {
-    constexpr int XP = MT / 32;                     // 16-byte X pieces per thread and stage
-    constexpr int NB = MT / 32;                     // B tiles (16 X rows) per wave
-    __shared__ __attribute__((aligned(16))) unsigned char lw[2][BN * ROWB];
-    __shared__ __attribute__((aligned(16))) unsigned char lx[2][MT * ROWB];
+constexpr int BK = 64, ROWB = BK * 2;
+
+__device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(n) only; n is one of a few literals
+    // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
+    switch (n) {
+        case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+        case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
+        case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
+        case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
+        case 16: __builtin_amdgcn_s_waitcnt(0x4f70); break;
+        case 24: __builtin_amdgcn_s_waitcnt(0x4f78); break;
+        default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+    }
+}
+
+template <int BN, int MT, bool INREG, int NS>
+__global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
+    const bf16_t *__restrict__ X, int ldx, const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
+    bf16_t *__restrict__ Y, float *__restrict__ P, size_t plane_stride, int M, int N, int K, int S, GemmGroups gr) {
+    constexpr int ROWS = BN + MT;                   // rows of a stage buffer: W rows, then X rows
+    constexpr int LPS = ROWS / 32;                  // direct loads per thread and stage (8 rows per wave instruction)
+    constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
+    constexpr int NA = BN / 32, NB = MT / 32;       // 16-row operand tiles per wave
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int m_tiles = (M + MT - 1) / MT;
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
     // m tiles of one (n tile, plane)) get ids 8 apart: same XCD, same L2, adjacent in time.
@@ -120,104 +132,99 @@ __global__ __launch_bounds__(256, OCC2 ? 2 : 1) void gemm_bf16_kernel(const bf16
     const int Kp = K / S, kbase = INREG ? 0 : sp * Kp, n_stage = (INREG ? K : Kp) / BK;
     const int plane_stages = Kp / BK;
     const int n0 = n_tile * BN, m0 = m_tile * MT;
-    const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
     const int lr = lane & 15, lq = lane >> 4, wn = wave & 1, wm = wave >> 1;
 
-    const int prow = tid >> 3, pcol = tid & 7;      // piece p = tid + 256 u: row prow + 32 u, 16-byte column pcol
-    const bf16_t *wg[4], *xg[XP];
+    // Direct load j of this wave covers stage rows (j * 4 + wave) * 8 .. + 8; lane l fetches
+    // row + l / 8, global 16-byte column (l % 8) ^ swizzle(row).
+    const bf16_t *src[LPS];
 #pragma unroll
-    for (int q = 0; q < 4; ++q) wg[q] = W + (size_t)(n0 + prow + 32 * q) * K + kbase + pcol * 8;
-#pragma unroll
-    for (int q = 0; q < XP; ++q) {
-        const int mr = min(m0 + prow + 32 * q, M - 1);
-        xg[q] = X + (size_t)(list ? list[mr] / gr.x_div : mr) * ldx + kbase + pcol * 8;
+    for (int j = 0; j < LPS; ++j) {
+        const int row = (j * 4 + wave) * 8 + (lane >> 3);
+        const int col = (lane & 7) ^ ((row >> 1) & 7);
+        if (row < BN) {
+            src[j] = W + (size_t)(n0 + row) * K + kbase + col * 8;
+        } else {
+            const int mr = min(m0 + row - BN, M - 1);
+            src[j] = X + (size_t)(list ? list[mr] / gr.x_div : mr) * ldx + kbase + col * 8;
+        }
     }
-    const int loff = prow * ROWB + pcol * 16;
-
-    u32x4 rw[RING][4], rx[RING][XP];
-    f32x4 acc[4][NB], total[INREG ? 4 : 1][INREG ? NB : 1];
+    auto issue = [&](int st) {                         // all direct loads of stage st into ring buffer st % NS
+        unsigned char *buf = lds + (st % NS) * STAGE;
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+        for (int j = 0; j < LPS; ++j)
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)st * BK),
+                                             (__attribute__((address_space(3))) void *)(buf + (j * 4 + wave) * 8 * ROWB),
+                                             16, 0, 0);
+    };
+
+    f32x4 acc[NA][NB], total[INREG ? NA : 1][INREG ? NB : 1];
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
             if (INREG) total[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
         }
-    // a plane ends on a multiple of RING stages: fold its sum into the total, start the next from zero
-#define DYN_GEMM_PLANE_END(ST_DONE)                                                                      \
-    if (INREG && (ST_DONE) % plane_stages == 0) {                                                        \
-        _Pragma("unroll") for (int a = 0; a < 4; ++a) _Pragma("unroll") for (int b = 0; b < NB; ++b) {   \
-            total[a][b] += acc[a][b];                                                                    \
-            acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};                                                       \
-        }                                                                                                \
-    }
 
-#define DYN_GEMM_FETCH(SLOT, ST)                                                                         \
-    {                                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                    \
-            rw[SLOT][q] = *reinterpret_cast<const u32x4 *>(wg[q] + (size_t)(ST) * BK);                   \
-        _Pragma("unroll") for (int q = 0; q < XP; ++q)                                                   \
-            rx[SLOT][q] = *reinterpret_cast<const u32x4 *>(xg[q] + (size_t)(ST) * BK);                   \
+    // operand read offsets inside a stage buffer (bytes), k-step 0; k-step 1 flips column bit 2
+    int a_off[NA], b_off[NB];
+#pragma unroll
+    for (int a = 0; a < NA; ++a) {
+        const int row = wn * (BN / 2) + a * 16 + lr;
+        a_off[a] = row * ROWB + ((lq ^ ((row >> 1) & 7)) << 4);
     }
-#define DYN_GEMM_PARK(SLOT, BUF)                                                                         \
-    {                                                                                                    \
-        _Pragma("unroll") for (int q = 0; q < 4; ++q)                                                    \
-            *reinterpret_cast<u32x4 *>(&lw[BUF][loff + 32 * q * ROWB]) = rw[SLOT][q];                    \
-        _Pragma("unroll") for (int q = 0; q < XP; ++q)                                                   \
-            *reinterpret_cast<u32x4 *>(&lx[BUF][loff + 32 * q * ROWB]) = rx[SLOT][q];                    \
+#pragma unroll
+    for (int b = 0; b < NB; ++b) {
+        const int row = BN + wm * (MT / 2) + b * 16 + lr;
+        b_off[b] = row * ROWB + ((lq ^ ((row >> 1) & 7)) << 4);
     }
-#define DYN_GEMM_MMA(BUF)                                                                                \
-    _Pragma("unroll") for (int ks = 0; ks < 2; ++ks) {                                                   \
-        bf16x8 av[4], bv[NB];                                                                            \
-        _Pragma("unroll") for (int a = 0; a < 4; ++a) av[a] = *reinterpret_cast<const bf16x8 *>(         \
-            &lw[BUF][(wn * 64 + a * 16 + lr) * ROWB + ks * 64 + lq * 16]);                               \
-        _Pragma("unroll") for (int b = 0; b < NB; ++b) bv[b] = *reinterpret_cast<const bf16x8 *>(        \
-            &lx[BUF][(wm * (MT / 2) + b * 16 + lr) * ROWB + ks * 64 + lq * 16]);                         \
-        _Pragma("unroll") for (int a = 0; a < 4; ++a) _Pragma("unroll") for (int b = 0; b < NB; ++b)     \
-            acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);       \
-    }
-    // Stage i: fetch stage i+3 into the ring, multiply stage i out of LDS buffer i%2, park
-    // stage i+1 in the other buffer, barrier.  J = i mod 4 is a literal so that every ring
-    // index is static; n_stage is a multiple of 4 (gemm_supported / gemm_split_k), and the
-    // steady-state loop has no conditional loads so that outstanding loads are counted exactly.
-#define DYN_GEMM_STAGE(J, FETCH, PARK)                                                                   \
-    {                                                                                                    \
-        if (FETCH) DYN_GEMM_FETCH(((J) + 3) % RING, st0 + (J) + 3)                                       \
-        DYN_GEMM_MMA((J) % 2)                                                                            \
-        if (PARK) DYN_GEMM_PARK(((J) + 1) % RING, ((J) + 1) % 2)                                         \
-        __syncthreads();                                                                                 \
-    }
-    static_assert(RING == 4, "stages are written out four at a time");
-    DYN_GEMM_FETCH(0, 0)
-    DYN_GEMM_FETCH(1, 1)
-    DYN_GEMM_FETCH(2, 2)
-    DYN_GEMM_PARK(0, 0)
-    __syncthreads();
-    int st0 = 0;
-    for (; st0 < n_stage - RING; st0 += RING) {
-        DYN_GEMM_STAGE(0, true, true)
-        DYN_GEMM_STAGE(1, true, true)
-        DYN_GEMM_STAGE(2, true, true)
-        DYN_GEMM_STAGE(3, true, true)
-        DYN_GEMM_PLANE_END(st0 + RING)
-    }
-    DYN_GEMM_STAGE(0, true, true)
-    DYN_GEMM_STAGE(1, false, true)
-    DYN_GEMM_STAGE(2, false, true)
-    DYN_GEMM_STAGE(3, false, false)
-    DYN_GEMM_PLANE_END(st0 + RING)
-#undef DYN_GEMM_PLANE_END
-#undef DYN_GEMM_STAGE
-#undef DYN_GEMM_MMA
-#undef DYN_GEMM_PARK
-#undef DYN_GEMM_FETCH
 
 #pragma unroll
-    for (int a = 0; a < 4; ++a)
+    for (int d = 0; d < NS - 1; ++d)
+        if (d < n_stage) issue(d);
+    for (int st = 0; st < n_stage; ++st) {
+        // stage st has landed when at most the loads of the stages issued after it are outstanding
+        const int ahead = min(NS - 2, n_stage - 1 - st);
+        if (ahead >= 2) wait_vmcnt(2 * LPS);
+        else if (ahead == 1) wait_vmcnt(LPS);
+        else wait_vmcnt(0);
+        // Bare barrier: __syncthreads() would add a fence that drains every outstanding load, which
+        // is exactly the prefetch.  The loads of stage st are complete (waited above) and, being
+        // direct-to-LDS, visible once complete; the reads of stage st-1 were consumed by MFMAs.
+        __builtin_amdgcn_s_barrier();
+        if (st + NS - 1 < n_stage) issue(st + NS - 1);
+        const unsigned char *buf = lds + (st % NS) * STAGE;
+#pragma unroll
+        for (int ks = 0; ks < 2; ++ks) {
+            bf16x8 av[NA], bv[NB];
+#pragma unroll
+            for (int a = 0; a < NA; ++a) av[a] = *reinterpret_cast<const bf16x8 *>(buf + (a_off[a] ^ (ks << 6)));
+#pragma unroll
+            for (int b = 0; b < NB; ++b) bv[b] = *reinterpret_cast<const bf16x8 *>(buf + (b_off[b] ^ (ks << 6)));
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b)
+                    acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
+        }
+        if (INREG && (st + 1) % plane_stages == 0) {   // a plane ends: fold its sum into the total, start from zero
+#pragma unroll
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    total[a][b] += acc[a][b];
+                    acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+        }
+    }
+
+#pragma unroll
+    for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int m = m0 + wm * (MT / 2) + b * 16 + lr;
-            const int n = n0 + wn * 64 + a * 16 + 4 * lq;
+            const int n = n0 + wn * (BN / 2) + a * 16 + 4 * lq;
             if (m >= M) continue;
             const size_t orow = list ? list[m] : m;
             f32x4 o = INREG ? total[a][b] : acc[a][b];
@@ -235,6 +242,23 @@ __global__ __launch_bounds__(256, OCC2 ? 2 : 1) void gemm_bf16_kernel(const bf16
                 *reinterpret_cast<f32x4 *>(P + (size_t)sp * plane_stride + orow * N + n) = o;
             }
         }
+}
+
+template <int BN, int MT, bool INREG, int NS>
+hipError_t launch_gemm_bf16(int grid, hipStream_t s, const void *X, int ldx, const void *W, const void *R, void *Y,
+                            float *partial, size_t plane_stride, int rows, int N, int K, int S, const GemmGroups &gr) {
+    constexpr int STAGE = (BN + MT) * ROWB;
+    static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "ring does not fit in LDS");
+    static bool attr_set = false;                      // above 64 KB of dynamic LDS needs an opt-in, once
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS>,
+                                           hipFuncAttributeMaxDynamicSharedMemorySize, NS * STAGE);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL((gemm_bf16_kernel<BN, MT, INREG, NS>), dim3(grid), dim3(256), NS * STAGE, s, (const bf16_t *)X, ldx,
+                       (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, gr);
+    return hipGetLastError();
 }
 
 // Y = bf16((((P_0 + P_1) + ...) + P_{S-1}) + R), four elements per thread.
@@ -261,7 +285,7 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float *__restric
 
 bool gemm_supported(int dtype, int N, int K) {
     if (dtype == 0) return N > 0 && K > 0;
-    return N > 0 && K > 0 && N % BN == 0 && K % (BK * RING) == 0;
+    return N > 0 && K > 0 && N % 128 == 0 && K % BK == 0;
 }
 
 int gemm_split_k(int dtype, int N, int K) {
@@ -269,10 +293,10 @@ int gemm_split_k(int dtype, int N, int K) {
     // enough workgroups to occupy 256 CUs twice over, chunks of at least 8 k-steps
     static int forced = -1;
     if (forced < 0) { const char *e = getenv("DYN_GEMM_SPLIT"); forced = e ? atoi(e) : 0; }
-    const int unit = BK * RING;                       // a plane is a multiple of RING stages
+    // planes of at least four stages; enough (128-row tile, plane) pairs to occupy the chip
     int S = 1;
-    while ((N / BN) * S < 192 && K % (S * 2 * unit) == 0 && K / (S * 2) >= 2 * unit) S *= 2;
-    if (forced > 0 && K % (forced * unit) == 0) S = forced;
+    while ((N / 128) * S < 192 && K % (S * 2 * BK) == 0 && K / (S * 2) >= 4 * BK * 2) S *= 2;
+    if (forced > 0 && K % (forced * BK) == 0) S = forced;
     return S;
 }
 
@@ -290,18 +314,27 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     const int S = gemm_split_k(dtype, N, K);
     const int MT = rows <= 64 ? 64 : 128;
     const int m_tiles = (rows + MT - 1) / MT;
-    const bool inreg = S > 1 && (N / BN) * m_tiles >= 256;      // enough tiles without spreading the planes
-    const int ns = (N / BN) * (inreg ? 1 : S);
-    const int grid = ((ns + 7) / 8) * 8 * m_tiles;
-#define DYN_GEMM_LAUNCH(...)                                                                                        \
-    hipLaunchKernelGGL((gemm_bf16_kernel<__VA_ARGS__>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx,        \
-                       (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, none)
-    if (inreg) DYN_GEMM_LAUNCH(128, true, false);
-    else if (MT == 64) DYN_GEMM_LAUNCH(64, false, false);
-    else if (m_tiles >= DYN_OCC2_TILES) DYN_GEMM_LAUNCH(128, false, true);
-    else DYN_GEMM_LAUNCH(128, false, false);
-#undef DYN_GEMM_LAUNCH
-    hipError_t e = hipGetLastError();
+    // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
+    // workgroups, a shallow ring and two workgroups per CU so that one multiplies while the other
+    // waits at its barrier.  Few-row launches are bound by memory: deep ring, one workgroup per CU.
+#ifndef DYN_BIG_BN
+#define DYN_BIG_BN 128
+#define DYN_BIG_MT 128
+#define DYN_BIG_NS 2
+#endif
+    const int big_tiles = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
+    const bool big = N % DYN_BIG_BN == 0 && big_tiles >= 256;
+    const bool inreg = S > 1 && big;
+    hipError_t e;
+    if (big) {
+        const int grid = (((N / DYN_BIG_BN) + 7) / 8) * 8 * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
+        if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+        else e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+    } else {
+        const int grid = ((((N / 128) * S) + 7) / 8) * 8 * m_tiles;
+        if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+        else e = launch_gemm_bf16<128, 128, false, 4>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+    }
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1 || inreg) return e;
     const size_t n_vec = (size_t)rows * N / 4;
@@ -332,15 +365,11 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
     const int S = gemm_split_k(dtype, N, K);
     const int MT = max_rows <= 64 ? 64 : 128;
     const int m_tiles = (max_rows + MT - 1) / MT;
-    const int ns = (N / BN) * S * gr.n_groups;
+    const int ns = (N / 128) * S * gr.n_groups;
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
-    if (MT == 64)
-        hipLaunchKernelGGL((gemm_bf16_kernel<64, false, false>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
-    else
-        hipLaunchKernelGGL((gemm_bf16_kernel<128, false, false>), dim3(grid), dim3(256), 0, s, (const bf16_t *)X, ldx, (const bf16_t *)W,
-                           (const bf16_t *)nullptr, (bf16_t *)Y, partial, plane_stride, max_rows, N, K, S, gr);
-    hipError_t e = hipGetLastError();
+    hipError_t e;
+    if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
+    else e = launch_gemm_bf16<128, 128, false, 4>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1 || gr.force_planes) return e;
     // output rows row0 .. row0 + n_rows - 1 are exactly the rows the groups wrote

@@ -9,27 +9,45 @@ namespace dyn {
 
 constexpr int kMaxExperts = 16;
 
-// One wave per token.  Lane l accumulates its slice of every expert's dot product in fp32,
-// a butterfly adds the slices, lane 0 picks the top_k largest logits (ties to the lower
-// index) and normalises exp(logit - max) over the picked ones.
+// One 256-thread workgroup per token.  Every thread takes contiguous 8-element pieces of the
+// row, multiplies them with the same pieces of all E router rows (all loads of a piece are
+// independent, so they are in flight together), a butterfly and a fixed-order LDS step add the
+// slices, thread 0 picks the top_k largest logits (ties to the lower index) and normalises
+// exp(logit - max) over the picked ones.
 template <typename T>
 __global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ h, int ldh, const float *__restrict__ w_router,
                                                     int32_t *__restrict__ sel, float *__restrict__ wgt, int rows,
                                                     int H, int E, int top_k) {
-    const int t = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
-    if (t >= rows) return;
+    const int t = blockIdx.x, lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     float acc[kMaxExperts];
 #pragma unroll
     for (int e = 0; e < kMaxExperts; ++e) acc[e] = 0.f;
-    for (int k = lane; k < H; k += 64) {
-        const float x = to_f32<T>(h[(size_t)t * ldh + k]);
+    for (int k0 = threadIdx.x * 8; k0 < H; k0 += 256 * 8) {
+        float x[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) x[i] = to_f32<T>(h[(size_t)t * ldh + k0 + i]);
 #pragma unroll
         for (int e = 0; e < kMaxExperts; ++e)
-            if (e < E) acc[e] = fmaf(x, w_router[(size_t)e * H + k], acc[e]);
-    }
+            if (e < E) {
+                const f32x4 w0 = *reinterpret_cast<const f32x4 *>(w_router + (size_t)e * H + k0);
+                const f32x4 w1 = *reinterpret_cast<const f32x4 *>(w_router + (size_t)e * H + k0 + 4);
 #pragma unroll
-    for (int e = 0; e < kMaxExperts; ++e) acc[e] = wave_sum(acc[e]);
-    if (lane != 0) return;
+                for (int i = 0; i < 4; ++i) acc[e] = fmaf(x[i], w0[i], acc[e]);
+#pragma unroll
+                for (int i = 0; i < 4; ++i) acc[e] = fmaf(x[4 + i], w1[i], acc[e]);
+            }
+    }
+    __shared__ float part[4][kMaxExperts];
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e) {
+        const float v = wave_sum(acc[e]);
+        if (lane == 0) part[wave][e] = v;
+    }
+    __syncthreads();
+    if (threadIdx.x != 0) return;
+    float logit[kMaxExperts];
+#pragma unroll
+    for (int e = 0; e < kMaxExperts; ++e) logit[e] = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
     bool used[kMaxExperts] = {};
     int pick[kMaxExperts];
     float mx = -INFINITY;
@@ -37,23 +55,23 @@ __global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ h, int
         int best = -1;
 #pragma unroll
         for (int e = 0; e < kMaxExperts; ++e)
-            if (e < E && !used[e] && (best < 0 || acc[e] > acc[best])) best = e;
+            if (e < E && !used[e] && (best < 0 || logit[e] > logit[best])) best = e;
         used[best] = true;
         pick[j] = best;
-        mx = fmaxf(mx, acc[best]);
+        mx = fmaxf(mx, logit[best]);
     }
     float denom = 0.f;
-    for (int j = 0; j < top_k; ++j) denom += expf(acc[pick[j]] - mx);
+    for (int j = 0; j < top_k; ++j) denom += expf(logit[pick[j]] - mx);
     for (int j = 0; j < top_k; ++j) {
         sel[(size_t)t * top_k + j] = pick[j];
-        wgt[(size_t)t * top_k + j] = expf(acc[pick[j]] - mx) / denom;
+        wgt[(size_t)t * top_k + j] = expf(logit[pick[j]] - mx) / denom;
     }
 }
 
 hipError_t launch_route(int dtype, const void *h, int ldh, const float *w_router, int32_t *sel, float *wgt, int rows,
                         int H, int E, int top_k, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
-    const dim3 grid((rows + 3) / 4);
+    const dim3 grid(rows);
     if (dtype == 0)
         hipLaunchKernelGGL(route_kernel<float>, grid, dim3(256), 0, s, (const float *)h, ldh, w_router, sel, wgt, rows, H, E, top_k);
     else

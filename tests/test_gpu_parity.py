@@ -110,11 +110,14 @@ def test_cu_partitioned_streams_and_graph_replay(name):
         step = B.DeviceStep(run.layer, data)
         st = torch.cuda.Stream()
         for rep in range(4):
+            say("case %s masked partitions graph=%s replay %d" % (name, use_graph, rep))
             step.y.zero_()
             torch.cuda.synchronize()
             with torch.cuda.stream(st):
                 run.layer.forward(step.batch, sched, st)
+            say("  issued")
             st.synchronize()
+            say("  done")
             assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8)), (use_graph, rep)
             # eager work of the program itself between replays
             y1, _, _ = run.run(B.sequential())
