@@ -16,6 +16,7 @@
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
+#include <mutex>
 #include <string>
 #include <vector>
 
@@ -259,26 +260,39 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
     return DYN_OK;
 }
 
+// CU-masked streams are hardware queues whose mask is set through the driver.  They are made
+// once per distinct mask and stream id for the whole process, on an idle device, shared by
+// every layer handle and never destroyed: creating or destroying such a queue while other
+// queues are live has hung the runtime here (once mid-forward, twice in dyn_layer_destroy).
+struct MaskedStream {
+    int stream_id;
+    std::vector<uint32_t> mask;
+    hipStream_t stream;
+};
+std::vector<MaskedStream> g_masked_streams;
+std::mutex g_masked_mutex;
+
 dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream_t *out) {
     const int partition = key / DYN_MAX_STREAMS;
-    std::vector<uint32_t> mask;
-    if (partition > 0)
-        mask.assign(s->cu_masks + (size_t)(partition - 1) * s->cu_mask_words,
-                    s->cu_masks + (size_t)partition * s->cu_mask_words);
-    if (L->streams[key] && L->stream_mask[key] != mask) {   // partition redefined: rebuild the stream
-        HIP_TRY(hipStreamSynchronize(L->streams[key]));
-        HIP_TRY(hipStreamDestroy(L->streams[key]));
-        L->streams[key] = nullptr;
-    }
-    if (!L->streams[key]) {
-        if (partition > 0) {
-            // A CU-masked stream is a hardware queue of its own whose mask is set through the
-            // driver; do that on an idle device, never while kernels of a forward are in flight.
-            HIP_TRY(hipDeviceSynchronize());
-            HIP_TRY(hipExtStreamCreateWithCUMask(&L->streams[key], (uint32_t)mask.size(), mask.data()));
-        } else
-            HIP_TRY(hipStreamCreateWithFlags(&L->streams[key], hipStreamNonBlocking));
-        L->stream_mask[key] = mask;
+    if (partition > 0) {
+        std::vector<uint32_t> mask(s->cu_masks + (size_t)(partition - 1) * s->cu_mask_words,
+                                   s->cu_masks + (size_t)partition * s->cu_mask_words);
+        while (!mask.empty() && mask.back() == 0) mask.pop_back();      // trailing zero words name no CU
+        if (!L->streams[key] || L->stream_mask[key] != mask) {
+            std::lock_guard<std::mutex> lock(g_masked_mutex);
+            hipStream_t found = nullptr;
+            for (const MaskedStream &m : g_masked_streams)
+                if (m.stream_id == key % DYN_MAX_STREAMS && m.mask == mask) found = m.stream;
+            if (!found) {
+                HIP_TRY(hipDeviceSynchronize());
+                HIP_TRY(hipExtStreamCreateWithCUMask(&found, (uint32_t)mask.size(), mask.data()));
+                g_masked_streams.push_back(MaskedStream{key % DYN_MAX_STREAMS, mask, found});
+            }
+            L->streams[key] = found;
+            L->stream_mask[key] = mask;
+        }
+    } else if (!L->streams[key]) {
+        HIP_TRY(hipStreamCreateWithFlags(&L->streams[key], hipStreamNonBlocking));
     }
     *out = L->streams[key];
     return DYN_OK;
@@ -343,15 +357,25 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
                 err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
                 if (err != hipSuccess) break;
                 dyn::GemmGroups gr{counts, lists, n_pairs, c.top_k, c.n_experts, (size_t)2 * I * H, 0};
+                if (dyn::gemm_gated_supported(c.dtype, 2 * I, H)) {   // SiLU gate in the epilogue: DYN_OP_SILU has nothing left to do
+                    err = dyn::launch_gemm_gated(base + ws.h, ws.ld_h, w.w_gate_up, base + ws.act, ws.ld_act, gr, rows, 2 * I, H, st, mid);
+                    break;
+                }
                 err = dyn::launch_gemm_grouped(c.dtype, base + ws.h, ws.ld_h, w.w_gate_up, base + ws.gu,
                                                (float *)(base + ws.gemm_partial[2]), T * c.top_k * 2 * I, gr, rows, pair0,
                                                n_pairs, 2 * I, H, st, mid);
+                break;
+            }
+            if (dyn::gemm_gated_supported(c.dtype, 2 * I, H)) {       // SiLU gate in the epilogue: DYN_OP_SILU has nothing left to do
+                err = dyn::launch_gemm_gated(rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_gate_up, (void *)rowp(base + ws.act, ws.ld_act),
+                                             ws.ld_act, dyn::GemmGroups{}, rows, 2 * I, H, st, mid);
                 break;
             }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
                                    partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st, mid);
             break;
         case DYN_OP_SILU:
+            if (dyn::gemm_gated_supported(c.dtype, 2 * I, H)) break;   // done in the gate/up projection's epilogue
             if (c.n_experts) {
                 const size_t pair0 = (size_t)d.r0 * c.top_k;
                 err = dyn::launch_silu_mul(c.dtype, base + ws.gu + pair0 * 2 * I * e, base + ws.act + pair0 * ws.ld_act * e,
@@ -514,11 +538,13 @@ dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights
 
 void dyn_layer_destroy(dyn_layer *L) {
     if (!L) return;
+    (void)hipDeviceSynchronize();
     for (auto &g : L->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
     for (auto ev : L->events) (void)hipEventDestroy(ev);
     for (auto ev : L->prof_events) (void)hipEventDestroy(ev);
     if (L->fork_event) (void)hipEventDestroy(L->fork_event);
-    for (auto st : L->streams) if (st) (void)hipStreamDestroy(st);
+    for (int key = 0; key < DYN_MAX_STREAMS; ++key)          // plain side streams; masked ones are process-wide
+        if (L->streams[key]) (void)hipStreamDestroy(L->streams[key]);
     if (L->capture_stream) (void)hipStreamDestroy(L->capture_stream);
     delete L;
 }

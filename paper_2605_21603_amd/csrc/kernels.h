@@ -51,6 +51,13 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
                                size_t plane_stride, const GemmGroups &gr, int max_rows, int row0, int n_rows, int N, int K,
                                hipStream_t s, hipEvent_t mid = nullptr);
 
+// Gate/up projection with the SiLU gate applied in the epilogue (bf16, split factor 1 only):
+// Y[row, N2/2] = silu(X Wg^T) * (X Wu^T), row pitch ldy.  gr.n_groups = 0: plain, pointers offset to
+// the dispatch's first row, max_rows rows.  Grouped: as launch_gemm_grouped.
+bool gemm_gated_supported(int dtype, int N2, int K);
+hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int ldy, const GemmGroups &gr, int max_rows,
+                             int N2, int K, hipStream_t s, hipEvent_t mid = nullptr);
+
 // MoE router for token rows: logits = h W_r^T in fp32, top_k largest (ties to the lower index),
 // softmax over the selected logits.  sel / wgt are [rows, top_k], largest logit first.
 hipError_t launch_route(int dtype, const void *h, int ldh, const float *w_router, int32_t *sel, float *wgt, int rows,

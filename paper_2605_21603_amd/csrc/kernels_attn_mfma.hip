@@ -38,51 +38,58 @@ constexpr int kPrefillSets = 4;          // sets of 16 MFMA columns per wave for
 // the tokens of multi-token sequences (prefill chunks) in groups of up to tg1 = NQG * 16 / G.
 // One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
 // (first token row, chunk | tokens << 20) at list[2 + 2 i].
-__global__ __launch_bounds__(256) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
-                                                        const int32_t *__restrict__ pos_of_token, int rows, int ct,
-                                                        int tg1, int32_t *__restrict__ plan0, int32_t *__restrict__ plan1) {
-    __shared__ int scan[2][256];
-    __shared__ int base[2];
-    if (threadIdx.x < 2) base[threadIdx.x] = 0;
-    __syncthreads();
-    for (int t0 = 0; t0 < rows; t0 += 256) {
+__global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
+                                                         const int32_t *__restrict__ pos_of_token, int rows, int ct,
+                                                         int tg1, int32_t *__restrict__ plan0, int32_t *__restrict__ plan1) {
+    // One workgroup of 16 waves walks the rows 1024 at a time.  A sequence's tokens are adjacent
+    // rows with consecutive positions, so a token leads its group iff it starts its sequence or
+    // its aligned block, and the group's size is a count of independent look-ahead loads (no
+    // dependent chain).  Entry offsets come from a wave scan plus one LDS step per list.
+    __shared__ int wave_tot[2][16];
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+    int base0 = 0, base1 = 0;
+    for (int t0 = 0; t0 < rows; t0 += 1024) {
         const int t = t0 + threadIdx.x;
         int nc = 0, n_tok = 0, which = 0;
         if (t < rows) {
-            const int s = seq_of_token[t];
+            const int s = seq_of_token[t], p = pos_of_token[t];
             const bool prev_same = t > 0 && seq_of_token[t - 1] == s, next_same = t + 1 < rows && seq_of_token[t + 1] == s;
             which = prev_same || next_same;
-            const int tg = which ? tg1 : 1, blk = pos_of_token[t] / tg;
-            const bool leader = !prev_same || pos_of_token[t - 1] / tg != blk;
-            if (leader) {
+            const int tg = which ? tg1 : 1;
+            if (!prev_same || p % tg == 0) {                 // group leader
+                const int cand = tg - p % tg;                // positions left in the aligned block
                 n_tok = 1;
-                while (n_tok < tg && t + n_tok < rows && seq_of_token[t + n_tok] == s && pos_of_token[t + n_tok] / tg == blk)
-                    ++n_tok;
-                nc = (pos_of_token[t + n_tok - 1] + ct) / ct;        // chunks the group's last token reaches
+                for (int j = 1; j < 16; ++j)                 // tg <= 16: independent loads, matches form a prefix
+                    n_tok += (j < cand && t + j < rows && seq_of_token[t + j] == s) ? 1 : 0;
+                nc = (p + n_tok - 1 + ct) / ct;              // chunks the group's last token reaches
             }
         }
-        scan[0][threadIdx.x] = which ? 0 : nc;
-        scan[1][threadIdx.x] = which ? nc : 0;
+        int v0 = which ? 0 : nc, v1 = which ? nc : 0;        // inclusive wave scans of both lists
+#pragma unroll
+        for (int off = 1; off < 64; off <<= 1) {
+            const int u0 = __shfl_up(v0, off, 64), u1 = __shfl_up(v1, off, 64);
+            if (lane >= off) { v0 += u0; v1 += u1; }
+        }
+        if (lane == 63) { wave_tot[0][wave] = v0; wave_tot[1][wave] = v1; }
         __syncthreads();
-        for (int off = 1; off < 256; off <<= 1) {           // inclusive Hillis-Steele scans of both lists
-            const int v0 = threadIdx.x >= off ? scan[0][threadIdx.x - off] : 0;
-            const int v1 = threadIdx.x >= off ? scan[1][threadIdx.x - off] : 0;
-            __syncthreads();
-            scan[0][threadIdx.x] += v0;
-            scan[1][threadIdx.x] += v1;
-            __syncthreads();
+        int pre0 = 0, pre1 = 0, tot0 = 0, tot1 = 0;
+#pragma unroll
+        for (int w = 0; w < 16; ++w) {
+            if (w < wave) { pre0 += wave_tot[0][w]; pre1 += wave_tot[1][w]; }
+            tot0 += wave_tot[0][w];
+            tot1 += wave_tot[1][w];
         }
         int32_t *plan = which ? plan1 : plan0;
-        const int start = base[which] + scan[which][threadIdx.x] - nc;
+        const int start = which ? base1 + pre1 + v1 - nc : base0 + pre0 + v0 - nc;
         for (int c = 0; c < nc; ++c) {
             plan[2 + 2 * (start + c)] = t;
             plan[3 + 2 * (start + c)] = c | (n_tok << 20);
         }
-        __syncthreads();
-        if (threadIdx.x == 255) { base[0] += scan[0][255]; base[1] += scan[1][255]; }
-        __syncthreads();
+        base0 += tot0;
+        base1 += tot1;
+        __syncthreads();                                      // wave_tot is reused by the next batch
     }
-    if (threadIdx.x == 0) { plan0[0] = base[0]; plan1[0] = base[1]; }
+    if (threadIdx.x == 0) { plan0[0] = base0; plan1[0] = base1; }
 }
 
 // Persistent waves: wave w of the launch takes (entry, kv head) pairs w, w + n_waves, ...
@@ -307,8 +314,8 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     // two work lists per dispatch: single-token sequences, multi-token sequences
     const int G = sh.n_q / sh.n_kv, TG = 16 / G;
     int32_t *plan0 = plan, *plan1 = plan + 2 + 2 * (size_t)rows * sh.max_chunks;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(256), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
-                       kPrefillSets * TG, plan0, plan1);
+    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
+                       kPrefillSets * TG < 16 ? kPrefillSets * TG : 16, plan0, plan1);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;

@@ -85,6 +85,11 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // where there are enough tiles to fill the chip without spreading planes over workgroups and
 // the fp32 plane traffic would cost more than the weights.
 constexpr int BK = 64, ROWB = BK * 2;
+#ifndef DYN_BIG_BN             // tile and ring depth of the many-row (matrix-core-bound) regime
+#define DYN_BIG_BN 128
+#define DYN_BIG_MT 128
+#define DYN_BIG_NS 2
+#endif
 
 __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(n) only; n is one of a few literals
     // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
@@ -99,10 +104,16 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
     }
 }
 
-template <int BN, int MT, bool INREG, int NS>
+//
+// GATED (gate/up projection with S = 1): the tile's first half of W rows are gate rows, the
+// second half the matching up rows (N/2 further down), arranged so that a wave holds both for
+// its columns; the epilogue writes silu(gate) * up, N/2 wide with row pitch ldy, straight from
+// the fp32 accumulators.
+template <int BN, int MT, bool INREG, int NS, bool GATED>
 __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const bf16_t *__restrict__ X, int ldx, const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
-    bf16_t *__restrict__ Y, float *__restrict__ P, size_t plane_stride, int M, int N, int K, int S, GemmGroups gr) {
+    bf16_t *__restrict__ Y, int ldy, float *__restrict__ P, size_t plane_stride, int M, int N, int K, int S,
+    GemmGroups gr) {
     constexpr int ROWS = BN + MT;                   // rows of a stage buffer: W rows, then X rows
     constexpr int LPS = ROWS / 32;                  // direct loads per thread and stage (8 rows per wave instruction)
     constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
@@ -143,7 +154,12 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
         const int row = (j * 4 + wave) * 8 + (lane >> 3);
         const int col = (lane & 7) ^ ((row >> 1) & 7);
         if (row < BN) {
-            src[j] = W + (size_t)(n0 + row) * K + kbase + col * 8;
+            int n = n0 + row;
+            if (GATED) {   // stage row = wave half wn, then gate tiles, then up tiles
+                const int wn_r = row / (BN / 2), in_w = row % (BN / 2), up = in_w / (BN / 4);
+                n = n_tile * (BN / 2) + wn_r * (BN / 4) + in_w % (BN / 4) + up * (N / 2);
+            }
+            src[j] = W + (size_t)n * K + kbase + col * 8;
         } else {
             const int mr = min(m0 + row - BN, M - 1);
             src[j] = X + (size_t)(list ? list[mr] / gr.x_div : mr) * ldx + kbase + col * 8;
@@ -219,6 +235,26 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
         }
     }
 
+    if (GATED) {
+#pragma unroll
+        for (int a = 0; a < NA / 2; ++a)
+#pragma unroll
+            for (int b = 0; b < NB; ++b) {
+                const int m = m0 + wm * (MT / 2) + b * 16 + lr;
+                const int n = n_tile * (BN / 2) + wn * (BN / 4) + a * 16 + 4 * lq;
+                if (m >= M) continue;
+                const size_t orow = list ? list[m] : m;
+                const f32x4 g = acc[a][b], up = acc[a + NA / 2][b];
+                float o[4];
+#pragma unroll
+                for (int r = 0; r < 4; ++r) o[r] = g[r] / (1.0f + expf(-g[r])) * up[r];
+                u32x2 ov;
+                ov[0] = (uint32_t)f2bf(o[0]) | ((uint32_t)f2bf(o[1]) << 16);
+                ov[1] = (uint32_t)f2bf(o[2]) | ((uint32_t)f2bf(o[3]) << 16);
+                *reinterpret_cast<u32x2 *>(Y + orow * ldy + n) = ov;
+            }
+        return;
+    }
 #pragma unroll
     for (int a = 0; a < NA; ++a)
 #pragma unroll
@@ -244,20 +280,22 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
         }
 }
 
-template <int BN, int MT, bool INREG, int NS>
+template <int BN, int MT, bool INREG, int NS, bool GATED = false>
 hipError_t launch_gemm_bf16(int grid, hipStream_t s, const void *X, int ldx, const void *W, const void *R, void *Y,
-                            float *partial, size_t plane_stride, int rows, int N, int K, int S, const GemmGroups &gr) {
+                            float *partial, size_t plane_stride, int rows, int N, int K, int S, const GemmGroups &gr,
+                            int ldy = 0) {
     constexpr int STAGE = (BN + MT) * ROWB;
     static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "ring does not fit in LDS");
     static bool attr_set = false;                      // above 64 KB of dynamic LDS needs an opt-in, once
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS, GATED>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, NS * STAGE);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<BN, MT, INREG, NS>), dim3(grid), dim3(256), NS * STAGE, s, (const bf16_t *)X, ldx,
-                       (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, partial, plane_stride, rows, N, K, S, gr);
+    hipLaunchKernelGGL((gemm_bf16_kernel<BN, MT, INREG, NS, GATED>), dim3(grid), dim3(256), NS * STAGE, s,
+                       (const bf16_t *)X, ldx, (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, ldy ? ldy : N, partial,
+                       plane_stride, rows, N, K, S, gr);
     return hipGetLastError();
 }
 
@@ -317,11 +355,6 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
     // workgroups, a shallow ring and two workgroups per CU so that one multiplies while the other
     // waits at its barrier.  Few-row launches are bound by memory: deep ring, one workgroup per CU.
-#ifndef DYN_BIG_BN
-#define DYN_BIG_BN 128
-#define DYN_BIG_MT 128
-#define DYN_BIG_NS 2
-#endif
     const int big_tiles = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
     const bool big = N % DYN_BIG_BN == 0 && big_tiles >= 256;
     const bool inreg = S > 1 && big;
@@ -342,6 +375,30 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
                        (bf16_t *)Y, n_vec, S);
     return hipGetLastError();
+}
+
+bool gemm_gated_supported(int dtype, int N2, int K) { return dtype == 1 && gemm_split_k(dtype, N2, K) == 1; }
+
+// act[rows or listed rows, N2/2] = silu(X Wg^T) * (X Wu^T) with W = [gate rows; up rows] ([N2, K]),
+// output row pitch ldy.  Plain (gr.n_groups = 0: X, Y offset to the dispatch) or expert-grouped.
+hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int ldy, const GemmGroups &gr, int max_rows,
+                             int N2, int K, hipStream_t s, hipEvent_t mid) {
+    if (max_rows <= 0) return hipSuccess;
+    const int groups = gr.n_groups ? gr.n_groups : 1;
+    hipError_t e;
+    const int big_tiles = (N2 / DYN_BIG_BN) * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
+    if (!gr.n_groups && big_tiles >= 256) {
+        const int grid = (((N2 / DYN_BIG_BN) + 7) / 8) * 8 * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
+        e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0,
+                                                                            max_rows, N2, K, 1, gr, ldy);
+    } else {
+        const int MT = max_rows <= 64 ? 64 : 128;
+        const int grid = ((((N2 / 128) * groups) + 7) / 8) * 8 * ((max_rows + MT - 1) / MT);
+        if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+        else e = launch_gemm_bf16<128, 128, false, 4, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+    }
+    if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
+    return e;
 }
 
 // Expert-grouped form: group e multiplies the rows named by its list with its own weight
