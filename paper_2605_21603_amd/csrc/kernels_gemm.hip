@@ -85,30 +85,23 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // where there are enough tiles to fill the chip without spreading planes over workgroups and
 // the fp32 plane traffic would cost more than the weights.
 constexpr int BK = 64, ROWB = BK * 2;
+constexpr int kRotGroup = 32, kRotStep = 9;   // stage-order rotation of the bf16 kernel
 #ifndef DYN_BIG_BN             // tile and ring depth of the many-row (matrix-core-bound) regime
 #define DYN_BIG_BN 128
 #define DYN_BIG_MT 128
 #define DYN_BIG_NS 2
 #endif
 
-__device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(n) only; n is one of a few literals
+__device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(n) only; n folds to a literal <= 63
     // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
+#define DYN_W(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | ((N) & 15) | (((N) >> 4) << 14)); break;
     switch (n) {
-        case 0: __builtin_amdgcn_s_waitcnt(0x0f70); break;
-        case 6: __builtin_amdgcn_s_waitcnt(0x0f76); break;
-        case 8: __builtin_amdgcn_s_waitcnt(0x0f78); break;
-        case 12: __builtin_amdgcn_s_waitcnt(0x0f7c); break;
-        case 16: __builtin_amdgcn_s_waitcnt(0x4f70); break;
-        case 24: __builtin_amdgcn_s_waitcnt(0x4f78); break;
-        default: __builtin_amdgcn_s_waitcnt(0x0f70); break;
+        DYN_W(0) DYN_W(6) DYN_W(7) DYN_W(8) DYN_W(12) DYN_W(14) DYN_W(16) DYN_W(18) DYN_W(21) DYN_W(24) DYN_W(28) DYN_W(32)
+        default: __builtin_amdgcn_s_waitcnt(0x0f70); break;       // unknown count: wait for everything
     }
+#undef DYN_W
 }
 
-//
-// GATED (gate/up projection with S = 1): the tile's first half of W rows are gate rows, the
-// second half the matching up rows (N/2 further down), arranged so that a wave holds both for
-// its columns; the epilogue writes silu(gate) * up, N/2 wide with row pitch ldy, straight from
-// the fp32 accumulators.
 template <int BN, int MT, bool INREG, int NS, bool GATED>
 __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const bf16_t *__restrict__ X, int ldx, const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
@@ -165,11 +158,23 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
             src[j] = X + (size_t)(list ? list[mr] / gr.x_div : mr) * ldx + kbase + col * 8;
         }
     }
-    auto issue = [&](int st) {                         // all direct loads of stage st into ring buffer st % NS
+    // Stage order: the k stages of a plane are visited starting `rot` stages in and wrapping round,
+    // with rot a function of the n tile (groups of kRotGroup tiles share one).  Workgroups that run
+    // at the same time then read different column offsets of their 8 KB-pitched weight rows, which
+    // spreads the requests over the memory channels; tiles of one group keep reading the same X
+    // columns together, so X stays shared in L2.  The order depends on (N, K, n tile) only, never
+    // on the number of rows, so every schedule adds the same terms in the same order.
+    const int rot = (int)(((unsigned)(n_tile / kRotGroup) * kRotStep) % (unsigned)plane_stages);
+    int iss_w = 0, iss_base = 0;                       // next stage to issue: index inside its plane, plane's first stage
+    auto issue = [&](int st) {                         // all direct loads of stage st into ring buffer st % NS; st ascends by one per call
         unsigned char *buf = lds + (st % NS) * STAGE;
+        int kst = iss_w + rot;
+        if (kst >= plane_stages) kst -= plane_stages;
+        kst += iss_base;
+        if (++iss_w == plane_stages) { iss_w = 0; iss_base += plane_stages; }
 #pragma unroll
         for (int j = 0; j < LPS; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)st * BK),
+            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)kst * BK),
                                              (__attribute__((address_space(3))) void *)(buf + (j * 4 + wave) * 8 * ROWB),
                                              16, 0, 0);
     };
@@ -202,7 +207,9 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
     for (int st = 0; st < n_stage; ++st) {
         // stage st has landed when at most the loads of the stages issued after it are outstanding
         const int ahead = min(NS - 2, n_stage - 1 - st);
-        if (ahead >= 2) wait_vmcnt(2 * LPS);
+        if (ahead >= 4) wait_vmcnt(4 * LPS);
+        else if (ahead == 3) wait_vmcnt(3 * LPS);
+        else if (ahead == 2) wait_vmcnt(2 * LPS);
         else if (ahead == 1) wait_vmcnt(LPS);
         else wait_vmcnt(0);
         // Bare barrier: __syncthreads() would add a fence that drains every outstanding load, which
@@ -285,7 +292,7 @@ hipError_t launch_gemm_bf16(int grid, hipStream_t s, const void *X, int ldx, con
                             float *partial, size_t plane_stride, int rows, int N, int K, int S, const GemmGroups &gr,
                             int ldy = 0) {
     constexpr int STAGE = (BN + MT) * ROWB;
-    static_assert(NS >= 2 && NS <= 4 && NS * STAGE <= 160 * 1024, "ring does not fit in LDS");
+    static_assert(NS >= 2 && NS <= 6 && NS * STAGE <= 160 * 1024, "ring does not fit in LDS");
     static bool attr_set = false;                      // above 64 KB of dynamic LDS needs an opt-in, once
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS, GATED>,
@@ -329,12 +336,9 @@ bool gemm_supported(int dtype, int N, int K) {
 int gemm_split_k(int dtype, int N, int K) {
     if (dtype == 0) return 1;
     // enough workgroups to occupy 256 CUs twice over, chunks of at least 8 k-steps
-    static int forced = -1;
-    if (forced < 0) { const char *e = getenv("DYN_GEMM_SPLIT"); forced = e ? atoi(e) : 0; }
     // planes of at least four stages; enough (128-row tile, plane) pairs to occupy the chip
     int S = 1;
     while ((N / 128) * S < 192 && K % (S * 2 * BK) == 0 && K / (S * 2) >= 4 * BK * 2) S *= 2;
-    if (forced > 0 && K % (forced * BK) == 0) S = forced;
     return S;
 }
 
