@@ -6,8 +6,10 @@ A step is one pass of the whole layer (norms, projections, rotary + cache append
 attention, gated MLP) over one batch of seeded synthetic input that is resident in HBM
 before the timed region.  The default workload is the Llama-3-8B-shaped decode layer at
 batch 128 with contexts uniform in [512, 4096].  The step is timed under the sequential
-schedule and under overlapped two-micro-batch schedules; `value` is the best overlapped
-schedule's tokens/s, the sequential figure is reported beside it.  Prints one JSON line.
+schedule and under overlapped two-micro-batch schedules; `value` is the tokens/s of the
+fastest of them (the method falls back to the sequential order when splitting does not pay),
+`config.schedule` names it, and the sequential and best overlapped figures are reported
+beside it.  Prints one JSON line.
 """
 import argparse
 import json
@@ -22,6 +24,14 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0        # MI355X HBM3E, published
 MFMA_BF16_PEAK_TFLOPS = 2500.0
 
+# HBM bytes per launch of the attention kernel, read with rocprofv3 counters (FETCH_SIZE and
+# WRITE_SIZE in runs of their own, scaled by a 1 GiB copy probe).  Counters cannot be read
+# from inside this process, so the figure of the committed counter summary is repeated here.
+ROCPROF_TRAFFIC = {
+    "c2": {"bytes": 1273515213 + 21788877,
+           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,834 x 2.0 KiB + WRITE_SIZE 21,278 KiB)"},
+}
+
 
 def log(msg):
     print(msg, file=sys.stderr, flush=True)
@@ -32,6 +42,19 @@ def candidate_schedules(B, w, use_graph):
     chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
     mlp = [B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN]
     gemms = [B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP, B.DYN_OP_DOWN]
+    if w.shape.n_layers > 1:
+        # the many-layer step: two and four micro-batches, plain and CU-partitioned streams
+        lo, hi = [0x0000FFFF] * 8, [0xFFFF0000] * 8
+        T = w.n_tokens
+        r4 = tuple(T * i // 4 for i in range(5))
+        return {
+            "k2_mlp_merged_stagger2": B.nano_schedule(rows, chain, merged_ops=mlp, stagger=2, use_graph=use_graph),
+            "k2_split_stagger2_cu_partitioned": B.nano_schedule(rows, chain, stagger=2, partitions=[1, 2], cu_masks=[lo, hi],
+                                                                use_graph=use_graph),
+            "k4_mlp_merged_stagger1_cu_partitioned": B.nano_schedule(r4, chain, merged_ops=mlp, stagger=1,
+                                                                     partitions=[1, 2, 1, 2], streams=[0, 1, 2, 3],
+                                                                     cu_masks=[lo, hi], use_graph=use_graph),
+        }
     return {
         "k2_split_stagger0": B.nano_schedule(rows, chain, stagger=0, use_graph=use_graph),
         "k2_split_stagger2": B.nano_schedule(rows, chain, stagger=2, use_graph=use_graph),
@@ -86,7 +109,10 @@ def cpu_baseline(w, data, n_sample=128):
     ctx = [c for _, c in w.seqs]
     order = np.argsort(ctx)
     picks = sorted({int(order[0]), int(order[-1])} | {int(i) for i in order[:: max(1, len(order) // n_sample)][:n_sample]})
-    w2, d2 = gen.sub_batch(w, data, picks)
+    if data["x"].device.type == "cpu":
+        w2, d2 = gen.sub_batch(w, data, picks)
+    else:                                   # generated in device memory: copy the sampled sequences out
+        w2, d2 = gen.extract_sequences(w, data, picks)
     sh = w.shape
     dt = orc.dtype_code(sh.dtype)
     x = orc.widen(orc.to_storage(d2["x"]), dt)
@@ -137,7 +163,12 @@ def main():
 
     w = gen.config(args.workload)
     log("generating %s (seed %d) ..." % (w.name, w.seed))
-    data = gen.generate(w)
+    if w.shape.n_layers > 1:                # caches beyond host memory: drawn directly in device memory
+        data = gen.generate(w, device="cuda:0", stacked=True)
+        torch.cuda.synchronize()
+        log("generated in device memory: %.1f GB allocated" % (torch.cuda.memory_allocated() / 1e9))
+    else:
+        data = gen.generate(w)
     weights = [{k: v.to("cuda:0") for k, v in lw.items()} for lw in data["weights"]]
     layer = B.DynLayer(B.make_config(w.shape), weights)
     step = B.DeviceStep(layer, data)
@@ -154,7 +185,8 @@ def main():
     for name, sched in cands.items():
         results[name] = time_schedule(layer, step, sched, stream, args.steps, args.warmup)
         log("%s: %.1f us/step" % (name, results[name] * 1e3))
-    best = min((k for k in results if k != "sequential" or len(results) == 1), key=lambda k: results[k])
+    best_ovl = min((k for k in results if k != "sequential" or len(results) == 1), key=lambda k: results[k])
+    best = min(results, key=lambda k: results[k])
 
     # Dominant kernel (paged attention): average launch duration from HIP events recorded on
     # its own stream around the kernel, over `steps` eager sequential forwards.
@@ -176,6 +208,7 @@ def main():
     attn_gb = attention_bytes(w) / 1e9
     achieved = attn_gb / (attn_avg_ms * 1e-3)
 
+    traffic = ROCPROF_TRAFFIC.get(w.name)
     byts, flops = layer_bytes_flops(w)
     t_roof_ms = max(byts / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
     T = w.n_tokens
@@ -190,18 +223,22 @@ def main():
                    "schedule": best, "nano_rows": list(w.nano_rows), "hip_graph": use_graph},
         "sequential_tokens_per_s": T / (results["sequential"] * 1e-3),
         "sequential_ms_per_step": results["sequential"],
-        "overlap_speedup": results["sequential"] / results[best],
+        "best_overlapped_schedule": best_ovl,
+        "best_overlapped_ms_per_step": results[best_ovl],
+        "overlap_speedup": results["sequential"] / results[best_ovl],
         "schedules_ms": results,
         "layer_roofline": {"algorithmic_bytes": byts, "algorithmic_flops": flops, "t_roof_ms": t_roof_ms,
-                           "frac_overlapped": t_roof_ms / results[best], "frac_sequential": t_roof_ms / results["sequential"]},
+                           "frac_overlapped": t_roof_ms / results[best_ovl], "frac_sequential": t_roof_ms / results["sequential"]},
         "op_ms_sequential_eager": {k: sum(v) / len(v) for k, v in op_ms.items()},
         "roofline": {"bound": "hbm", "kernel": "attn_mfma_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
-                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": traffic["bytes"] if traffic else None,
+                     "traffic_source": traffic["source"] if traffic else None,
                      "bytes_per_launch": attention_bytes(w), "avg_launch_ms": attn_avg_ms},
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample ...")
-        out["cpu_baseline"] = cpu_baseline(w, data)
+        out["cpu_baseline"] = cpu_baseline(w, data, 128 if w.shape.n_layers == 1 else 6)
     print(json.dumps(out), flush=True)
 
 
