@@ -168,6 +168,74 @@ typedef struct {
 dyn_status dyn_layer_set_profiling(dyn_layer *layer, int on);
 dyn_status dyn_layer_get_slot_times(dyn_layer *layer, dyn_slot_time *out, int capacity, int *n_out);
 
+/* ---- Programmable scheduling (Section 3.2.2, Figure 6) -------------------------------
+ *
+ * The paper lets a strategy author write the schedule as a short program over three
+ * calls: split the batch into micro-batches of chosen sizes, ask which operators of a
+ * micro-batch are ready, and execute operators on a stream.  dyn_scheduler is that
+ * interface as a recorder: the calls below check each step against the ready-operator
+ * rule as it is made and append to a dyn_schedule that dyn_layer_forward then runs (and
+ * replays as a HIP graph).  Host only; no GPU call, no device memory. */
+typedef struct dyn_scheduler dyn_scheduler;
+
+/* A recorder for batches of this token / sequence structure.  q_start_host as in dyn_batch
+ * (copied).  The operator chain (dense or MoE) comes from cfg. */
+dyn_status dyn_scheduler_create(const dyn_layer_config *cfg, int n_tokens, int n_seqs, const int32_t *q_start_host,
+                                dyn_scheduler **out);
+void dyn_scheduler_destroy(dyn_scheduler *s);
+
+/* split([bs_1 .. bs_k]): micro-batch sizes in tokens, unequal sizes allowed, zero allowed;
+ * they must add up to n_tokens and every cut must fall on a sequence boundary.  Discards
+ * anything recorded before.  Without a split the batch is one micro-batch. */
+dyn_status dyn_scheduler_split(dyn_scheduler *s, int k, const int32_t *sizes);
+
+/* CU partitions that execute calls may name (1..n_partitions; 0 is the whole device). */
+dyn_status dyn_scheduler_set_partitions(dyn_scheduler *s, int n_partitions, const uint32_t *cu_masks, int cu_mask_words);
+
+/* get_ready_ops(i): the operators of micro-batch `nano` whose predecessors have been
+ * executed and that have not been executed themselves.  Writes at most `capacity` operator
+ * codes to ops and returns how many are ready (0: the micro-batch has finished the layer;
+ * the layer's operators form a chain, so the answer is 0 or 1); -1 on a bad argument. */
+int dyn_scheduler_get_ready_ops(const dyn_scheduler *s, int nano, uint8_t *ops, int capacity);
+
+/* execute(ops, stream): n (operator, micro-batch) pairs.
+ *   n = 1                                   split form: one micro-batch's operator.
+ *   same operator, adjacent micro-batches   merge form: one dispatch over their joint rows.
+ *   anything else                           no fused kernel exists for different operators:
+ *                                           the sequential fallback, one dispatch per pair,
+ *                                           in the order given, all on this stream.
+ * Every pair must be ready (DYN_ERR_SCHEDULE otherwise, nothing recorded).  stream is
+ * 0..DYN_MAX_STREAMS-1 within CU partition `partition`; stream 0 of partition 0 is the
+ * stream the forward is called on. */
+dyn_status dyn_scheduler_execute(dyn_scheduler *s, int n, const uint8_t *ops, const uint8_t *nanos, int stream,
+                                 int partition);
+
+/* Ends the recording: fails with DYN_ERR_SCHEDULE if some micro-batch has not finished
+ * the chain.  *out borrows arrays owned by the scheduler: it stays valid until the next
+ * split or destroy.  The recorded issue order is that of one layer and repeats per layer. */
+dyn_status dyn_scheduler_finish(dyn_scheduler *s, int use_graph, dyn_schedule *out);
+
+/* ---- Cost model and built-in policy (Section 2.1 "Splitting"; Section 5.3.1) ---------
+ *
+ * Splitting pays when a compute-bound operator of one micro-batch can run beside a
+ * memory-bound operator of another, and costs a second read of the weights.  The policy
+ * estimates every operator from its algorithmic bytes and FLOPs and this GPU's measured
+ * rates, compares the sequential order with a two-micro-batch split at the boundary
+ * between multi-token (prefill) and single-token (decode) sequences, and records the
+ * winner through the scheduler calls above. */
+typedef struct {
+    int split;                   /* 0: sequential order chosen; 1: two micro-batches */
+    int cut_row;                 /* rows [0, cut_row) | [cut_row, n_tokens) when split */
+    float est_sequential_us;     /* model's estimate of one layer, sequential */
+    float est_split_us;          /* model's estimate of one layer, split (0 if no legal cut) */
+} dyn_policy_choice;
+
+/* ctx_len_host[s] = keys sequence s attends including this step's tokens (HOST, n_seqs).
+ * Records the chosen schedule into s (discarding earlier recordings) and fills *out;
+ * choice may be NULL. */
+dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int use_graph, dyn_schedule *out,
+                           dyn_policy_choice *choice);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *dyn_last_error(void);
 

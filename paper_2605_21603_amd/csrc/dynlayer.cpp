@@ -23,7 +23,7 @@
 
 #include "kernels.h"
 
-namespace {
+namespace dyn {
 
 thread_local std::string g_err;
 
@@ -36,6 +36,13 @@ dyn_status fail(dyn_status st, const char *fmt, ...) {
     g_err = buf;
     return st;
 }
+
+}  // namespace dyn
+
+namespace {
+
+using dyn::fail;
+using dyn::g_err;
 
 #define HIP_TRY(expr)                                                                                  \
     do {                                                                                               \

@@ -96,7 +96,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
     // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
 #define DYN_W(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | ((N) & 15) | (((N) >> 4) << 14)); break;
     switch (n) {
-        DYN_W(0) DYN_W(6) DYN_W(7) DYN_W(8) DYN_W(12) DYN_W(14) DYN_W(16) DYN_W(18) DYN_W(21) DYN_W(24) DYN_W(28) DYN_W(32)
+        DYN_W(0) DYN_W(6) DYN_W(7) DYN_W(8) DYN_W(9) DYN_W(12) DYN_W(14) DYN_W(16) DYN_W(18) DYN_W(21) DYN_W(24) DYN_W(27) DYN_W(28) DYN_W(32)
         default: __builtin_amdgcn_s_waitcnt(0x0f70); break;       // unknown count: wait for everything
     }
 #undef DYN_W
@@ -364,9 +364,23 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     const bool inreg = S > 1 && big;
     hipError_t e;
     if (big) {
-        const int grid = (((N / DYN_BIG_BN) + 7) / 8) * 8 * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-        if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-        else e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+        // Tile height: two workgroups fit a CU, so 512 tiles run at a time and the launch takes
+        // ceil(tiles / 512) rounds of a duration proportional to the tile height.  A taller
+        // tile that saves a round wins (2112 rows x 4096 columns: 544 tiles of 128 rows need
+        // two rounds, 448 tiles of 160 rows one).  The summation order of an output element
+        // does not depend on the tile height.
+        const int nt = N / DYN_BIG_BN;
+        const long cost128 = (long)((nt * ((rows + 127) / 128) + 511) / 512) * 128;
+        const long cost160 = (long)((nt * ((rows + 159) / 160) + 511) / 512) * 160;
+        if (cost160 < cost128) {
+            const int grid = ((nt + 7) / 8) * 8 * ((rows + 159) / 160);
+            if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, 160, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+            else e = launch_gemm_bf16<DYN_BIG_BN, 160, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+        } else {
+            const int grid = ((nt + 7) / 8) * 8 * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
+            if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+            else e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+        }
     } else {
         const int grid = ((((N / 128) * S) + 7) / 8) * 8 * m_tiles;
         if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
