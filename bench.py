@@ -130,6 +130,52 @@ def cpu_baseline(w, data, n_sample=128):
                       % (len(picks), w.n_seqs, dt_s)}
 
 
+def policy_sweep(args):
+    """Where splitting starts to pay: a prefill chunk of P tokens beside D decode sequences at
+    context C, Llama-3-8B layer.  For every point: measured sequential and split (two
+    streams, round-robin issue; HIP-graph replays), the cost model's two estimates and the
+    policy's choice.  Prints one JSON object with the table."""
+    import torch
+    from paper_2605_21603_amd import binding as B
+    from workloads import gen
+    rows, weights, layer = [], None, None
+    stream = torch.cuda.Stream()
+    for P in (256, 512, 1024, 2048, 4096):
+        for D, Cx in ((64, 2048), (64, 8192), (256, 2048), (256, 8192)):
+            w = gen.mixed(P, D, Cx)
+            data = gen.generate(w, device="cuda:0")
+            if layer is None:                       # the same layer weights serve every point
+                weights = data["weights"]
+                layer = B.DynLayer(B.make_config(w.shape), weights)
+            data["weights"] = weights
+            step = B.DeviceStep(layer, data)
+            md = gen.metadata(w)
+            sch = B.Scheduler(B.make_config(w.shape), md["q_start"])
+            _, choice = sch.auto(md["ctx_len"], use_graph=True)
+            sch.split([P, D])
+            while sch.get_ready_ops(0) or sch.get_ready_ops(1):
+                for b in range(2):
+                    r = sch.get_ready_ops(b)
+                    if r:
+                        sch.execute([(r[0], b)], stream=b)
+            split = sch.finish(use_graph=True)
+            t_seq = time_schedule(layer, step, B.sequential(use_graph=True), stream, args.steps, args.warmup)
+            t_split = time_schedule(layer, step, split, stream, args.steps, args.warmup)
+            rows.append({"prefill_tokens": P, "decodes": D, "decode_ctx": Cx, "sequential_us": t_seq * 1e3,
+                         "split_us": t_split * 1e3, "est_sequential_us": choice["est_sequential_us"],
+                         "est_split_us": choice["est_split_us"], "policy_split": choice["split"],
+                         "split_is_faster": t_split < t_seq})
+            log("P=%4d D=%3d ctx=%4d  sequential %7.1f us (model %7.1f)  split %7.1f us (model %7.1f)  policy: %s  measured: %s"
+                % (P, D, Cx, t_seq * 1e3, choice["est_sequential_us"], t_split * 1e3, choice["est_split_us"],
+                   "split" if choice["split"] else "sequential", "split" if t_split < t_seq else "sequential"))
+            del step, data
+            torch.cuda.empty_cache()
+    agree = sum(r["policy_split"] == r["split_is_faster"] for r in rows)
+    regret = [min(r["sequential_us"], r["split_us"]) / (r["split_us"] if r["policy_split"] else r["sequential_us"]) for r in rows]
+    print(json.dumps({"policy_sweep": rows, "policy_agrees_with_measurement": "%d of %d" % (agree, len(rows)),
+                      "worst_policy_efficiency": min(regret)}), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -141,9 +187,15 @@ def main():
     ap.add_argument("--schedules", default="all",
                     help="comma-separated overlapped schedules to time beside sequential ('all', or 'none')")
     ap.add_argument("--no-event-profile", action="store_true", help="skip the per-operator HIP-event pass")
+    ap.add_argument("--policy-sweep", action="store_true",
+                    help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device-to-device five times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     args = ap.parse_args()
+    if args.policy_sweep:
+        if args.gpus != 1:
+            sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
+        return policy_sweep(args)
     if args.gpus != 1:
         sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
 

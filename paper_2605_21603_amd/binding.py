@@ -55,6 +55,10 @@ class dyn_schedule(C.Structure):
                 ("slots", C.c_void_p), ("use_graph", C.c_int)]
 
 
+class dyn_policy_choice(C.Structure):
+    _fields_ = [("split", C.c_int), ("cut_row", C.c_int), ("est_sequential_us", C.c_float), ("est_split_us", C.c_float)]
+
+
 class dyn_slot_time(C.Structure):
     _fields_ = [("layer", C.c_int), ("op", C.c_int), ("nano", C.c_int), ("n_nano", C.c_int), ("stream", C.c_int),
                 ("partition", C.c_int), ("start_ms", C.c_float), ("main_start_ms", C.c_float), ("main_stop_ms", C.c_float),
@@ -62,7 +66,9 @@ class dyn_slot_time(C.Structure):
 
 
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
-           "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error"]
+           "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
+           "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
+           "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto"]
 
 _lib = None
 
@@ -84,6 +90,15 @@ def lib() -> C.CDLL:
         l.dyn_layer_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
         l.dyn_layer_get_slot_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
+        l.dyn_scheduler_create.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
+        l.dyn_scheduler_destroy.argtypes = [C.c_void_p]
+        l.dyn_scheduler_destroy.restype = None
+        l.dyn_scheduler_split.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        l.dyn_scheduler_set_partitions.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+        l.dyn_scheduler_get_ready_ops.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_int]
+        l.dyn_scheduler_execute.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
+        l.dyn_scheduler_finish.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
+        l.dyn_policy_auto.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         _lib = l
     return _lib
 
@@ -167,6 +182,83 @@ def nano_schedule(nano_rows: Sequence[int], chain: Sequence[int] = DENSE_CHAIN, 
                 pos = [p + 1 for p in pos]
         tick += 1
     return Schedule(DYN_SCHED_EXPLICIT, list(nano_rows), slots, max(streams) + 1, cu_masks, use_graph)
+
+
+class RecordedSchedule:
+    """A dyn_schedule filled in by the library's scheduler; it borrows the scheduler's
+    arrays, so it keeps the scheduler alive.  Accepted wherever a Schedule is."""
+
+    def __init__(self, scheduler: "Scheduler", c_sched: dyn_schedule):
+        self._scheduler = scheduler
+        self._c = c_sched
+
+    def to_c(self) -> dyn_schedule:
+        return self._c
+
+    @property
+    def slots(self) -> List[tuple]:
+        arr = C.cast(self._c.slots, C.POINTER(dyn_slot))
+        return [(arr[i].op, arr[i].nano, arr[i].n_nano, arr[i].stream, arr[i].partition) for i in range(self._c.n_slots)]
+
+    @property
+    def nano_rows(self) -> List[int]:
+        arr = C.cast(self._c.nano_rows, C.POINTER(C.c_int32))
+        return [arr[i] for i in range(self._c.k + 1)]
+
+
+class Scheduler:
+    """The library's schedule recorder: split / get_ready_ops / execute / finish.  A
+    strategy is a short program over these calls; every call is checked by the library."""
+
+    def __init__(self, cfg: dyn_layer_config, q_start: Sequence[int]):
+        self._q = np.ascontiguousarray(q_start, dtype=np.int32)
+        self._h = C.c_void_p()
+        _check(lib().dyn_scheduler_create(C.byref(cfg), int(self._q[-1]), len(self._q) - 1, _ptr(self._q), C.byref(self._h)))
+
+    def close(self):
+        if self._h:
+            lib().dyn_scheduler_destroy(self._h)
+            self._h = C.c_void_p()
+
+    def __del__(self):
+        try:
+            self.close()
+        except Exception:
+            pass
+
+    def split(self, sizes: Sequence[int]) -> None:
+        a = np.ascontiguousarray(sizes, dtype=np.int32)
+        _check(lib().dyn_scheduler_split(self._h, len(a), _ptr(a)))
+
+    def set_partitions(self, cu_masks: Sequence[Sequence[int]]) -> None:
+        m = np.ascontiguousarray(cu_masks, dtype=np.uint32).reshape(len(cu_masks), -1) if len(cu_masks) else np.zeros((0, 1), np.uint32)
+        _check(lib().dyn_scheduler_set_partitions(self._h, m.shape[0], _ptr(m) if m.shape[0] else None, m.shape[1] if m.shape[0] else 0))
+
+    def get_ready_ops(self, nano: int) -> List[int]:
+        buf = (C.c_uint8 * DYN_N_OPS)()
+        n = lib().dyn_scheduler_get_ready_ops(self._h, nano, buf, DYN_N_OPS)
+        if n < 0:
+            raise DynError(DYN_ERR_INVALID_ARG, dyn_last_error())
+        return [buf[i] for i in range(n)]
+
+    def execute(self, pairs: Sequence[Sequence[int]], stream: int = 0, partition: int = 0) -> None:
+        """pairs: (operator, micro-batch) tuples."""
+        ops = (C.c_uint8 * max(1, len(pairs)))(*[p[0] for p in pairs])
+        nanos = (C.c_uint8 * max(1, len(pairs)))(*[p[1] for p in pairs])
+        _check(lib().dyn_scheduler_execute(self._h, len(pairs), ops, nanos, stream, partition))
+
+    def finish(self, use_graph: bool = False) -> RecordedSchedule:
+        c = dyn_schedule()
+        _check(lib().dyn_scheduler_finish(self._h, int(use_graph), C.byref(c)))
+        return RecordedSchedule(self, c)
+
+    def auto(self, ctx_len: Sequence[int], use_graph: bool = False):
+        """The built-in policy: returns (schedule, choice dict)."""
+        ctx = np.ascontiguousarray(ctx_len, dtype=np.int32)
+        c, ch = dyn_schedule(), dyn_policy_choice()
+        _check(lib().dyn_policy_auto(self._h, _ptr(ctx), int(use_graph), C.byref(c), C.byref(ch)))
+        return RecordedSchedule(self, c), {"split": bool(ch.split), "cut_row": ch.cut_row,
+                                           "est_sequential_us": ch.est_sequential_us, "est_split_us": ch.est_split_us}
 
 
 class DynLayer:

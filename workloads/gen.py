@@ -90,6 +90,16 @@ def _uniform_ctx(seed: int, n: int, lo: int, hi: int) -> List[int]:
     return [int(v) for v in rng.integers(lo, hi + 1, size=n)]
 
 
+def mixed(prefill_tokens: int, n_decode: int, decode_ctx: int, shape: LayerShape = LLAMA3_8B, seed: int = 0) -> Workload:
+    """One prefill chunk with no prior context followed by n_decode single-token sequences
+    that all attend decode_ctx keys (the shape family of configuration 3); either part may
+    be absent.  Default cut: the prefill / decode boundary."""
+    seqs = (((prefill_tokens, prefill_tokens),) if prefill_tokens else ()) + tuple((1, decode_ctx) for _ in range(n_decode))
+    T = prefill_tokens + n_decode
+    return Workload("mix_p%d_d%dx%d" % (prefill_tokens, n_decode, decode_ctx), shape, seqs, seed,
+                    (0, prefill_tokens, T) if prefill_tokens and n_decode else (0, T))
+
+
 def config(name: str) -> Workload:
     """The named workloads: c1..c5 are the five benchmark configurations, the *_small
     ones are reduced shapes the CPU oracle finishes in seconds."""
