@@ -306,8 +306,8 @@ dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream
     return DYN_OK;
 }
 
-dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws, const Dispatch &d, hipStream_t st,
-                     hipEvent_t mid, hipEvent_t pre) {
+dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, const WsLayout &ws, const Dispatch &d,
+                     hipStream_t st, hipEvent_t mid, hipEvent_t pre) {
     const dyn_layer_config &c = L->cfg;
     const dyn_layer_weights &w = L->w[d.layer];
     const size_t e = esize(c);
@@ -320,7 +320,10 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const WsLayout &ws,
     char *x_out = d.layer == nl - 1 ? (char *)b->y : (d.layer % 2 ? base + ws.xb : base + ws.xa);
     auto rowp = [&](const char *p, int width) { return p + (size_t)d.r0 * width * e; };
     const size_t T = (size_t)b->n_tokens;
-    dyn::AttnShape sh{c.n_q_heads, c.n_kv_heads, c.head_dim, c.page_size, b->max_pages_per_seq, L->chunk_pages, ws.max_chunks};
+    dyn::AttnShape sh{c.n_q_heads, c.n_kv_heads, c.head_dim, c.page_size, b->max_pages_per_seq, L->chunk_pages, ws.max_chunks, 0};
+    if (d.partition > 0 && s->mode == DYN_SCHED_EXPLICIT)
+        for (int i = 0; i < s->cu_mask_words; ++i)
+            sh.n_cus += __builtin_popcount(s->cu_masks[(d.partition - 1) * s->cu_mask_words + i]);
     char *kc = (char *)b->k_cache + (size_t)d.layer * b->kv_layer_stride;
     char *vc = (char *)b->v_cache + (size_t)d.layer * b->kv_layer_stride;
     auto partial = [&](int i, int width) { return (float *)(base + ws.gemm_partial[i]) + (size_t)d.r0 * width; };
@@ -461,7 +464,7 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
             for (int j = 1; j <= 3; ++j) HIP_TRY(hipEventRecord(L->prof_events[j + 4 * i], st));
         }
         const bool mark = profile && d.r1 > d.r0;
-        dyn_status rc = launch_op(L, b, ws, d, st, mark ? L->prof_events[3 + 4 * i] : nullptr,
+        dyn_status rc = launch_op(L, b, s, ws, d, st, mark ? L->prof_events[3 + 4 * i] : nullptr,
                                   mark ? L->prof_events[2 + 4 * i] : nullptr);
         if (rc != DYN_OK) return rc;
         if (profile) HIP_TRY(hipEventRecord(L->prof_events[4 + 4 * i], st));

@@ -19,6 +19,7 @@ struct AttnShape {
     int max_pages_per_seq;         // block-table row length
     int chunk_pages;               // pages per split-KV chunk (a constant of the layer)
     int max_chunks;                // chunks that fit max_pages_per_seq: stride of the partial arrays
+    int n_cus;                     // CUs of the stream's partition (0: whole device); sizes the persistent launch
 };
 
 // Expert grouping of a projection (all fields zero: plain GEMM).  Group e has counts[e] rows;

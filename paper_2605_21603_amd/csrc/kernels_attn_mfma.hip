@@ -320,13 +320,16 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
     const long max_items = (long)rows * sh.n_kv * sh.max_chunks;
-    const int grid = (int)((max_items + 3) / 4 < kPersistentGroups ? (max_items + 3) / 4 : kPersistentGroups);
+    // every workgroup of a persistent launch has to be resident at once (the work is dealt out by
+    // wave index): two per CU of the partition the stream runs on
+    const int groups = sh.n_cus > 0 && 2 * sh.n_cus < kPersistentGroups ? 2 * sh.n_cus : kPersistentGroups;
+    const int grid = (int)((max_items + 3) / 4 < groups ? (max_items + 3) / 4 : groups);
     hipLaunchKernelGGL(attn_mfma_kernel<1>, dim3(grid), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
                        plan0);
     e = hipGetLastError();
     if (e == hipSuccess && any_multi) {
-        const int grid1 = (int)((max_items + 3) / 4 < kPersistentGroups / 2 ? (max_items + 3) / 4 : kPersistentGroups / 2);
+        const int grid1 = (int)((max_items + 3) / 4 < groups / 2 ? (max_items + 3) / 4 : groups / 2);
         hipLaunchKernelGGL(attn_mfma_kernel<kPrefillSets>, dim3(grid1), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
                            pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml,
                            sh, plan1);
