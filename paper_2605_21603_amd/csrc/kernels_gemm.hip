@@ -116,8 +116,18 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
     // m tiles of one (n tile, plane)) get ids 8 apart: same XCD, same L2, adjacent in time.
     const int u = blockIdx.x % 8, v = blockIdx.x / 8;
-    const int m_tile = v % m_tiles;
+    int m_tile = v % m_tiles;
     int ns = (v / m_tiles) * 8 + u;
+    if (gr.n_groups) {
+        // Expert-grouped launches size the grid for the largest possible group, so most tiles
+        // past the first m tile are empty.  All first m tiles come first and the mostly empty
+        // ones trail the launch (interleaved, every second workgroup was an empty one that
+        // still had to wait for a free 128 KB LDS slot, and the launch took twice as long);
+        // an m tile keeps the XCD of its n tile.
+        const int per_m = gridDim.x / m_tiles;         // a multiple of 8
+        m_tile = blockIdx.x / per_m;
+        ns = blockIdx.x % per_m;
+    }
     const int32_t *list = nullptr;
     const int SG = INREG ? 1 : S;                      // planes spread over the grid
     if (gr.n_groups) {                                 // grouped: (expert, n tile, plane); rows come from the expert's list
