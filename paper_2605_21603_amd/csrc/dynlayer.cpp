@@ -131,7 +131,7 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
     w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
     w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
-    w.plan = take((t * w.max_chunks + t) * 4 * sizeof(int32_t));   // per dispatch: two lists of 2 header words + 2 per entry
+    w.plan = take((t * w.max_chunks + 2 * t) * 4 * sizeof(int32_t));   // per dispatch: two lists of 2 header words + 2 per entry, one chunk size per token
     if (c.n_experts) {
         const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter);
         w.sel = take(t * c.top_k * sizeof(int32_t));
@@ -345,7 +345,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
                                         (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
                                         (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
-                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 1) * 4, d.any_multi, sh, rows, st, mid, pre);
+                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 2) * 4, d.any_multi, sh, rows, st, mid, pre);
             break;
         case DYN_OP_OPROJ:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),

@@ -81,11 +81,12 @@ template <typename T, bool BASE2>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml,
                                                            const int32_t *__restrict__ pos_of_token,
+                                                           const int32_t *__restrict__ ct_of_token,
                                                            T *__restrict__ out, int ld_out, AttnShape sh, int n_pairs) {
     const int pair = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
     if (pair >= n_pairs) return;
     const int t = pair / sh.n_q;
-    const int d = sh.head_dim, ct = sh.chunk_pages * sh.page_size;
+    const int d = sh.head_dim, ct = ct_of_token ? ct_of_token[t] : sh.chunk_pages * sh.page_size;   // per-token chunk size if given
     const int n_chunks = (pos_of_token[t] + ct) / ct;     // ceil((pos + 1) / ct)
     const float *ml = part_ml + (size_t)pair * sh.max_chunks * 2;
     const float *po = part_o + (size_t)pair * sh.max_chunks * d;
@@ -140,16 +141,16 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 }
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
-                                    const int32_t *pos_of_token, void *out, int ld_out, const AttnShape &sh, int rows,
-                                    hipStream_t s) {
+                                    const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
+                                    const AttnShape &sh, int rows, hipStream_t s) {
     const int n_pairs = rows * sh.n_q;
     const dim3 grid((n_pairs + 7) / 8), block(256);
     if (dtype == 0) {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, ld_out, sh, n_pairs);
-        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (float *)out, ld_out, sh, n_pairs);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs);
+        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs);
     } else {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
-        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
+        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
     }
     return hipGetLastError();
 }
@@ -169,7 +170,7 @@ hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *s
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, out, ld_out, sh, rows, s);
+    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, nullptr, out, ld_out, sh, rows, s);
 }
 
 }  // namespace dyn

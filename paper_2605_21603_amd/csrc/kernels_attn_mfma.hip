@@ -1,11 +1,13 @@
-// Paged causal attention for bf16 caches, head_dim 128, 16-position pages: the layer's
-// HBM-bound operator (the paper's memory-bound "decode attention", Section 2).
+// Paged attention for bf16 caches, head_dim 128, 16-position pages, decode form: the layer's
+// HBM-bound operator (the paper's memory-bound "decode attention", Section 2), plus the
+// device-side work lists shared with the prefill form (kernels_attn_prefill.hip).
 //
-// One wave owns one (token, kv head, chunk of pages) and serves every q head of that kv
-// head's group at once, so K and V are fetched once per kv head.  A page of K is 16 rows
-// of 256 bytes, a page of V is 128 rows (one per head-dim index) of 32 bytes; both are
-// loaded straight into MFMA operand layout with fully used 64-byte / 32-byte row segments,
-// no LDS.  The group's scores are a skinny but real contraction
+// A wave serves one token of a single-token sequence against one 256-position chunk of one
+// kv head, all q heads of that kv head's group at once, so K and V are fetched once per kv
+// head.  A page of K is 16 rows of 256 bytes, a page of V is 128 rows (one per head-dim
+// index) of 32 bytes; both are loaded straight into MFMA operand layout with fully used
+// 64-byte / 32-byte row segments, no LDS.  The group's scores are a skinny but real
+// contraction
 //     S[16 positions, G heads] = K_page[16, 128] Q^T[128, G]      (4 x mfma 16x16x32)
 //     O^T[128, G]           += V_page^T[128, 16] P[16, G]         (8 x mfma 16x16x16)
 // whose D layout (lane: head l%16, positions 4*(l/16)+r) is exactly the B layout the second
@@ -21,30 +23,37 @@
 namespace dyn {
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
-                                    const int32_t *pos_of_token, void *out, int ld_out, const AttnShape &sh, int rows,
-                                    hipStream_t s);
+                                    const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
+                                    const AttnShape &sh, int rows, hipStream_t s);
+int attn_prefill_block_tokens(const AttnShape &sh);
+hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
+                                    const int32_t *block_table, const void *k_cache, const void *v_cache, float *part_o,
+                                    float *part_ml, const AttnShape &sh, int32_t *plan, int chunk_pages, long max_items,
+                                    int max_groups, hipStream_t s);
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
 constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of the 256 CUs
-constexpr int kPrefillSets = 4;          // sets of 16 MFMA columns per wave for multi-token sequences
+constexpr int kPrefillChunkPages = 64;   // multi-token sequences: chunks of 1024 positions per work item
 
 // Work lists, built on the device from the positions (contexts differ by 8x inside a batch, so
 // a dense token x max_chunks grid would be mostly empty workgroups).  A wave serves a query
 // group: tokens of one sequence whose positions fall in the same aligned block of `tg`
 // positions, all of them against one pass over the keys.  List 0 holds the tokens that are
 // alone in their sequence this step (decode: groups of one, 4 of 16 MFMA columns live), list 1
-// the tokens of multi-token sequences (prefill chunks) in groups of up to tg1 = NQG * 16 / G.
+// the tokens of multi-token sequences (prefill chunks) in query blocks of up to tg1 tokens, against
+// chunks of ct1 positions.
 // One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
 // (first token row, chunk | tokens << 20) at list[2 + 2 i].
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
                                                          const int32_t *__restrict__ pos_of_token, int rows, int ct,
-                                                         int tg1, int32_t *__restrict__ plan0, int32_t *__restrict__ plan1) {
+                                                         int tg1, int ct1, int32_t *__restrict__ plan0,
+                                                         int32_t *__restrict__ plan1, int32_t *__restrict__ ct_of_token) {
     // One workgroup of 16 waves walks the rows 1024 at a time.  A sequence's tokens are adjacent
     // rows with consecutive positions, so a token leads its group iff it starts its sequence or
-    // its aligned block, and the group's size is a count of independent look-ahead loads (no
-    // dependent chain).  Entry offsets come from a wave scan plus one LDS step per list.
+    // its aligned block, and the group's size comes from a bisection over the look-ahead rows.
+    // Entry offsets come from a wave scan plus one LDS step per list.
     __shared__ int wave_tot[2][16];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
     int base0 = 0, base1 = 0;
@@ -58,11 +67,19 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
             const int tg = which ? tg1 : 1;
             if (!prev_same || p % tg == 0) {                 // group leader
                 const int cand = tg - p % tg;                // positions left in the aligned block
-                n_tok = 1;
-                for (int j = 1; j < 16; ++j)                 // tg <= 16: independent loads, matches form a prefix
-                    n_tok += (j < cand && t + j < rows && seq_of_token[t + j] == s) ? 1 : 0;
-                nc = (p + n_tok - 1 + ct) / ct;              // chunks the group's last token reaches
+                // rows t .. t + n_tok - 1 belong to the sequence: the matches form a prefix of the
+                // candidates, found by bisection (a few dependent cache hits instead of tg loads)
+                int lo = 1, hi = min(cand, rows - t);        // n_tok lies in [lo, hi]
+                while (lo < hi) {
+                    const int mid = (lo + hi + 1) >> 1;
+                    if (seq_of_token[t + mid - 1] == s) lo = mid;
+                    else hi = mid - 1;
+                }
+                n_tok = lo;
+                const int ctw = which ? ct1 : ct;
+                nc = (p + n_tok - 1 + ctw) / ctw;            // chunks the group's last token reaches
             }
+            ct_of_token[t] = which ? ct1 : ct;               // the chunk size this token's partials are indexed by
         }
         int v0 = which ? 0 : nc, v1 = which ? nc : 0;        // inclusive wave scans of both lists
 #pragma unroll
@@ -89,7 +106,7 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
         base1 += tot1;
         __syncthreads();                                      // wave_tot is reused by the next batch
     }
-    if (threadIdx.x == 0) { plan0[0] = base0; plan1[0] = base1; }
+    if (threadIdx.x == 0) { plan0[0] = base0; plan1[0] = base1; plan1[1] = 0; }   // list sizes; list 1's work counter
 }
 
 // Persistent waves: wave w of the launch takes (entry, kv head) pairs w, w + n_waves, ...
@@ -98,9 +115,8 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
 // pair - whose indices were fetched while this pair was being multiplied - so the stream of
 // loads never drains at a pair boundary and the three dependent lookups (work list ->
 // position / sequence -> block table) are off the critical path.
-// NQG = sets of 16 MFMA columns per wave: 1 for decode (eight waves per CU keep HBM busy),
-// 4 for prefill groups of 16 tokens (keys come from L2 and are re-read once per group, so
-// wider groups are what makes it fast; four waves per CU).
+// NQG = sets of 16 MFMA columns per wave; the decode list uses 1 (eight waves per CU keep HBM
+// busy, 4 of the 16 columns live with four q heads per kv head).
 struct AttnItem {
     int t, c, n_tok;                  // first token row of the query group, chunk, tokens in the group
     int n_keys, lp_first, seq_pages;  // keys the group's last token attends, first logical page of the chunk, its pages
@@ -312,10 +328,11 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
         return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
                                         part_o, part_ml, sh, rows, s, mid);
     // two work lists per dispatch: single-token sequences, multi-token sequences
-    const int G = sh.n_q / sh.n_kv, TG = 16 / G;
     int32_t *plan0 = plan, *plan1 = plan + 2 + 2 * (size_t)rows * sh.max_chunks;
+    int32_t *ct_of_token = plan + 4 + 4 * (size_t)rows * sh.max_chunks;
+    const int ct1 = kPrefillChunkPages * PS;
     hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
-                       kPrefillSets * TG < 16 ? kPrefillSets * TG : 16, plan0, plan1);
+                       attn_prefill_block_tokens(sh), ct1, plan0, plan1, ct_of_token);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
@@ -328,16 +345,12 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh,
                        plan0);
     e = hipGetLastError();
-    if (e == hipSuccess && any_multi) {
-        const int grid1 = (int)((max_items + 3) / 4 < groups / 2 ? (max_items + 3) / 4 : groups / 2);
-        hipLaunchKernelGGL(attn_mfma_kernel<kPrefillSets>, dim3(grid1), dim3(256), 0, s, (const bf16_t *)qkv, seq_of_token,
-                           pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml,
-                           sh, plan1);
-        e = hipGetLastError();
-    }
+    if (e == hipSuccess && any_multi)
+        e = launch_attention_prefill(qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, part_o, part_ml, sh,
+                                     plan1, kPrefillChunkPages, max_items, groups, s);
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, out, ld_out, sh, rows, s);
+    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, ct_of_token, out, ld_out, sh, rows, s);
 }
 
 }  // namespace dyn

@@ -96,10 +96,73 @@ __global__ __launch_bounds__(256) void rope_kv_kernel(T *__restrict__ qkv, const
     }
 }
 
+// Vector form for head dims whose half is a multiple of the 16-byte vector: one workgroup per
+// token.  The d/2 angles of the token are reduced and their sine / cosine taken once (not once
+// per head) into LDS; then a thread rotates V pair indices of one head with 16-byte loads and
+// stores (q in place, k into its cache page), and the v heads are scattered into the
+// position-fastest V page element by element.  Same arithmetic per element as the scalar form.
+template <typename T>
+__global__ __launch_bounds__(256) void rope_kv_vec_kernel(T *__restrict__ qkv, const int32_t *__restrict__ seq_of_token,
+                                                          const int32_t *__restrict__ pos_of_token,
+                                                          const int32_t *__restrict__ block_table,
+                                                          T *__restrict__ k_cache, T *__restrict__ v_cache,
+                                                          RopeTable tab, AttnShape sh) {
+    constexpr int V = 16 / sizeof(T);
+    typedef T vec_t __attribute__((ext_vector_type(V)));
+    __shared__ float cs[2][128];                          // cos, sin of the token's angles (head_dim <= 256)
+    const int t = blockIdx.x;
+    const int d = sh.head_dim, half = d >> 1;
+    const int pos = pos_of_token[t];
+    for (int i = threadIdx.x; i < half; i += 256) {
+        const double ang = (double)pos * tab.inv_freq[i];
+        const double turns = rint(ang * 0.15915494309189535);          // 1 / (2 pi)
+        const float red = (float)fma(-turns, 6.283185307179586, ang);
+        float sn, c;
+        sincosf(red, &sn, &c);
+        cs[0][i] = c;
+        cs[1][i] = sn;
+    }
+    const int page = block_table[(size_t)seq_of_token[t] * sh.max_pages_per_seq + pos / sh.page_size];
+    const int slot = pos % sh.page_size;
+    __syncthreads();
+    T *row = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * d);
+    const int per_head = half / V, n_rot = (sh.n_q + sh.n_kv) * per_head;
+    for (int u = threadIdx.x; u < n_rot; u += 256) {
+        const int hh = u / per_head, i0 = (u % per_head) * V;
+        T *z = row + hh * d;
+        const vec_t a = *reinterpret_cast<const vec_t *>(z + i0), b = *reinterpret_cast<const vec_t *>(z + i0 + half);
+        vec_t lo, hi;
+#pragma unroll
+        for (int e = 0; e < V; ++e) {
+            const float c = cs[0][i0 + e], sn = cs[1][i0 + e], fa = to_f32<T>(a[e]), fb = to_f32<T>(b[e]);
+            lo[e] = from_f32<T>(fa * c - fb * sn);
+            hi[e] = from_f32<T>(fb * c + fa * sn);
+        }
+        T *dst = hh < sh.n_q ? z : k_cache + (((size_t)page * sh.n_kv + (hh - sh.n_q)) * sh.page_size + slot) * d;
+        *reinterpret_cast<vec_t *>(dst + i0) = lo;
+        *reinterpret_cast<vec_t *>(dst + i0 + half) = hi;
+    }
+    const T *vrow = row + (sh.n_q + sh.n_kv) * d;
+    for (int u = threadIdx.x; u < sh.n_kv * d; u += 256) {              // v heads -> V page [kvh][d][slot]
+        const int g = u / d, i = u % d;
+        v_cache[(((size_t)page * sh.n_kv + g) * d + i) * sh.page_size + slot] = vrow[u];
+    }
+}
+
 hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                           const int32_t *block_table, void *k_cache, void *v_cache, const RopeTable &tab,
                           const AttnShape &sh, int rows, hipStream_t s) {
     if (rows <= 0) return hipSuccess;
+    const int vec = dtype == 0 ? 4 : 8;
+    if ((sh.head_dim / 2) % vec == 0 && sh.head_dim <= 256) {
+        if (dtype == 0)
+            hipLaunchKernelGGL(rope_kv_vec_kernel<float>, dim3(rows), dim3(256), 0, s, (float *)qkv, seq_of_token,
+                               pos_of_token, block_table, (float *)k_cache, (float *)v_cache, tab, sh);
+        else
+            hipLaunchKernelGGL(rope_kv_vec_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (bf16_t *)qkv, seq_of_token,
+                               pos_of_token, block_table, (bf16_t *)k_cache, (bf16_t *)v_cache, tab, sh);
+        return hipGetLastError();
+    }
     const int items = (sh.n_q + 2 * sh.n_kv) * (sh.head_dim / 2);
     const dim3 grid(rows, (items + 255) / 256);
     if (dtype == 0)
