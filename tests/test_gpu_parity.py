@@ -11,7 +11,8 @@ from gpu_util import GpuRun, check_against_oracle, say
 
 pytestmark = pytest.mark.gpu
 
-SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small", "c4_small", "f32_moe_small", "c3_mid"]
+SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small", "c4_small", "f32_moe_small", "c3_mid", "pf_long", "pf_g8",
+         "pf_mha"]
 
 
 def schedules_for(w):

@@ -138,6 +138,18 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536, n_layers=3)
         ctx = _uniform_ctx(4, 24, 1, 520)
         return Workload("c5_small", sh, tuple((1, c) for c in ctx), 4, (0, 5, 11, 18, 24))
+    if name == "pf_long":       # a prefill chunk after 2300 cached positions: several 1024-position chunks per query block
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
+        seqs = ((200, 2500), (1, 1100), (70, 70), (1, 33), (3, 1027))
+        return Workload("pf_long", sh, seqs, 9, (0, 200, 275))
+    if name == "pf_g8":         # eight q heads per kv head: two tokens per 16-column set, 32-token query blocks
+        sh = LayerShape("bf16", 1024, 8, 1, 128, 1024)
+        seqs = ((45, 45), (1, 300), (33, 1090), (1, 1))
+        return Workload("pf_g8", sh, seqs, 10, (0, 46, 80))
+    if name == "pf_mha":        # one q head per kv head: sixteen tokens per set, 256-token query blocks
+        sh = LayerShape("bf16", 512, 4, 4, 128, 1024)
+        seqs = ((300, 300), (1, 77), (20, 400))
+        return Workload("pf_mha", sh, seqs, 11, (0, 300, 321))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
