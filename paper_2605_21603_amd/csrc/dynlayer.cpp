@@ -124,7 +124,7 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     const int widths[4][2] = {{qkv_width(c), c.hidden}, {c.hidden, c.n_q_heads * c.head_dim},
                               {2 * c.mlp_inter, c.hidden}, {c.hidden, c.mlp_inter}};
     for (int i = 0; i < 4; ++i) {
-        const int S = dyn::gemm_split_k(c.dtype, widths[i][0], widths[i][1]);
+        const int S = dyn::gemm_split_k(c.dtype, widths[i][0], widths[i][1], i >= 2 && c.n_experts ? c.n_experts : 1);
         const size_t prow = (i == 2 ? (size_t)pairs : 1) * t;     // the MoE gate/up projection has a row per (token, expert)
         w.gemm_partial[i] = take(S > 1 ? (size_t)S * prow * widths[i][0] * sizeof(float) : 0);
     }
@@ -133,7 +133,7 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
     w.plan = take((t * w.max_chunks + 2 * t) * 4 * sizeof(int32_t));   // per dispatch: two lists of 2 header words + 2 per entry, one chunk size per token
     if (c.n_experts) {
-        const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter);
+        const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter, c.n_experts);
         w.sel = take(t * c.top_k * sizeof(int32_t));
         w.wgt = take(t * c.top_k * sizeof(float));
         // a dispatch over rows r0.. uses ints [r0 * top_k * 2E, ...): E counts + E lists of up to rows * top_k pairs
@@ -402,7 +402,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                 int32_t *lists = counts + c.n_experts;
                 err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
                 if (err != hipSuccess) break;
-                const int Sd = dyn::gemm_split_k(c.dtype, H, I);
+                const int Sd = dyn::gemm_split_k(c.dtype, H, I, c.n_experts);
                 const size_t plane = T * c.top_k * H;
                 dyn::GemmGroups gr{counts, lists, n_pairs, 1, c.n_experts, (size_t)H * I, 1};
                 err = dyn::launch_gemm_grouped(c.dtype, base + ws.act, ws.ld_act, w.w_down, nullptr,

@@ -35,7 +35,8 @@ struct GemmGroups {
 
 // Split-K factor of a GEMM with output width N and depth K.  A function of (N, K) alone so
 // that a row's summation order never depends on how many rows are in flight.
-int gemm_split_k(int dtype, int N, int K);
+// Expert-grouped projections multiply `groups` matrices in one launch and need fewer planes each.
+int gemm_split_k(int dtype, int N, int K, int groups = 1);
 bool gemm_supported(int dtype, int N, int K);
 
 // ld_out: elements between output rows (>= H).

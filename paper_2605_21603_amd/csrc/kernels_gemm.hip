@@ -10,6 +10,7 @@
 // 64-row micro-batch has the same bits as in the merged batch.
 #include <cstdlib>
 
+#include <algorithm>
 #include "common.h"
 #include "kernels.h"
 
@@ -343,12 +344,12 @@ bool gemm_supported(int dtype, int N, int K) {
     return N > 0 && K > 0 && N % 128 == 0 && K % BK == 0;
 }
 
-int gemm_split_k(int dtype, int N, int K) {
+int gemm_split_k(int dtype, int N, int K, int groups) {
     if (dtype == 0) return 1;
     // enough workgroups to occupy 256 CUs twice over, chunks of at least 8 k-steps
     // planes of at least four stages; enough (128-row tile, plane) pairs to occupy the chip
     int S = 1;
-    while ((N / 128) * S < 192 && K % (S * 2 * BK) == 0 && K / (S * 2) >= 4 * BK * 2) S *= 2;
+    while ((N / 128) * S * std::max(groups, 1) < 192 && K % (S * 2 * BK) == 0 && K / (S * 2) >= 4 * BK * 2) S *= 2;
     return S;
 }
 
@@ -447,7 +448,7 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
         if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
         return e0;
     }
-    const int S = gemm_split_k(dtype, N, K);
+    const int S = gemm_split_k(dtype, N, K, gr.n_groups);
     const int MT = max_rows <= 64 ? 64 : 128;
     const int m_tiles = (max_rows + MT - 1) / MT;
     const int ns = (N / 128) * S * gr.n_groups;
