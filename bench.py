@@ -237,6 +237,9 @@ def main():
     for name, sched in cands.items():
         results[name] = time_schedule(layer, step, sched, stream, args.steps, args.warmup)
         log("%s: %.1f us/step" % (name, results[name] * 1e3))
+    # what the library's own policy would run for this batch, and its cost estimates
+    md = gen.metadata(w)
+    _, policy = B.Scheduler(B.make_config(w.shape), md["q_start"]).auto(md["ctx_len"], use_graph=use_graph)
     best_ovl = min((k for k in results if k != "sequential" or len(results) == 1), key=lambda k: results[k])
     best = min(results, key=lambda k: results[k])
 
@@ -279,6 +282,9 @@ def main():
         "best_overlapped_ms_per_step": results[best_ovl],
         "overlap_speedup": results["sequential"] / results[best_ovl],
         "schedules_ms": results,
+        "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",
+                   "est_sequential_ms_per_layer": policy["est_sequential_us"] * 1e-3,
+                   "est_split_ms_per_layer": policy["est_split_us"] * 1e-3 if policy["est_split_us"] else None},
         "layer_roofline": {"algorithmic_bytes": byts, "algorithmic_flops": flops, "t_roof_ms": t_roof_ms,
                            "frac_overlapped": t_roof_ms / results[best_ovl], "frac_sequential": t_roof_ms / results["sequential"]},
         "op_ms_sequential_eager": {k: sum(v) / len(v) for k, v in op_ms.items()},

@@ -127,7 +127,9 @@ __global__ __launch_bounds__(256) void rope_kv_vec_kernel(T *__restrict__ qkv, c
     __syncthreads();
     T *row = qkv + (size_t)t * ((sh.n_q + 2 * sh.n_kv) * d);
     const int per_head = half / V, n_rot = (sh.n_q + sh.n_kv) * per_head;
-    for (int u = threadIdx.x; u < n_rot; u += 256) {
+    // a token's units are dealt over gridDim.y workgroups (few tokens: more workgroups than tokens)
+    const int first = blockIdx.y * 256 + threadIdx.x, step = gridDim.y * 256;
+    for (int u = first; u < n_rot; u += step) {
         const int hh = u / per_head, i0 = (u % per_head) * V;
         T *z = row + hh * d;
         const vec_t a = *reinterpret_cast<const vec_t *>(z + i0), b = *reinterpret_cast<const vec_t *>(z + i0 + half);
@@ -143,7 +145,7 @@ __global__ __launch_bounds__(256) void rope_kv_vec_kernel(T *__restrict__ qkv, c
         *reinterpret_cast<vec_t *>(dst + i0 + half) = hi;
     }
     const T *vrow = row + (sh.n_q + sh.n_kv) * d;
-    for (int u = threadIdx.x; u < sh.n_kv * d; u += 256) {              // v heads -> V page [kvh][d][slot]
+    for (int u = first; u < sh.n_kv * d; u += step) {                   // v heads -> V page [kvh][d][slot]
         const int g = u / d, i = u % d;
         v_cache[(((size_t)page * sh.n_kv + g) * d + i) * sh.page_size + slot] = vrow[u];
     }
@@ -155,11 +157,12 @@ hipError_t launch_rope_kv(int dtype, void *qkv, const int32_t *seq_of_token, con
     if (rows <= 0) return hipSuccess;
     const int vec = dtype == 0 ? 4 : 8;
     if ((sh.head_dim / 2) % vec == 0 && sh.head_dim <= 256) {
+        const dim3 grid(rows, rows < 512 ? 4 : 1);
         if (dtype == 0)
-            hipLaunchKernelGGL(rope_kv_vec_kernel<float>, dim3(rows), dim3(256), 0, s, (float *)qkv, seq_of_token,
+            hipLaunchKernelGGL(rope_kv_vec_kernel<float>, grid, dim3(256), 0, s, (float *)qkv, seq_of_token,
                                pos_of_token, block_table, (float *)k_cache, (float *)v_cache, tab, sh);
         else
-            hipLaunchKernelGGL(rope_kv_vec_kernel<bf16_t>, dim3(rows), dim3(256), 0, s, (bf16_t *)qkv, seq_of_token,
+            hipLaunchKernelGGL(rope_kv_vec_kernel<bf16_t>, grid, dim3(256), 0, s, (bf16_t *)qkv, seq_of_token,
                                pos_of_token, block_table, (bf16_t *)k_cache, (bf16_t *)v_cache, tab, sh);
         return hipGetLastError();
     }
