@@ -2,15 +2,17 @@
 // compute-bound form of the layer's attention (the paper's compute-bound operator class,
 // Section 2), bf16 caches, head_dim 128, 16-position pages.
 //
-// A 4-wave workgroup serves one query block - up to 4 * 16 tokens of one sequence whose
+// An 8-wave workgroup serves one query block - up to 8 * 8 tokens of one sequence whose
 // positions fall in one aligned block - against one chunk of up to 1024 cached positions of
 // one kv head.  K and V tiles of 32 positions (two pages, 16 KB) go from global memory
-// straight into an LDS ring with direct loads, once per workgroup, and all four waves read
+// straight into an LDS ring with direct loads, once per workgroup, and all eight waves read
 // their MFMA operands from there: a key is fetched once per 64 query tokens and q-head
-// group instead of once per 16, and the waves hold no K/V staging registers, so two
-// workgroups fit a CU and one wave's softmax overlaps another's matrix products.
-//   S[32 pos, 64 cols]  = K_tile[32, 128] Q^T[128, 64]       (32 x mfma 16x16x32 per wave)
-//   O^T[128, 64 cols]  += V_tile^T[128, 32] P[32, 64]        (32 x mfma 16x16x32 per wave)
+// group, and the waves hold no K/V staging registers.  A wave owns two sets of 16 columns
+// (64 accumulator registers): everything fits the 256 vector registers of a wave at two
+// waves per SIMD, so one wave's softmax overlaps another's matrix products and no operand
+// ever sits in an accumulation register it has to be copied out of.
+//   S[32 pos, 32 cols]  = K_tile[32, 128] Q^T[128, 32]       (16 x mfma 16x16x32 per wave)
+//   O^T[128, 32 cols]  += V_tile^T[128, 32] P[32, 32]        (16 x mfma 16x16x32 per wave)
 // A column is (token, q head of the kv head's group); the D layout of the first product
 // (lane: column l % 16, positions 4 (l / 16) + r of a page) is the B layout of the second
 // with the k index running over (page 0: 4 positions, page 1: 4 positions), and V's
@@ -29,20 +31,18 @@ namespace {
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16;
-constexpr int kSets = 4;                      // sets of 16 MFMA columns per wave
+constexpr int kSets = 2;                      // sets of 16 MFMA columns per wave
+constexpr int kWaves = 8;                     // waves per workgroup
 constexpr int kRing = 3, kTile = 16384;       // LDS ring of K/V tiles: [K page a][K page b][V page a][V page b], 4 KB each
 
 __device__ __forceinline__ void wait_vm(int n) {   // s_waitcnt vmcnt(n) only
-    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0f74);
+    if (n == 2) __builtin_amdgcn_s_waitcnt(0x0f72);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
 }
 
 }  // namespace
 
-#ifndef DYN_PREFILL_OCC
-#define DYN_PREFILL_OCC 1
-#endif
-__global__ __launch_bounds__(256, DYN_PREFILL_OCC) void attn_prefill_kernel(const bf16_t *__restrict__ qkv,
+__global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16_t *__restrict__ qkv,
                                                               const int32_t *__restrict__ seq_of_token,
                                                               const int32_t *__restrict__ pos_of_token,
                                                               const int32_t *__restrict__ block_table,
@@ -110,15 +110,16 @@ __global__ __launch_bounds__(256, DYN_PREFILL_OCC) void attn_prefill_kernel(cons
         const int wave_min_keys = wave_tok0 < n_tok ? pos_of_token[t0 + wave_tok0] + 1 : 0;
         __syncthreads();                                                  // pid is visible
 
-        // Wave w copies one 4 KB page of every tile: K page a, K page b, V page a, V page b.
-        const int half = wave & 1, is_v = wave >> 1;
+        // Wave w copies 2 KB of every tile: half a page of K page a, K page b, V page a, V page b.
+        const int half = (wave >> 1) & 1, is_v = wave >> 2, part = wave & 1;
         auto issue = [&](int tile) {
             const int tcl = min(tile, n_tile - 1);                        // past the end: a harmless reload
             const int pg = pid[min(2 * tcl + half, n_pg - 1)];
             unsigned char *dst = lds + (tile % kRing) * kTile + is_v * 8192 + half * 4096;
             const size_t page_elems = ((size_t)pg * sh.n_kv + g) * (PS * HD);
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int jj = 0; jj < 2; ++jj) {
+                const int j = part * 2 + jj;                              // which KB of the page
                 const bf16_t *src;
                 if (is_v) {
                     const int r = j * 32 + (lane >> 1), h = lane & 1;     // V row (head-dim index), 16-byte half in LDS
@@ -150,7 +151,7 @@ __global__ __launch_bounds__(256, DYN_PREFILL_OCC) void attn_prefill_kernel(cons
         issue(0);
         issue(1);
         for (int ti = 0; ti < n_tile; ++ti) {
-            wait_vm(4);                                                   // tile ti has landed (tile ti + 1 may be in flight)
+            wait_vm(2);                                                   // tile ti has landed (tile ti + 1 may be in flight)
             __builtin_amdgcn_s_barrier();                                 // everyone's part of it, and everyone is done with tile ti - 1
             issue(ti + 2);
             const int key0 = (lp0 + 2 * ti) * PS;
@@ -262,7 +263,7 @@ __global__ __launch_bounds__(256, DYN_PREFILL_OCC) void attn_prefill_kernel(cons
     }
 }
 
-int attn_prefill_block_tokens(const AttnShape &sh) { return 4 * kSets * (16 / (sh.n_q / sh.n_kv)); }
+int attn_prefill_block_tokens(const AttnShape &sh) { return kWaves * kSets * (16 / (sh.n_q / sh.n_kv)); }
 
 hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                                     const int32_t *block_table, const void *k_cache, const void *v_cache, float *part_o,
@@ -277,7 +278,7 @@ hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token
         attr_set = true;
     }
     const int grid = (int)(max_items < max_groups ? max_items : max_groups);
-    hipLaunchKernelGGL(attn_prefill_kernel, dim3(grid), dim3(256), lds_bytes, s, (const bf16_t *)qkv, seq_of_token,
+    hipLaunchKernelGGL(attn_prefill_kernel, dim3(grid), dim3(kWaves * 64), lds_bytes, s, (const bf16_t *)qkv, seq_of_token,
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh, plan,
                        plan + 1, chunk_pages);
     return hipGetLastError();
