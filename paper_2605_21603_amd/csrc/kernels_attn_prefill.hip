@@ -33,10 +33,11 @@ typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 constexpr int HD = 128, PS = 16;
 constexpr int kSets = 2;                      // sets of 16 MFMA columns per wave
 constexpr int kWaves = 8;                     // waves per workgroup
-constexpr int kRing = 3, kTile = 16384;       // LDS ring of K/V tiles: [K page a][K page b][V page a][V page b], 4 KB each
+constexpr int kTP = 4;                         // pages (16 positions each) per K/V tile
+constexpr int kRing = 3, kTile = 2 * kTP * 4096;   // LDS ring of K/V tiles: kTP K pages, then kTP V pages, 4 KB each
 
 __device__ __forceinline__ void wait_vm(int n) {   // s_waitcnt vmcnt(n) only
-    if (n == 2) __builtin_amdgcn_s_waitcnt(0x0f72);
+    if (n == 4) __builtin_amdgcn_s_waitcnt(0x0f74);
     else __builtin_amdgcn_s_waitcnt(0x0f70);
 }
 
@@ -82,7 +83,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
         const int seq_pages = (n_keys + PS - 1) / PS;
         const int lp0 = c * chunk_pages;
         const int n_pg = min(chunk_pages, seq_pages - lp0);
-        const int n_tile = (n_pg + 1) / 2;
+        const int n_tile = (n_pg + kTP - 1) / kTP;
         const int32_t *bt = block_table + (size_t)seq_of_token[t0] * sh.max_pages_per_seq;
 
         if (tid < chunk_pages) pid[tid] = bt[lp0 + min(tid, n_pg - 1)];
@@ -110,16 +111,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
         const int wave_min_keys = wave_tok0 < n_tok ? pos_of_token[t0 + wave_tok0] + 1 : 0;
         __syncthreads();                                                  // pid is visible
 
-        // Wave w copies 2 KB of every tile: half a page of K page a, K page b, V page a, V page b.
-        const int half = (wave >> 1) & 1, is_v = wave >> 2, part = wave & 1;
+        // Wave w copies one 4 KB page of every tile: K pages 0..3 (waves 0..3), V pages 0..3 (waves 4..7).
+        const int wpage = wave & (kTP - 1), is_v = wave / kTP;
         auto issue = [&](int tile) {
             const int tcl = min(tile, n_tile - 1);                        // past the end: a harmless reload
-            const int pg = pid[min(2 * tcl + half, n_pg - 1)];
-            unsigned char *dst = lds + (tile % kRing) * kTile + is_v * 8192 + half * 4096;
+            const int pg = pid[min(kTP * tcl + wpage, n_pg - 1)];
+            unsigned char *dst = lds + (tile % kRing) * kTile + is_v * (kTP * 4096) + wpage * 4096;
             const size_t page_elems = ((size_t)pg * sh.n_kv + g) * (PS * HD);
 #pragma unroll
-            for (int jj = 0; jj < 2; ++jj) {
-                const int j = part * 2 + jj;                              // which KB of the page
+            for (int j = 0; j < 4; ++j) {
                 const bf16_t *src;
                 if (is_v) {
                     const int r = j * 32 + (lane >> 1), h = lane & 1;     // V row (head-dim index), 16-byte half in LDS
@@ -151,16 +151,16 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
         issue(0);
         issue(1);
         for (int ti = 0; ti < n_tile; ++ti) {
-            wait_vm(2);                                                   // tile ti has landed (tile ti + 1 may be in flight)
+            wait_vm(4);                                                   // tile ti has landed (tile ti + 1 may be in flight)
             __builtin_amdgcn_s_barrier();                                 // everyone's part of it, and everyone is done with tile ti - 1
             issue(ti + 2);
-            const int key0 = (lp0 + 2 * ti) * PS;
+            const int key0 = (lp0 + kTP * ti) * PS;
             if (key0 >= wave_keys) continue;                              // wave-uniform: nothing of this tile is visible to the wave
-            const unsigned char *kb = lds + (ti % kRing) * kTile, *vb = kb + 8192;
+            const unsigned char *kb = lds + (ti % kRing) * kTile, *vb = kb + kTP * 4096;
 
-            f32x4 sv[kSets][2];                                           // raw scores q . k
+            f32x4 sv[kSets][kTP];                                         // raw scores q . k
 #pragma unroll
-            for (int pi = 0; pi < 2; ++pi) {
+            for (int pi = 0; pi < kTP; ++pi) {
                 bf16x8 kf[4];
 #pragma unroll
                 for (int ks = 0; ks < 4; ++ks)
@@ -174,24 +174,26 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
                 }
             }
             __builtin_amdgcn_sched_barrier(0);
-            // Causal mask: only the last one or two tiles of a block have positions that some live
-            // column of the wave must not see (wave-uniform test).
-            if (key0 + 2 * PS > wave_min_keys) {
+            // Causal mask: only the last tiles of a block have positions that some live column of
+            // the wave must not see (wave-uniform test).
+            if (key0 + kTP * PS > wave_min_keys) {
 #pragma unroll
                 for (int q = 0; q < kSets; ++q)
 #pragma unroll
-                    for (int pi = 0; pi < 2; ++pi)
+                    for (int pi = 0; pi < kTP; ++pi)
 #pragma unroll
                         for (int r = 0; r < 4; ++r)
                             if (key0 + pi * PS + 4 * lq + r >= nk[q]) sv[q][pi][r] = -INFINITY;
             }
-            bf16x8 pb[kSets];
+            bf16x8 pb[kSets][kTP / 2];                                    // probabilities: one k = 32 operand per pair of pages
             bool rescale = false;
             float alpha[kSets];
 #pragma unroll
             for (int q = 0; q < kSets; ++q) {
-                float mx = fmaxf(fmaxf(fmaxf(sv[q][0][0], sv[q][0][1]), fmaxf(sv[q][0][2], sv[q][0][3])),
-                                 fmaxf(fmaxf(sv[q][1][0], sv[q][1][1]), fmaxf(sv[q][1][2], sv[q][1][3])));
+                float mx = -INFINITY;
+#pragma unroll
+                for (int pi = 0; pi < kTP; ++pi)
+                    mx = fmaxf(mx, fmaxf(fmaxf(sv[q][pi][0], sv[q][pi][1]), fmaxf(sv[q][pi][2], sv[q][pi][3])));
                 mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
                 mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
                 mx *= sscale;
@@ -205,15 +207,18 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
                 alpha[q] = move ? __builtin_amdgcn_exp2f(m_run[q] - m_ref) : 1.0f;
                 rescale |= move;
                 m_run[q] = m_new;
-                f32x4 p0, p1;
 #pragma unroll
-                for (int r = 0; r < 4; ++r) {
-                    p0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[q][0][r], sscale, -m_ref));
-                    p1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[q][1][r], sscale, -m_ref));
+                for (int pp = 0; pp < kTP / 2; ++pp) {
+                    f32x4 p0, p1;
+#pragma unroll
+                    for (int r = 0; r < 4; ++r) {
+                        p0[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[q][2 * pp][r], sscale, -m_ref));
+                        p1[r] = __builtin_amdgcn_exp2f(__builtin_fmaf(sv[q][2 * pp + 1][r], sscale, -m_ref));
+                    }
+                    const u32x2 w0 = __builtin_bit_cast(u32x2, __builtin_convertvector(p0, bf16x4));
+                    const u32x2 w1 = __builtin_bit_cast(u32x2, __builtin_convertvector(p1, bf16x4));
+                    pb[q][pp] = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
                 }
-                const u32x2 w0 = __builtin_bit_cast(u32x2, __builtin_convertvector(p0, bf16x4));
-                const u32x2 w1 = __builtin_bit_cast(u32x2, __builtin_convertvector(p1, bf16x4));
-                pb[q] = __builtin_bit_cast(bf16x8, u32x4{w0[0], w0[1], w1[0], w1[1]});
             }
             if (__any(rescale)) {
 #pragma unroll
@@ -226,22 +231,31 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
             // the denominator sums the probabilities exactly as the value product sees them (rounded
             // to bf16): one more matrix product, against a block of ones
 #pragma unroll
-            for (int q = 0; q < kSets; ++q) acc_l[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[q], acc_l[q], 0, 0, 0);
+            for (int pp = 0; pp < kTP / 2; ++pp)
+#pragma unroll
+                for (int q = 0; q < kSets; ++q) acc_l[q] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(ones, pb[q][pp], acc_l[q], 0, 0, 0);
             // positions past the block's last key (in the chunk's last tile) hold stale cache bits,
             // which must not meet their zero probabilities (0 * NaN): masked out of V
-            const int nv0 = n_keys - key0 - 4 * lq, nv1 = nv0 - PS;
-            const uint32_t m00 = (nv0 > 0 ? 0x0000ffffu : 0u) | (nv0 > 1 ? 0xffff0000u : 0u);
-            const uint32_t m01 = (nv0 > 2 ? 0x0000ffffu : 0u) | (nv0 > 3 ? 0xffff0000u : 0u);
-            const uint32_t m10 = (nv1 > 0 ? 0x0000ffffu : 0u) | (nv1 > 1 ? 0xffff0000u : 0u);
-            const uint32_t m11 = (nv1 > 2 ? 0x0000ffffu : 0u) | (nv1 > 3 ? 0xffff0000u : 0u);
+            uint32_t vm[kTP][2];
+#pragma unroll
+            for (int pi = 0; pi < kTP; ++pi) {
+                const int nv = n_keys - key0 - pi * PS - 4 * lq;
+                vm[pi][0] = (nv > 0 ? 0x0000ffffu : 0u) | (nv > 1 ? 0xffff0000u : 0u);
+                vm[pi][1] = (nv > 2 ? 0x0000ffffu : 0u) | (nv > 3 ? 0xffff0000u : 0u);
+            }
             __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
             for (int dt = 0; dt < 8; ++dt) {
-                const u32x2 x0 = *reinterpret_cast<const u32x2 *>(vb + dt * 512 + v_off);
-                const u32x2 x1 = *reinterpret_cast<const u32x2 *>(vb + 4096 + dt * 512 + v_off);
-                const bf16x8 vf = __builtin_bit_cast(bf16x8, u32x4{x0[0] & m00, x0[1] & m01, x1[0] & m10, x1[1] & m11});
 #pragma unroll
-                for (int q = 0; q < kSets; ++q) acc[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[q], acc[q][dt], 0, 0, 0);
+                for (int pp = 0; pp < kTP / 2; ++pp) {
+                    const u32x2 x0 = *reinterpret_cast<const u32x2 *>(vb + (2 * pp) * 4096 + dt * 512 + v_off);
+                    const u32x2 x1 = *reinterpret_cast<const u32x2 *>(vb + (2 * pp + 1) * 4096 + dt * 512 + v_off);
+                    const bf16x8 vf = __builtin_bit_cast(bf16x8, u32x4{x0[0] & vm[2 * pp][0], x0[1] & vm[2 * pp][1],
+                                                                       x1[0] & vm[2 * pp + 1][0], x1[1] & vm[2 * pp + 1][1]});
+#pragma unroll
+                    for (int q = 0; q < kSets; ++q)
+                        acc[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[q][pp], acc[q][dt], 0, 0, 0);
+                }
                 if (dt & 1) __builtin_amdgcn_sched_barrier(0);
             }
         }
