@@ -103,15 +103,16 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
 #undef DYN_W
 }
 
-template <int BN, int MT, bool INREG, int NS, bool GATED>
-__global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
+template <int BN, int MT, bool INREG, int NS, bool GATED, int NW>
+__global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const bf16_t *__restrict__ X, int ldx, const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
     bf16_t *__restrict__ Y, int ldy, float *__restrict__ P, size_t plane_stride, int M, int N, int K, int S,
     GemmGroups gr) {
     constexpr int ROWS = BN + MT;                   // rows of a stage buffer: W rows, then X rows
-    constexpr int LPS = ROWS / 32;                  // direct loads per thread and stage (8 rows per wave instruction)
+    constexpr int WNW = NW / 2, RW = BN / WNW;      // waves along n (two along m); W rows per wave column
+    constexpr int LPS = ROWS / (NW * 8);            // direct loads per thread and stage (8 rows per wave instruction)
     constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
-    constexpr int NA = BN / 32, NB = MT / 32;       // 16-row operand tiles per wave
+    constexpr int NA = RW / 16, NB = MT / 32;       // 16-row operand tiles per wave
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int m_tiles = (M + MT - 1) / MT;
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
@@ -148,20 +149,20 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
     const int plane_stages = Kp / BK;
     const int n0 = n_tile * BN, m0 = m_tile * MT;
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
-    const int lr = lane & 15, lq = lane >> 4, wn = wave & 1, wm = wave >> 1;
+    const int lr = lane & 15, lq = lane >> 4, wn = wave % WNW, wm = wave / WNW;
 
-    // Direct load j of this wave covers stage rows (j * 4 + wave) * 8 .. + 8; lane l fetches
+    // Direct load j of this wave covers stage rows (j * NW + wave) * 8 .. + 8; lane l fetches
     // row + l / 8, global 16-byte column (l % 8) ^ swizzle(row).
     const bf16_t *src[LPS];
 #pragma unroll
     for (int j = 0; j < LPS; ++j) {
-        const int row = (j * 4 + wave) * 8 + (lane >> 3);
+        const int row = (j * NW + wave) * 8 + (lane >> 3);
         const int col = (lane & 7) ^ ((row >> 1) & 7);
         if (row < BN) {
             int n = n0 + row;
             if (GATED) {   // stage row = wave half wn, then gate tiles, then up tiles
-                const int wn_r = row / (BN / 2), in_w = row % (BN / 2), up = in_w / (BN / 4);
-                n = n_tile * (BN / 2) + wn_r * (BN / 4) + in_w % (BN / 4) + up * (N / 2);
+                const int wn_r = row / RW, in_w = row % RW, up = in_w / (RW / 2);
+                n = n_tile * (BN / 2) + wn_r * (RW / 2) + in_w % (RW / 2) + up * (N / 2);
             }
             src[j] = W + (size_t)n * K + kbase + col * 8;
         } else {
@@ -175,7 +176,8 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
     // spreads the requests over the memory channels; tiles of one group keep reading the same X
     // columns together, so X stays shared in L2.  The order depends on (N, K, n tile) only, never
     // on the number of rows, so every schedule adds the same terms in the same order.
-    const int rot = (int)(((unsigned)(n_tile / kRotGroup) * kRotStep) % (unsigned)plane_stages);
+    const int rot_group = (GATED ? n_tile * (BN / 2) / 64 : n0 / 128) / kRotGroup;   // by output column, the same for every tile shape
+    const int rot = (int)(((unsigned)rot_group * kRotStep) % (unsigned)plane_stages);
     int iss_w = 0, iss_base = 0;                       // next stage to issue: index inside its plane, plane's first stage
     auto issue = [&](int st) {                         // all direct loads of stage st into ring buffer st % NS; st ascends by one per call
         unsigned char *buf = lds + (st % NS) * STAGE;
@@ -186,7 +188,7 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
 #pragma unroll
         for (int j = 0; j < LPS; ++j)
             __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)kst * BK),
-                                             (__attribute__((address_space(3))) void *)(buf + (j * 4 + wave) * 8 * ROWB),
+                                             (__attribute__((address_space(3))) void *)(buf + (j * NW + wave) * 8 * ROWB),
                                              16, 0, 0);
     };
 
@@ -203,7 +205,7 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
     int a_off[NA], b_off[NB];
 #pragma unroll
     for (int a = 0; a < NA; ++a) {
-        const int row = wn * (BN / 2) + a * 16 + lr;
+        const int row = wn * RW + a * 16 + lr;
         a_off[a] = row * ROWB + ((lq ^ ((row >> 1) & 7)) << 4);
     }
 #pragma unroll
@@ -259,7 +261,7 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
                 const int m = m0 + wm * (MT / 2) + b * 16 + lr;
-                const int n = n_tile * (BN / 2) + wn * (BN / 4) + a * 16 + 4 * lq;
+                const int n = n_tile * (BN / 2) + wn * (RW / 2) + a * 16 + 4 * lq;
                 if (m >= M) continue;
                 const size_t orow = list ? list[m] : m;
                 const f32x4 g = acc[a][b], up = acc[a + NA / 2][b];
@@ -278,7 +280,7 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
             const int m = m0 + wm * (MT / 2) + b * 16 + lr;
-            const int n = n0 + wn * (BN / 2) + a * 16 + 4 * lq;
+            const int n = n0 + wn * RW + a * 16 + 4 * lq;
             if (m >= M) continue;
             const size_t orow = list ? list[m] : m;
             f32x4 o = INREG ? total[a][b] : acc[a][b];
@@ -298,7 +300,7 @@ __global__ __launch_bounds__(256, ((BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) 
         }
 }
 
-template <int BN, int MT, bool INREG, int NS, bool GATED = false>
+template <int BN, int MT, bool INREG, int NS, bool GATED = false, int NW = 4>
 hipError_t launch_gemm_bf16(int grid, hipStream_t s, const void *X, int ldx, const void *W, const void *R, void *Y,
                             float *partial, size_t plane_stride, int rows, int N, int K, int S, const GemmGroups &gr,
                             int ldy = 0) {
@@ -306,12 +308,12 @@ hipError_t launch_gemm_bf16(int grid, hipStream_t s, const void *X, int ldx, con
     static_assert(NS >= 2 && NS <= 6 && NS * STAGE <= 160 * 1024, "ring does not fit in LDS");
     static bool attr_set = false;                      // above 64 KB of dynamic LDS needs an opt-in, once
     if (!attr_set) {
-        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS, GATED>,
+        hipError_t e = hipFuncSetAttribute((const void *)gemm_bf16_kernel<BN, MT, INREG, NS, GATED, NW>,
                                            hipFuncAttributeMaxDynamicSharedMemorySize, NS * STAGE);
         if (e != hipSuccess) return e;
         attr_set = true;
     }
-    hipLaunchKernelGGL((gemm_bf16_kernel<BN, MT, INREG, NS, GATED>), dim3(grid), dim3(256), NS * STAGE, s,
+    hipLaunchKernelGGL((gemm_bf16_kernel<BN, MT, INREG, NS, GATED, NW>), dim3(grid), dim3(NW * 64), NS * STAGE, s,
                        (const bf16_t *)X, ldx, (const bf16_t *)W, (const bf16_t *)R, (bf16_t *)Y, ldy ? ldy : N, partial,
                        plane_stride, rows, N, K, S, gr);
     return hipGetLastError();
@@ -353,6 +355,15 @@ int gemm_split_k(int dtype, int N, int K, int groups) {
     return S;
 }
 
+namespace {
+// 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
+// of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at
+// least two mostly full m tiles and enough tiles to fill the chip (2112 x 28672 x 4096: 519 ->
+// 432 us; 512 rows: 164 -> 121 us; 320 rows and fewer lose).  Not for planes folded in
+// registers: the second accumulator set does not fit.
+bool gemm_wide_tiles(int rows, int N) { return N % 256 == 0 && rows >= 448 && (N / 256) * ((rows + 255) / 256) >= 192; }
+}  // namespace
+
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
                        size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid) {
     if (rows <= 0) return hipSuccess;
@@ -380,6 +391,12 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         // tile that saves a round wins (2112 rows x 4096 columns: 544 tiles of 128 rows need
         // two rounds, 448 tiles of 160 rows one).  The summation order of an output element
         // does not depend on the tile height.
+        if (gemm_wide_tiles(rows, N) && !inreg) {
+            const int grid = ((N / 256 + 7) / 8) * 8 * ((rows + 255) / 256);
+            e = launch_gemm_bf16<256, 256, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
+            if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
+            return e;
+        }
         const int nt = N / DYN_BIG_BN;
         const long cost128 = (long)((nt * ((rows + 127) / 128) + 511) / 512) * 128;
         const long cost160 = (long)((nt * ((rows + 159) / 160) + 511) / 512) * 160;
@@ -416,7 +433,10 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
     const int groups = gr.n_groups ? gr.n_groups : 1;
     hipError_t e;
     const int big_tiles = (N2 / DYN_BIG_BN) * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-    if (!gr.n_groups && big_tiles >= 256) {
+    if (!gr.n_groups && gemm_wide_tiles(max_rows, N2)) {
+        const int grid = ((N2 / 256 + 7) / 8) * 8 * ((max_rows + 255) / 256);
+        e = launch_gemm_bf16<256, 256, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+    } else if (!gr.n_groups && big_tiles >= 256) {
         const int grid = (((N2 / DYN_BIG_BN) + 7) / 8) * 8 * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
         e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0,
                                                                             max_rows, N2, K, 1, gr, ldy);
