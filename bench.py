@@ -186,6 +186,8 @@ def main():
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedules", default="all",
                     help="comma-separated overlapped schedules to time beside sequential ('all', or 'none')")
+    ap.add_argument("--tune", action="store_true",
+                    help="also run the library's measured search over micro-batch sizes, forms and CU shares and time its choice")
     ap.add_argument("--no-event-profile", action="store_true", help="skip the per-operator HIP-event pass")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
@@ -237,8 +239,26 @@ def main():
     for name, sched in cands.items():
         results[name] = time_schedule(layer, step, sched, stream, args.steps, args.warmup)
         log("%s: %.1f us/step" % (name, results[name] * 1e3))
-    # what the library's own policy would run for this batch, and its cost estimates
+    # the library's measured tuner: unequal micro-batch sizes, forms, staggers, CU shares
     md = gen.metadata(w)
+    tuned = None
+    if args.tune:
+        log("tuning ...")
+        many = w.shape.n_layers > 1
+        sch_t = B.Scheduler(B.make_config(w.shape), md["q_start"])
+        t_sched, t_res, t_table = sch_t.tune(layer, step.batch, stream, ctx_len=md["ctx_len"], max_k=2, partitions=1,
+                                             warmup=1 if many else 2, iters=3 if many else 7, use_graph=use_graph)
+        torch.cuda.synchronize()
+        t_overlapped = [c for c in t_table if c["us"] > 0 and c["form"] != "sequential"]
+        t_fastest = min(t_overlapped, key=lambda c: c["us"]) if t_overlapped else None
+        tuned = {"chosen": t_res["best"], "fastest_overlapped": t_fastest, "us_sequential": t_res["us_sequential"],
+                 "candidates_timed": t_res["n_tried"], "candidates_refused": t_res["n_skipped"]}
+        log("tuner: chose %s; fastest overlapped candidate %s; sequential %.1f us" % (t_res["best"], t_fastest,
+                                                                                      t_res["us_sequential"]))
+        if t_res["best"]["form"] != "sequential":
+            results["tuned"] = time_schedule(layer, step, t_sched, stream, args.steps, args.warmup)
+            log("tuned: %.1f us/step" % (results["tuned"] * 1e3))
+    # what the library's own policy would run for this batch, and its cost estimates
     _, policy = B.Scheduler(B.make_config(w.shape), md["q_start"]).auto(md["ctx_len"], use_graph=use_graph)
     best_ovl = min((k for k in results if k != "sequential" or len(results) == 1), key=lambda k: results[k])
     best = min(results, key=lambda k: results[k])
@@ -282,6 +302,7 @@ def main():
         "best_overlapped_ms_per_step": results[best_ovl],
         "overlap_speedup": results["sequential"] / results[best_ovl],
         "schedules_ms": results,
+        "tuned": tuned,
         "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",
                    "est_sequential_ms_per_layer": policy["est_sequential_us"] * 1e-3,
                    "est_split_ms_per_layer": policy["est_split_us"] * 1e-3 if policy["est_split_us"] else None},

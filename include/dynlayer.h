@@ -236,6 +236,77 @@ typedef struct {
 dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int use_graph, dyn_schedule *out,
                            dyn_policy_choice *choice);
 
+/* ---- Measured tuning of micro-batch sizes and CU partitions (Section 2.1; Section 5.3.4) -
+ *
+ * The paper names two things a strategy author has to tune by hand: the sizes of the
+ * micro-batches (unequal sizes pay when operator durations differ) and the share of the
+ * compute units each overlapped stream gets (hard to choose for partitioned contexts), and
+ * reports a gain from choosing a kernel's share per batch size at run time.  The calls
+ * below do that search by measurement: enumerate candidate schedules for a batch's
+ * structure, record each through the scheduler calls above, time it on the device, and
+ * keep the fastest. */
+enum {
+    DYN_FORM_SEQUENTIAL = 0,   /* one micro-batch, chain order, caller's stream */
+    DYN_FORM_SPLIT = 1,        /* every operator per micro-batch, micro-batch b on stream b */
+    DYN_FORM_MLP_MERGED = 2,   /* per micro-batch up to the second norm; router and MLP once for all (merge form) */
+    DYN_FORM_ATTN_SPLIT = 3    /* the four projections once for all; norms, rotary, attention, gate per micro-batch */
+};
+
+typedef struct {
+    int k;                            /* micro-batches; 1 with DYN_FORM_SEQUENTIAL */
+    int32_t rows[DYN_MAX_NANO + 1];   /* cut points rows[0] = 0 .. rows[k] = n_tokens */
+    int form;                         /* DYN_FORM_* */
+    int stagger;                      /* micro-batch b is issued `stagger` operators behind micro-batch b-1 */
+    int cus_first;                    /* 0: plain streams.  Otherwise even micro-batches run on a partition of
+                                         cus_first CUs and odd ones on the remaining CUs (the same share of
+                                         every XCD); merged dispatches use the whole device */
+    float us;                         /* filled by dyn_tune: time of one forward in a replay loop, microseconds;
+                                         negative if the candidate could not be run */
+} dyn_tune_candidate;
+
+typedef struct {
+    int max_k;          /* largest number of micro-batches tried, 2..4 (0 = 2) */
+    int partitions;     /* CU-partition sizes tried: 0 none, 1 half | half, 2 adds 3/4 | 1/4, 3 adds 1/4 | 3/4 */
+    int n_cus;          /* CUs of the device (0 = 256); dyn_tune overwrites it with the device's count */
+    int warmup, iters;  /* per candidate: untimed forwards, then three timed runs of iters forwards issued
+                           back to back, median of the three means (0 = 2 and 7) */
+    int use_graph;      /* run candidates as HIP graph replays */
+    float min_gain;     /* an overlapped candidate is chosen only if it beats the sequential order by this
+                           fraction (negative = 0.02) */
+} dyn_tune_options;
+
+typedef struct {
+    dyn_tune_candidate best;    /* the schedule recorded into the scheduler when dyn_tune returns */
+    float us_sequential;
+    int n_tried, n_skipped;     /* candidates timed / candidates the device refused (e.g. no masked stream) */
+} dyn_tune_result;
+
+/* Host only.  Writes the candidates for the scheduler's batch structure to table (at most
+ * capacity) and returns how many there are (-1 on a bad argument): the sequential order;
+ * for two micro-batches cuts near 1/4, 3/8, 1/2, 5/8 and 3/4 of the tokens snapped to
+ * sequence boundaries, the cut that halves the summed context (ctx_len_host, HOST
+ * [n_seqs], may be NULL) and the boundary between multi-token and single-token sequences
+ * if there is exactly one, each in the three overlapped forms with staggers 0..2; equal
+ * cuts for three and four micro-batches up to opt->max_k; CU-partitioned variants per
+ * opt->partitions. */
+int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, const dyn_tune_options *opt,
+                        dyn_tune_candidate *table, int capacity);
+
+/* Host only.  Records candidate c into s (discarding earlier recordings, replacing its
+ * partitions) and ends the recording into *out, as dyn_scheduler_finish does. */
+dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_cus, int use_graph, dyn_schedule *out);
+
+/* Times every candidate on the batch (replay loops on hip_stream, each followed by a wait
+ * for its end event: this call blocks, allocates no device memory, and leaves y and the caches
+ * as one forward leaves them) and records the winner into s / *out.  s must have been
+ * created for this batch's structure.  table (may be NULL) receives the candidates with
+ * their times, at most capacity of them.  DYN_ERR_HIP if even the sequential order fails;
+ * DYN_ERR_UNSUPPORTED for opt->max_k > 3 (four micro-batches can be enumerated and
+ * recorded with the two calls above, but are not part of the device search). */
+dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const int32_t *ctx_len_host, const dyn_tune_options *opt,
+                    void *hip_stream, dyn_scheduler *s, dyn_schedule *out, dyn_tune_result *result,
+                    dyn_tune_candidate *table, int capacity);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *dyn_last_error(void);
 

@@ -20,6 +20,8 @@ DYN_F32, DYN_BF16 = 0, 1
 DYN_N_OPS = 10
 DYN_SCHED_SEQUENTIAL, DYN_SCHED_EXPLICIT = 0, 1
 DYN_MAX_NANO, DYN_MAX_STREAMS, DYN_MAX_PARTITIONS = 8, 8, 4
+DYN_FORM_SEQUENTIAL, DYN_FORM_SPLIT, DYN_FORM_MLP_MERGED, DYN_FORM_ATTN_SPLIT = 0, 1, 2, 3
+FORM_NAMES = ["sequential", "split", "mlp_merged", "attn_split"]
 OP_NAMES = ["norm1", "qkv", "rope_kv", "attn", "oproj", "norm2", "route", "gate_up", "silu", "down"]
 DENSE_CHAIN = [DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ, DYN_OP_NORM2, DYN_OP_GATE_UP,
                DYN_OP_SILU, DYN_OP_DOWN]
@@ -59,6 +61,24 @@ class dyn_policy_choice(C.Structure):
     _fields_ = [("split", C.c_int), ("cut_row", C.c_int), ("est_sequential_us", C.c_float), ("est_split_us", C.c_float)]
 
 
+class dyn_tune_candidate(C.Structure):
+    _fields_ = [("k", C.c_int), ("rows", C.c_int32 * (DYN_MAX_NANO + 1)), ("form", C.c_int), ("stagger", C.c_int),
+                ("cus_first", C.c_int), ("us", C.c_float)]
+
+    def as_dict(self) -> dict:
+        return {"k": self.k, "rows": [self.rows[i] for i in range(self.k + 1)], "form": FORM_NAMES[self.form],
+                "stagger": self.stagger, "cus_first": self.cus_first, "us": self.us}
+
+
+class dyn_tune_options(C.Structure):
+    _fields_ = [("max_k", C.c_int), ("partitions", C.c_int), ("n_cus", C.c_int), ("warmup", C.c_int), ("iters", C.c_int),
+                ("use_graph", C.c_int), ("min_gain", C.c_float)]
+
+
+class dyn_tune_result(C.Structure):
+    _fields_ = [("best", dyn_tune_candidate), ("us_sequential", C.c_float), ("n_tried", C.c_int), ("n_skipped", C.c_int)]
+
+
 class dyn_slot_time(C.Structure):
     _fields_ = [("layer", C.c_int), ("op", C.c_int), ("nano", C.c_int), ("n_nano", C.c_int), ("stream", C.c_int),
                 ("partition", C.c_int), ("start_ms", C.c_float), ("main_start_ms", C.c_float), ("main_stop_ms", C.c_float),
@@ -68,7 +88,8 @@ class dyn_slot_time(C.Structure):
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
            "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
-           "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto"]
+           "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
+           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune"]
 
 _lib = None
 
@@ -99,6 +120,10 @@ def lib() -> C.CDLL:
         l.dyn_scheduler_execute.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
         l.dyn_scheduler_finish.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_policy_auto.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        l.dyn_tune_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
+        l.dyn_tune_record.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
+        l.dyn_tune.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
+                               C.c_void_p, C.c_void_p, C.c_int]
         _lib = l
     return _lib
 
@@ -259,6 +284,47 @@ class Scheduler:
         _check(lib().dyn_policy_auto(self._h, _ptr(ctx), int(use_graph), C.byref(c), C.byref(ch)))
         return RecordedSchedule(self, c), {"split": bool(ch.split), "cut_row": ch.cut_row,
                                            "est_sequential_us": ch.est_sequential_us, "est_split_us": ch.est_split_us}
+
+
+    # ---- measured tuning of micro-batch sizes and CU partitions
+    @staticmethod
+    def _tune_options(max_k, partitions, n_cus, warmup, iters, use_graph, min_gain) -> dyn_tune_options:
+        return dyn_tune_options(int(max_k), int(partitions), int(n_cus), int(warmup), int(iters), int(use_graph), float(min_gain))
+
+    def tune_candidates(self, ctx_len: Optional[Sequence[int]] = None, max_k: int = 2, partitions: int = 0,
+                        n_cus: int = 0) -> List[dyn_tune_candidate]:
+        """The candidate schedules the tuner would time for this batch structure (host only)."""
+        ctx = np.ascontiguousarray(ctx_len, dtype=np.int32) if ctx_len is not None else None
+        opt = self._tune_options(max_k, partitions, n_cus, 0, 0, 0, -1.0)
+        n = lib().dyn_tune_candidates(self._h, _ptr(ctx) if ctx is not None else None, C.byref(opt), None, 0)
+        if n < 0:
+            raise DynError(DYN_ERR_INVALID_ARG, dyn_last_error())
+        table = (dyn_tune_candidate * max(n, 1))()
+        lib().dyn_tune_candidates(self._h, _ptr(ctx) if ctx is not None else None, C.byref(opt), table, n)
+        return [table[i] for i in range(n)]
+
+    def tune_record(self, cand: dyn_tune_candidate, n_cus: int = 0, use_graph: bool = False) -> RecordedSchedule:
+        """Records one candidate (host only)."""
+        c = dyn_schedule()
+        _check(lib().dyn_tune_record(self._h, C.byref(cand), int(n_cus), int(use_graph), C.byref(c)))
+        return RecordedSchedule(self, c)
+
+    def tune(self, layer: "DynLayer", batch, stream, ctx_len: Optional[Sequence[int]] = None, max_k: int = 2,
+             partitions: int = 0, warmup: int = 0, iters: int = 0, use_graph: bool = True, min_gain: float = -1.0):
+        """Times every candidate on the device and records the fastest: returns (schedule,
+        result dict, table of candidate dicts).  batch is a dyn_batch; stream a torch stream."""
+        ctx = np.ascontiguousarray(ctx_len, dtype=np.int32) if ctx_len is not None else None
+        opt = self._tune_options(max_k, partitions, 0, warmup, iters, use_graph, min_gain)
+        cap = 256
+        table = (dyn_tune_candidate * cap)()
+        c, res = dyn_schedule(), dyn_tune_result()
+        _check(lib().dyn_tune(layer.handle, C.byref(batch), _ptr(ctx) if ctx is not None else None, C.byref(opt),
+                              C.c_void_p(stream.cuda_stream), self._h, C.byref(c), C.byref(res), table, cap))
+        n = min(cap, res.n_tried + res.n_skipped)
+        return (RecordedSchedule(self, c),
+                {"best": res.best.as_dict(), "us_sequential": res.us_sequential, "n_tried": res.n_tried,
+                 "n_skipped": res.n_skipped},
+                [table[i].as_dict() for i in range(n)])
 
 
 class DynLayer:

@@ -11,7 +11,7 @@ import sys
 HERE = os.path.dirname(os.path.abspath(__file__))
 CSRC = os.path.join(HERE, "csrc")
 LIB = os.path.join(HERE, "libdynlayer.so")
-SOURCES = ["dynlayer.cpp", "dynsched.cpp", "kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn_generic.hip",
+SOURCES = ["dynlayer.cpp", "dynsched.cpp", "dyntune.cpp", "kernels_elementwise.hip", "kernels_gemm.hip", "kernels_attn_generic.hip",
            "kernels_attn_mfma.hip", "kernels_attn_prefill.hip", "kernels_moe.hip"]
 # packed fp32 instructions are switched off for every kernel (hipcc flag, device pass only)
 FLAGS = ["-O3", "--offload-arch=gfx950", "-fPIC", "-std=c++17", "-Wall",

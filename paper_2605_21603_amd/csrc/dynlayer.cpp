@@ -53,6 +53,7 @@ using dyn::g_err;
 struct Dispatch {
     int layer, op, nano, n_nano, r0, r1, stream, partition;
     bool any_multi;          // some sequence contributes more than one token to rows r0..r1
+    bool noop;               // launches nothing: no rows, or the gate when the projection's epilogue applied it
     std::vector<int> deps;   // dispatches (indices into the plan) whose output rows this one reads
     int key() const { return partition * DYN_MAX_STREAMS + stream; }
 };
@@ -249,7 +250,8 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
     for (int l = 0; l < L->cfg.n_layers; ++l)
         for (int i = 0; i < n_slots; ++i) {
             const dyn_slot &sl = slots[i];
-            Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, false, {}};
+            Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, false, false, {}};
+            d.noop = d.r1 <= d.r0 || (sl.op == DYN_OP_SILU && dyn::gemm_gated_supported(L->cfg.dtype, 2 * L->cfg.mlp_inter, L->cfg.hidden));
             {   // sequences inside [r0, r1): cut points are sequence boundaries
                 const int32_t *q = b->q_start_host;
                 const int s0 = (int)(std::lower_bound(q, q + b->n_seqs + 1, d.r0) - q);
@@ -446,8 +448,19 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
     int last_on[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
     std::fill(last_on, last_on + (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS, -1);
     std::vector<hipStream_t> st_of(plan.size());
+    // Dispatches that launch nothing take no part in the stream choreography: whoever depends
+    // on one depends on what it depended on.  Waiting and recording around them would give a
+    // captured graph forked branches without a node and the same edge several times.
+    // (Profiling, eager only, keeps them so that every dispatch has its time marks.)
+    std::vector<std::vector<int>> real_deps(plan.size());
     for (size_t i = 0; i < plan.size(); ++i) {
         const Dispatch &d = plan[i];
+        for (int dep : d.deps) {
+            const bool elided = plan[dep].noop && !profile;
+            for (int r : elided ? real_deps[dep] : std::vector<int>{dep})
+                if (std::find(real_deps[i].begin(), real_deps[i].end(), r) == real_deps[i].end()) real_deps[i].push_back(r);
+        }
+        if (d.noop && !profile) continue;
         const int key = d.key();
         hipStream_t st = origin;
         if (key != 0) {
@@ -457,8 +470,13 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
         }
         used[key] = true;
         st_of[i] = st;
-        for (int dep : d.deps)
-            if (st_of[dep] != st) HIP_TRY(hipStreamWaitEvent(st, L->events[dep], 0));
+        // one wait per producer stream: a stream's events complete in order, the latest covers the rest
+        for (int dep : real_deps[i]) {
+            if (st_of[dep] == st) continue;
+            bool latest = true;
+            for (int other : real_deps[i]) latest = latest && !(st_of[other] == st_of[dep] && other > dep);
+            if (latest) HIP_TRY(hipStreamWaitEvent(st, L->events[dep], 0));
+        }
         if (profile) {
             // the two middle events stay here unless the operator records them around its main kernel
             for (int j = 1; j <= 3; ++j) HIP_TRY(hipEventRecord(L->prof_events[j + 4 * i], st));

@@ -337,4 +337,172 @@ dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int us
     return dyn_scheduler_finish(s, use_graph, out);
 }
 
+// ---------------------------------------------------------------------------------------
+// Candidates of the measured tuner (Section 2.1: unequal micro-batch sizes, the share of
+// compute units per overlapped stream; Section 5.3.4: chosen per batch at run time).
+
+namespace {
+
+// the sequence boundary strictly inside (0, T) nearest to `target`; -1 if there is none
+int snap_to_boundary(const dyn_scheduler *s, long target) {
+    int best = -1;
+    for (int i = 1; i < s->n_seqs; ++i) {
+        const int b = s->q_start[i];
+        if (b <= 0 || b >= s->n_tokens) continue;
+        if (best < 0 || std::labs((long)b - target) < std::labs((long)best - target)) best = b;
+    }
+    return best;
+}
+
+bool op_is_merged(int form, int op) {
+    if (form == DYN_FORM_MLP_MERGED) return op >= DYN_OP_ROUTE;
+    if (form == DYN_FORM_ATTN_SPLIT) return op == DYN_OP_QKV || op == DYN_OP_OPROJ || op == DYN_OP_GATE_UP || op == DYN_OP_DOWN;
+    return false;
+}
+
+}  // namespace
+
+int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, const dyn_tune_options *opt,
+                        dyn_tune_candidate *table, int capacity) {
+    if (!s || !opt || capacity < 0 || (capacity > 0 && !table)) {
+        fail(DYN_ERR_INVALID_ARG, "NULL scheduler, options or table");
+        return -1;
+    }
+    const int max_k = opt->max_k ? opt->max_k : 2;
+    const int n_cus = opt->n_cus ? opt->n_cus : 256;
+    if (max_k < 1 || max_k > 4 || opt->partitions < 0 || opt->partitions > 3 || n_cus < 8 || n_cus % 8) {
+        fail(DYN_ERR_INVALID_ARG, "max_k outside 1..4, partitions outside 0..3 or n_cus not a multiple of 8");
+        return -1;
+    }
+    const int T = s->n_tokens;
+    int n = 0;
+    auto emit = [&](int k, const int32_t *rows, int form, int stagger, int cus_first) {
+        if (n < capacity) {
+            dyn_tune_candidate &c = table[n];
+            std::memset(&c, 0, sizeof c);
+            c.k = k;
+            std::copy(rows, rows + k + 1, c.rows);
+            c.form = form;
+            c.stagger = stagger;
+            c.cus_first = cus_first;
+        }
+        ++n;
+    };
+    const int32_t whole[2] = {0, T};
+    emit(1, whole, DYN_FORM_SEQUENTIAL, 0, 0);
+    if (max_k < 2 || s->n_seqs < 2) return n;
+
+    // two micro-batches: cut points in ascending order, each once
+    std::vector<int> cuts;
+    auto add_cut = [&](int c) {
+        if (c > 0 && c < T && std::find(cuts.begin(), cuts.end(), c) == cuts.end()) cuts.push_back(c);
+    };
+    for (int eighths : {2, 3, 4, 5, 6}) add_cut(snap_to_boundary(s, (long)T * eighths / 8));
+    if (ctx_len_host) {   // the boundary where the keys to attend (the attention's bytes) are halved
+        double total = 0, run = 0;
+        for (int i = 0; i < s->n_seqs; ++i) total += ctx_len_host[i];
+        for (int i = 0; i + 1 < s->n_seqs; ++i) {
+            run += ctx_len_host[i];
+            if (run >= total / 2) { add_cut(s->q_start[i + 1]); break; }
+        }
+    }
+    {   // multi-token (prefill) sequences on one side, single-token (decode) ones on the other
+        int flips = 0, at = -1;
+        for (int i = 1; i < s->n_seqs; ++i) {
+            const bool a = s->q_start[i] - s->q_start[i - 1] > 1, b = s->q_start[i + 1] - s->q_start[i] > 1;
+            if (a != b) { ++flips; at = s->q_start[i]; }
+        }
+        if (flips == 1) add_cut(at);
+    }
+    std::sort(cuts.begin(), cuts.end());
+    const int quarter = n_cus / 4;
+    const int shares[3] = {2 * quarter, 3 * quarter, quarter};
+    for (int c : cuts) {
+        const int32_t rows[3] = {0, c, T};
+        emit(2, rows, DYN_FORM_SPLIT, 0, 0);
+        emit(2, rows, DYN_FORM_SPLIT, 2, 0);
+        emit(2, rows, DYN_FORM_MLP_MERGED, 1, 0);
+        emit(2, rows, DYN_FORM_MLP_MERGED, 2, 0);
+        emit(2, rows, DYN_FORM_ATTN_SPLIT, 1, 0);
+        for (int p = 0; p < opt->partitions; ++p) {
+            emit(2, rows, DYN_FORM_SPLIT, 2, shares[p]);
+            emit(2, rows, DYN_FORM_MLP_MERGED, 2, shares[p]);
+        }
+    }
+    // three and four micro-batches: equal token counts snapped to boundaries, strictly increasing
+    for (int k = 3; k <= max_k; ++k) {
+        int32_t rows[DYN_MAX_NANO + 1] = {0};
+        bool ok = true;
+        for (int i = 1; i < k && ok; ++i) {
+            rows[i] = snap_to_boundary(s, (long)T * i / k);
+            ok = rows[i] > rows[i - 1];
+        }
+        rows[k] = T;
+        if (!ok || rows[k - 1] >= T) continue;
+        emit(k, rows, DYN_FORM_SPLIT, 1, 0);
+        emit(k, rows, DYN_FORM_MLP_MERGED, 1, 0);
+        emit(k, rows, DYN_FORM_ATTN_SPLIT, 1, 0);
+        if (opt->partitions > 0) emit(k, rows, DYN_FORM_MLP_MERGED, 1, shares[0]);
+    }
+    return n;
+}
+
+dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_cus, int use_graph, dyn_schedule *out) {
+    if (!s || !c || !out) return fail(DYN_ERR_INVALID_ARG, "NULL scheduler, candidate or output");
+    if (c->k < 1 || c->k > DYN_MAX_NANO || c->form < DYN_FORM_SEQUENTIAL || c->form > DYN_FORM_ATTN_SPLIT || c->stagger < 0)
+        return fail(DYN_ERR_INVALID_ARG, "candidate with k = %d, form = %d, stagger = %d", c->k, c->form, c->stagger);
+    if ((c->form == DYN_FORM_SEQUENTIAL) != (c->k == 1))
+        return fail(DYN_ERR_INVALID_ARG, "the sequential form has one micro-batch and the others at least two");
+    dyn_status rc;
+    int32_t sizes[DYN_MAX_NANO];
+    for (int i = 0; i < c->k; ++i) sizes[i] = c->rows[i + 1] - c->rows[i];
+    if (c->rows[0] != 0) return fail(DYN_ERR_SCHEDULE, "the first micro-batch starts at row %d", c->rows[0]);
+    if ((rc = dyn_scheduler_split(s, c->k, sizes)) != DYN_OK) return rc;
+    if (c->cus_first) {
+        // the same share of every XCD: the mask has one 32-bit word per 32 CUs
+        if (n_cus <= 0) n_cus = 256;
+        const int words = (n_cus + 31) / 32, per_word = n_cus / words;
+        const int low = c->cus_first / words;
+        if (c->cus_first % words || low < 1 || low >= per_word)
+            return fail(DYN_ERR_INVALID_ARG, "cus_first = %d does not divide into %d mask words of %d CUs", c->cus_first, words, per_word);
+        std::vector<uint32_t> masks((size_t)2 * words);
+        const uint32_t lo = (1u << low) - 1u, all = per_word == 32 ? 0xffffffffu : (1u << per_word) - 1u;
+        for (int i = 0; i < words; ++i) {
+            masks[i] = lo;
+            masks[words + i] = all & ~lo;
+        }
+        if ((rc = dyn_scheduler_set_partitions(s, 2, masks.data(), words)) != DYN_OK) return rc;
+    } else if ((rc = dyn_scheduler_set_partitions(s, 0, nullptr, 0)) != DYN_OK) {
+        return rc;
+    }
+    // Micro-batches advance operator by operator, micro-batch b `stagger` operators behind
+    // b-1; an operator of a merged class is dispatched once, when the last micro-batch arrives.
+    int pos[DYN_MAX_NANO] = {0};
+    const int k = c->k;
+    for (int tick = 0;; ++tick) {
+        bool done = true;
+        for (int b = 0; b < k; ++b) done = done && pos[b] >= s->n_chain;
+        if (done) break;
+        for (int b = 0; b < k; ++b) {
+            if (pos[b] >= s->n_chain || tick < b * c->stagger) continue;
+            const uint8_t op = (uint8_t)s->chain[pos[b]];
+            if (!op_is_merged(c->form, op)) {
+                const uint8_t nb = (uint8_t)b;
+                const int part = c->cus_first ? 1 + (b & 1) : 0;
+                if ((rc = dyn_scheduler_execute(s, 1, &op, &nb, k == 1 ? 0 : b, part)) != DYN_OK) return rc;
+                ++pos[b];
+            } else {
+                bool all_here = true;
+                for (int j = 0; j < k; ++j) all_here = all_here && pos[j] == pos[b];
+                if (!all_here) continue;
+                uint8_t ops[DYN_MAX_NANO], nbs[DYN_MAX_NANO];
+                for (int j = 0; j < k; ++j) { ops[j] = op; nbs[j] = (uint8_t)j; }
+                if ((rc = dyn_scheduler_execute(s, k, ops, nbs, 0, 0)) != DYN_OK) return rc;
+                for (int j = 0; j < k; ++j) ++pos[j];
+            }
+        }
+    }
+    return dyn_scheduler_finish(s, use_graph, out);
+}
+
 }  // extern "C"
