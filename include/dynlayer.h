@@ -236,6 +236,36 @@ typedef struct {
 dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int use_graph, dyn_schedule *out,
                            dyn_policy_choice *choice);
 
+/* ---- Data flow and memory accounting (Section 3.3.1, Algorithm 1; Section 2.1 "Overlapping") -
+ *
+ * The paper's backend analyses the operator graph once: every intermediate tensor gets a
+ * reference count (its out-degree) for lifetime management, and tensors that feed a merge
+ * point are written straight into a preallocated buffer so that a change of the number of
+ * micro-batches between producer and consumer costs no copy.  Here every intermediate lives
+ * at its global row index in a batch-sized buffer of the workspace, so every split or merge
+ * is in place by construction; this call is the static analysis for one schedule: it
+ * derives, per (tensor, layer, micro-batch) region, the dispatches that read it (the
+ * reference count) and its lifetime, and from those the peak of live intermediate bytes
+ * next to what the workspace reserves.  Lifetimes follow issue order within a stream; a
+ * region or a dispatch's scratch stays alive until the next dispatch on the stream of its
+ * last user is issued, because dispatches issued on other streams meanwhile may run beside
+ * it: overlap buffers the results of concurrently running micro-batches, which is the
+ * peak-memory cost the paper names.  Host only. */
+typedef struct {
+    size_t workspace_bytes;             /* dyn_layer_workspace_bytes for this batch: every buffer at batch size, no reuse */
+    size_t peak_live_bytes;             /* largest sum over live regions plus the running dispatch's scratch (split-K
+                                           planes, split-KV partials and work lists, expert lists), this schedule */
+    size_t peak_live_bytes_sequential;  /* the same for the sequential order */
+    int peak_at_dispatch;               /* issue index (layer-major) at which the peak occurs */
+    int n_regions;                      /* (tensor, layer, micro-batch) regions tracked */
+    int max_ref_count;                  /* most dispatches reading one region */
+    int n_resharded;                    /* regions written and read at different numbers of micro-batches (split form ->
+                                           merge form or back): served in place, zero copies */
+} dyn_memory_report;
+
+dyn_status dyn_schedule_memory(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched,
+                               dyn_memory_report *out);
+
 /* ---- Measured tuning of micro-batch sizes and CU partitions (Section 2.1; Section 5.3.4) -
  *
  * The paper names two things a strategy author has to tune by hand: the sizes of the
@@ -249,7 +279,9 @@ enum {
     DYN_FORM_SEQUENTIAL = 0,   /* one micro-batch, chain order, caller's stream */
     DYN_FORM_SPLIT = 1,        /* every operator per micro-batch, micro-batch b on stream b */
     DYN_FORM_MLP_MERGED = 2,   /* per micro-batch up to the second norm; router and MLP once for all (merge form) */
-    DYN_FORM_ATTN_SPLIT = 3    /* the four projections once for all; norms, rotary, attention, gate per micro-batch */
+    DYN_FORM_ATTN_SPLIT = 3,   /* the four projections once for all; norms, rotary, attention, gate per micro-batch */
+    DYN_FORM_MLP_SPLIT = 4     /* everything up to the second norm once for all, router and MLP per micro-batch:
+                                  the shape of the dual-batch-overlap example (Section 3.2.2, Example 1) */
 };
 
 typedef struct {
@@ -286,7 +318,7 @@ typedef struct {
  * for two micro-batches cuts near 1/4, 3/8, 1/2, 5/8 and 3/4 of the tokens snapped to
  * sequence boundaries, the cut that halves the summed context (ctx_len_host, HOST
  * [n_seqs], may be NULL) and the boundary between multi-token and single-token sequences
- * if there is exactly one, each in the three overlapped forms with staggers 0..2; equal
+ * if there is exactly one, each in the four overlapped forms with staggers 1..2; equal
  * cuts for three and four micro-batches up to opt->max_k; CU-partitioned variants per
  * opt->partitions. */
 int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, const dyn_tune_options *opt,

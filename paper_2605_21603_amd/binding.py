@@ -20,8 +20,8 @@ DYN_F32, DYN_BF16 = 0, 1
 DYN_N_OPS = 10
 DYN_SCHED_SEQUENTIAL, DYN_SCHED_EXPLICIT = 0, 1
 DYN_MAX_NANO, DYN_MAX_STREAMS, DYN_MAX_PARTITIONS = 8, 8, 4
-DYN_FORM_SEQUENTIAL, DYN_FORM_SPLIT, DYN_FORM_MLP_MERGED, DYN_FORM_ATTN_SPLIT = 0, 1, 2, 3
-FORM_NAMES = ["sequential", "split", "mlp_merged", "attn_split"]
+DYN_FORM_SEQUENTIAL, DYN_FORM_SPLIT, DYN_FORM_MLP_MERGED, DYN_FORM_ATTN_SPLIT, DYN_FORM_MLP_SPLIT = 0, 1, 2, 3, 4
+FORM_NAMES = ["sequential", "split", "mlp_merged", "attn_split", "mlp_split"]
 OP_NAMES = ["norm1", "qkv", "rope_kv", "attn", "oproj", "norm2", "route", "gate_up", "silu", "down"]
 DENSE_CHAIN = [DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ, DYN_OP_NORM2, DYN_OP_GATE_UP,
                DYN_OP_SILU, DYN_OP_DOWN]
@@ -61,6 +61,14 @@ class dyn_policy_choice(C.Structure):
     _fields_ = [("split", C.c_int), ("cut_row", C.c_int), ("est_sequential_us", C.c_float), ("est_split_us", C.c_float)]
 
 
+class dyn_memory_report(C.Structure):
+    _fields_ = [("workspace_bytes", C.c_size_t), ("peak_live_bytes", C.c_size_t), ("peak_live_bytes_sequential", C.c_size_t),
+                ("peak_at_dispatch", C.c_int), ("n_regions", C.c_int), ("max_ref_count", C.c_int), ("n_resharded", C.c_int)]
+
+    def as_dict(self) -> dict:
+        return {n: getattr(self, n) for n, _ in self._fields_}
+
+
 class dyn_tune_candidate(C.Structure):
     _fields_ = [("k", C.c_int), ("rows", C.c_int32 * (DYN_MAX_NANO + 1)), ("form", C.c_int), ("stagger", C.c_int),
                 ("cus_first", C.c_int), ("us", C.c_float)]
@@ -89,7 +97,7 @@ EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes",
            "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
-           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune"]
+           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory"]
 
 _lib = None
 
@@ -120,6 +128,7 @@ def lib() -> C.CDLL:
         l.dyn_scheduler_execute.argtypes = [C.c_void_p, C.c_int, C.c_void_p, C.c_void_p, C.c_int, C.c_int]
         l.dyn_scheduler_finish.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_policy_auto.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
+        l.dyn_schedule_memory.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_tune_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
         l.dyn_tune_record.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         l.dyn_tune.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -359,6 +368,14 @@ class DynLayer:
     def validate(self, batch: dyn_batch, sched: Schedule) -> None:
         sc = sched.to_c()
         _check(lib().dyn_schedule_validate(self.handle, C.addressof(batch), C.addressof(sc)))
+
+    def memory(self, batch: dyn_batch, sched: Schedule) -> dict:
+        """Static data-flow analysis of a schedule (host only): reference counts, reshard points
+        and the peak of live intermediate bytes next to the sequential order's."""
+        sc = sched.to_c()
+        rep = dyn_memory_report()
+        _check(lib().dyn_schedule_memory(self.handle, C.addressof(batch), C.addressof(sc), C.byref(rep)))
+        return rep.as_dict()
 
     def forward(self, batch: dyn_batch, sched: Schedule, stream: Optional[torch.cuda.Stream] = None) -> None:
         sc = sched.to_c()

@@ -516,6 +516,107 @@ uint64_t graph_key(const dyn_batch *b, const dyn_schedule *s, const std::vector<
     return h;
 }
 
+// Static data-flow analysis of one plan (Section 3.3.1, Algorithm 1): reference counts and
+// lifetimes of the intermediate regions, peak of live bytes in issue order.
+void analyse_memory(const dyn_layer *L, const dyn_batch *b, const std::vector<Dispatch> &plan, int k, const int32_t *rows,
+                    dyn_memory_report *out, size_t *peak, int *peak_at) {
+    const dyn_layer_config &c = L->cfg;
+    const size_t e = esize(c);
+    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    const int n_slots = (int)plan.size() / c.n_layers;
+    const bool moe = c.n_experts > 0, gated = dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden);
+    const int pairs = moe ? c.top_k : 1, H = c.hidden, I = c.mlp_inter, NQKV = qkv_width(c), NQ = c.n_q_heads * c.head_dim;
+    int slot_of[DYN_N_OPS][DYN_MAX_NANO];
+    for (auto &r : slot_of) std::fill(r, r + DYN_MAX_NANO, -1);
+    for (int i = 0; i < n_slots; ++i)
+        for (int nb = plan[i].nano; nb < plan[i].nano + plan[i].n_nano; ++nb) slot_of[plan[i].op][nb] = i;
+    struct Tensor { int producer; int consumers[2]; size_t row_bytes; bool from_previous_layer; bool present; };
+    const Tensor tensors[] = {
+        {DYN_OP_DOWN, {DYN_OP_NORM1, DYN_OP_OPROJ}, H * e, true, true},                       // layer input (not the caller's x)
+        {DYN_OP_NORM1, {DYN_OP_QKV, -1}, ws.ld_h * e, false, true},
+        {DYN_OP_QKV, {DYN_OP_ROPE_KV, DYN_OP_ATTN}, NQKV * e, false, true},                   // q and k rotated in place
+        {DYN_OP_ATTN, {DYN_OP_OPROJ, -1}, ws.ld_attn * e, false, true},
+        {DYN_OP_OPROJ, {DYN_OP_NORM2, DYN_OP_DOWN}, H * e, false, true},                      // x2: normed, and the residual of the MLP
+        {DYN_OP_NORM2, {moe ? DYN_OP_ROUTE : DYN_OP_GATE_UP, moe ? DYN_OP_GATE_UP : -1}, ws.ld_h * e, false, true},
+        {DYN_OP_ROUTE, {DYN_OP_GATE_UP, DYN_OP_DOWN}, (size_t)c.top_k * 8, false, moe},       // selected experts and their weights
+        {DYN_OP_GATE_UP, {DYN_OP_SILU, -1}, (size_t)pairs * 2 * I * e, false, !gated},
+        {gated ? DYN_OP_GATE_UP : DYN_OP_SILU, {DYN_OP_DOWN, -1}, (size_t)pairs * ws.ld_act * e, false, true},
+    };
+    std::vector<size_t> born(plan.size(), 0), dies(plan.size(), 0), scratch(plan.size(), 0);
+    // Issue order is a timeline only within a stream: what is issued on another stream after
+    // dispatch i may run beside it.  So whatever dispatch i is the last to touch stays alive
+    // until the next dispatch on i's own stream is issued (that one cannot start before i ends).
+    std::vector<int> until(plan.size());
+    {
+        int next_on[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
+        std::fill(next_on, next_on + (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS, (int)plan.size());
+        for (int i = (int)plan.size() - 1; i >= 0; --i) {
+            until[i] = next_on[plan[i].key()] - 1;
+            next_on[plan[i].key()] = i;
+        }
+    }
+    out->n_regions = out->max_ref_count = out->n_resharded = 0;
+    for (int l = 0; l < c.n_layers; ++l)
+        for (const Tensor &t : tensors) {
+            if (!t.present || (t.from_previous_layer && l == 0)) continue;
+            for (int nb = 0; nb < k; ++nb) {
+                const size_t n_rows = (size_t)(rows[nb + 1] - rows[nb]);
+                if (!n_rows) continue;
+                const int prod = (t.from_previous_layer ? l - 1 : l) * n_slots + slot_of[t.producer][nb];
+                int refs = 0, last = prod, seen[2] = {-1, -1};
+                bool resharded = false;
+                for (int j = 0; j < 2; ++j) {
+                    if (t.consumers[j] < 0) continue;
+                    const int cons = l * n_slots + slot_of[t.consumers[j]][nb];
+                    if (cons != seen[0]) { seen[refs] = cons; ++refs; }
+                    last = std::max(last, cons);
+                    resharded = resharded || plan[cons].n_nano != plan[prod].n_nano;
+                }
+                born[prod] += n_rows * t.row_bytes;
+                dies[until[last]] += n_rows * t.row_bytes;
+                ++out->n_regions;
+                out->max_ref_count = std::max(out->max_ref_count, refs);
+                out->n_resharded += resharded;
+            }
+        }
+    for (size_t i = 0; i < plan.size(); ++i) {          // scratch a dispatch holds while it runs
+        const Dispatch &d = plan[i];
+        const size_t r = (size_t)std::max(d.r1 - d.r0, 0);
+        auto planes = [&](int N, int K) {
+            return dyn::gemm_uses_plane_buffer(c.dtype, (int)r, N, K) ? (size_t)dyn::gemm_split_k(c.dtype, N, K) * r * N * sizeof(float) : 0;
+        };
+        const size_t lists = moe ? r * c.top_k * 2 * c.n_experts * sizeof(int32_t) : 0;
+        switch (d.op) {
+            case DYN_OP_QKV: scratch[i] = planes(NQKV, H); break;
+            case DYN_OP_OPROJ: scratch[i] = planes(H, NQ); break;
+            case DYN_OP_ATTN:
+                scratch[i] = r * c.n_q_heads * ws.max_chunks * (c.head_dim + 2) * sizeof(float) + (r * ws.max_chunks + 2 * r) * 4 * sizeof(int32_t);
+                break;
+            case DYN_OP_GATE_UP:
+                scratch[i] = moe ? lists + (gated ? 0 : (size_t)dyn::gemm_split_k(c.dtype, 2 * I, H, c.n_experts) > 1
+                                                            ? (size_t)dyn::gemm_split_k(c.dtype, 2 * I, H, c.n_experts) * r * pairs * 2 * I * sizeof(float) : 0)
+                                 : (gated ? 0 : planes(2 * I, H));
+                break;
+            case DYN_OP_DOWN:
+                scratch[i] = moe ? lists + (size_t)dyn::gemm_split_k(c.dtype, H, I, c.n_experts) * r * c.top_k * H * sizeof(float) : planes(H, I);
+                break;
+            default: break;
+        }
+    }
+    size_t live = 0;
+    *peak = 0;
+    *peak_at = 0;
+    for (size_t i = 0; i < plan.size(); ++i) {
+        born[i] += scratch[i];
+        dies[until[i]] += scratch[i];
+    }
+    for (size_t i = 0; i < plan.size(); ++i) {
+        live += born[i];
+        if (live > *peak) { *peak = live; *peak_at = (int)i; }
+        live -= dies[i];
+    }
+}
+
 dyn_status check_config(const dyn_layer_config *c) {
     if (c->dtype != DYN_F32 && c->dtype != DYN_BF16) return fail(DYN_ERR_INVALID_ARG, "dtype %d", c->dtype);
     if (c->n_layers < 1 || c->hidden < 1 || c->n_q_heads < 1 || c->n_kv_heads < 1 || c->head_dim < 1 ||
@@ -586,6 +687,28 @@ size_t dyn_layer_workspace_bytes(const dyn_layer *L, int max_tokens, int max_pag
 dyn_status dyn_schedule_validate(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s) {
     std::vector<Dispatch> plan;
     return build_plan(L, b, s, plan);
+}
+
+dyn_status dyn_schedule_memory(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, dyn_memory_report *out) {
+    if (!out) return fail(DYN_ERR_INVALID_ARG, "NULL report");
+    std::vector<Dispatch> plan;
+    dyn_status rc = build_plan(L, b, s, plan);
+    if (rc != DYN_OK) return rc;
+    *out = dyn_memory_report{};
+    out->workspace_bytes = ws_layout(L, b->n_tokens, b->max_pages_per_seq).total;
+    if (b->n_tokens == 0) return DYN_OK;
+    const int32_t whole[2] = {0, b->n_tokens};
+    dyn_memory_report seq_report{};
+    dyn_schedule seq{};
+    seq.mode = DYN_SCHED_SEQUENTIAL;
+    std::vector<Dispatch> seq_plan;
+    if ((rc = build_plan(L, b, &seq, seq_plan)) != DYN_OK) return rc;
+    int at = 0;
+    analyse_memory(L, b, seq_plan, 1, whole, &seq_report, &out->peak_live_bytes_sequential, &at);
+    const bool explicit_mode = s->mode == DYN_SCHED_EXPLICIT;
+    analyse_memory(L, b, plan, explicit_mode ? s->k : 1, explicit_mode ? s->nano_rows : whole, out, &out->peak_live_bytes,
+                   &out->peak_at_dispatch);
+    return DYN_OK;
 }
 
 dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, void *hip_stream) {

@@ -356,6 +356,7 @@ int snap_to_boundary(const dyn_scheduler *s, long target) {
 
 bool op_is_merged(int form, int op) {
     if (form == DYN_FORM_MLP_MERGED) return op >= DYN_OP_ROUTE;
+    if (form == DYN_FORM_MLP_SPLIT) return op <= DYN_OP_NORM2;
     if (form == DYN_FORM_ATTN_SPLIT) return op == DYN_OP_QKV || op == DYN_OP_OPROJ || op == DYN_OP_GATE_UP || op == DYN_OP_DOWN;
     return false;
 }
@@ -419,11 +420,11 @@ int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, con
     const int shares[3] = {2 * quarter, 3 * quarter, quarter};
     for (int c : cuts) {
         const int32_t rows[3] = {0, c, T};
-        emit(2, rows, DYN_FORM_SPLIT, 0, 0);
         emit(2, rows, DYN_FORM_SPLIT, 2, 0);
         emit(2, rows, DYN_FORM_MLP_MERGED, 1, 0);
         emit(2, rows, DYN_FORM_MLP_MERGED, 2, 0);
         emit(2, rows, DYN_FORM_ATTN_SPLIT, 1, 0);
+        emit(2, rows, DYN_FORM_MLP_SPLIT, 1, 0);
         for (int p = 0; p < opt->partitions; ++p) {
             emit(2, rows, DYN_FORM_SPLIT, 2, shares[p]);
             emit(2, rows, DYN_FORM_MLP_MERGED, 2, shares[p]);
@@ -449,7 +450,7 @@ int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, con
 
 dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_cus, int use_graph, dyn_schedule *out) {
     if (!s || !c || !out) return fail(DYN_ERR_INVALID_ARG, "NULL scheduler, candidate or output");
-    if (c->k < 1 || c->k > DYN_MAX_NANO || c->form < DYN_FORM_SEQUENTIAL || c->form > DYN_FORM_ATTN_SPLIT || c->stagger < 0)
+    if (c->k < 1 || c->k > DYN_MAX_NANO || c->form < DYN_FORM_SEQUENTIAL || c->form > DYN_FORM_MLP_SPLIT || c->stagger < 0)
         return fail(DYN_ERR_INVALID_ARG, "candidate with k = %d, form = %d, stagger = %d", c->k, c->form, c->stagger);
     if ((c->form == DYN_FORM_SEQUENTIAL) != (c->k == 1))
         return fail(DYN_ERR_INVALID_ARG, "the sequential form has one micro-batch and the others at least two");

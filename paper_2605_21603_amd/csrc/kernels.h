@@ -38,6 +38,8 @@ struct GemmGroups {
 // Expert-grouped projections multiply `groups` matrices in one launch and need fewer planes each.
 int gemm_split_k(int dtype, int N, int K, int groups = 1);
 bool gemm_supported(int dtype, int N, int K);
+// True if launch_gemm on `rows` rows writes split-K planes to `partial` (false: one plane, or planes folded in registers).
+bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K);
 
 // ld_out: elements between output rows (>= H).
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int ld_out, int rows, int H, float eps,

@@ -355,6 +355,12 @@ int gemm_split_k(int dtype, int N, int K, int groups) {
     return S;
 }
 
+bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K) {
+    if (dtype == 0 || rows <= 0 || gemm_split_k(dtype, N, K) == 1) return false;
+    // many-row launches fold the planes in registers (the rule of launch_gemm)
+    return !(N % DYN_BIG_BN == 0 && (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) >= 256);
+}
+
 namespace {
 // 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
 // of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at

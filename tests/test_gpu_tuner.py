@@ -89,4 +89,4 @@ def test_every_overlapped_form_of_the_table_is_bit_exact_on_a_prefill_decode_mix
         assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), c.as_dict()
         assert torch.equal(kc.view(torch.uint8), k0.view(torch.uint8)), c.as_dict()
         assert torch.equal(vc.view(torch.uint8), v0.view(torch.uint8)), c.as_dict()
-    assert len(seen) == 6
+    assert len(seen) == 7

@@ -82,7 +82,7 @@ def test_forms_and_staggers_offered_per_cut():
     cands = [c.as_dict() for c in sch.tune_candidates(md["ctx_len"], max_k=2, partitions=1)]
     cut = cands[1]["rows"][1]
     here = [(c["form"], c["stagger"], c["cus_first"]) for c in cands if c["k"] == 2 and c["rows"][1] == cut]
-    assert here == [("split", 0, 0), ("split", 2, 0), ("mlp_merged", 1, 0), ("mlp_merged", 2, 0), ("attn_split", 1, 0),
+    assert here == [("split", 2, 0), ("mlp_merged", 1, 0), ("mlp_merged", 2, 0), ("attn_split", 1, 0), ("mlp_split", 1, 0),
                     ("split", 2, 128), ("mlp_merged", 2, 128)]
     assert all(c["k"] <= 2 for c in cands)
     assert any(c["k"] == 4 for c in (x.as_dict() for x in sch.tune_candidates(md["ctx_len"], max_k=4)))
@@ -99,6 +99,8 @@ def test_recorded_forms_merge_what_they_say():
                                                                         B.DYN_OP_DOWN]
     assert merged(sch.tune_record(by_form[B.DYN_FORM_ATTN_SPLIT])) == [B.DYN_OP_QKV, B.DYN_OP_OPROJ, B.DYN_OP_GATE_UP,
                                                                         B.DYN_OP_DOWN]
+    assert merged(sch.tune_record(by_form[B.DYN_FORM_MLP_SPLIT])) == [B.DYN_OP_NORM1, B.DYN_OP_QKV, B.DYN_OP_ROPE_KV,
+                                                                       B.DYN_OP_ATTN, B.DYN_OP_OPROJ, B.DYN_OP_NORM2]
     seq = sch.tune_record(by_form[B.DYN_FORM_SEQUENTIAL])
     assert [s[0] for s in seq.slots] == B.MOE_CHAIN and all(s[3] == 0 and s[4] == 0 for s in seq.slots)
 
@@ -148,7 +150,7 @@ def test_bad_arguments_are_refused_on_the_host():
             setattr(c, k, v)
         return c
 
-    for bad in (variant(k=0), variant(form=7), variant(stagger=-1), variant(form=B.DYN_FORM_SEQUENTIAL),
+    for bad in (variant(k=0), variant(form=9), variant(stagger=-1), variant(form=B.DYN_FORM_SEQUENTIAL),
                 variant(cus_first=100), variant(cus_first=256)):
         with pytest.raises(B.DynError):
             sch.tune_record(bad, n_cus=256)
