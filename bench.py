@@ -176,6 +176,48 @@ def policy_sweep(args):
                       "worst_policy_efficiency": min(regret)}), flush=True)
 
 
+def trace_overlap(db_path):
+    """Timeline overlap fraction from a rocprofv3 --kernel-trace result database: inside the
+    window in which the library's kernels ran on more than one queue (the overlapped
+    schedules of this run), the share of time with at least two of its kernels resident.
+    Kernels of one stream never overlap, so two resident kernels belong to different
+    micro-batches (or to a merged dispatch beside a split one).  Prints one JSON object."""
+    import sqlite3
+    cur = sqlite3.connect(db_path).cursor()
+    rows = cur.execute("select start, end, queue_id, stream_id from kernels where name like '%dyn::%' order by start").fetchall()
+    if not rows:
+        sys.exit("bench.py: no dyn:: kernels in %s" % db_path)
+    lanes = {}
+    for st, en, q, sid in rows:
+        lanes.setdefault((q, sid), []).append((st, en))
+    main_lane = max(lanes, key=lambda k: len(lanes[k]))
+    side = [iv for k, v in lanes.items() if k != main_lane for iv in v]
+    out = {"kernels": len(rows), "queues": len(lanes)}
+    if side:
+        w0, w1 = min(a for a, _ in side), max(b for _, b in side)
+        # forwards alternate main-only and forked phases: widen the window to whole forwards is not
+        # needed, the fraction is taken over first side-stream start .. last side-stream end
+        events = []
+        for st, en, q, sid in rows:
+            a, b = max(st, w0), min(en, w1)
+            if b > a:
+                events += [(a, 1), (b, -1)]
+        events.sort()
+        depth, last, busy, ovl = 0, w0, 0, 0
+        for t, d in events:
+            if depth >= 1:
+                busy += t - last
+            if depth >= 2:
+                ovl += t - last
+            depth += d
+            last = t
+        out.update({"window_ms": (w1 - w0) * 1e-6, "busy_ms": busy * 1e-6, "overlapped_ms": ovl * 1e-6,
+                    "overlap_fraction_of_window": ovl / (w1 - w0), "overlap_fraction_of_busy": ovl / busy})
+    else:
+        out.update({"window_ms": 0.0, "overlap_fraction_of_window": 0.0})
+    print(json.dumps(out), flush=True)
+
+
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -193,7 +235,11 @@ def main():
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device-to-device five times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
+    ap.add_argument("--trace-overlap", metavar="DB",
+                    help="only read a rocprofv3 --kernel-trace result database and print the timeline overlap fraction")
     args = ap.parse_args()
+    if args.trace_overlap:
+        return trace_overlap(args.trace_overlap)
     if args.policy_sweep:
         if args.gpus != 1:
             sys.exit("bench.py: this build runs on one GPU only (no collectives, no sharding); use --gpus 1")
