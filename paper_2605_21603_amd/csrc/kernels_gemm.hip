@@ -109,10 +109,11 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     bf16_t *__restrict__ Y, int ldy, float *__restrict__ P, size_t plane_stride, int M, int N, int K, int S,
     GemmGroups gr) {
     constexpr int ROWS = BN + MT;                   // rows of a stage buffer: W rows, then X rows
-    constexpr int WNW = NW / 2, RW = BN / WNW;      // waves along n (two along m); W rows per wave column
+    constexpr int WMW = (NW == 8 && BN < MT) ? 4 : 2;   // waves along m
+    constexpr int WNW = NW / WMW, RW = BN / WNW;     // waves along n; W rows per wave column
     constexpr int LPS = ROWS / (NW * 8);            // direct loads per thread and stage (8 rows per wave instruction)
     constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
-    constexpr int NA = RW / 16, NB = MT / 32;       // 16-row operand tiles per wave
+    constexpr int NA = RW / 16, NB = MT / (16 * WMW);       // 16-row operand tiles per wave
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int m_tiles = (M + MT - 1) / MT;
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
@@ -210,7 +211,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     }
 #pragma unroll
     for (int b = 0; b < NB; ++b) {
-        const int row = BN + wm * (MT / 2) + b * 16 + lr;
+        const int row = BN + wm * (MT / WMW) + b * 16 + lr;
         b_off[b] = row * ROWB + ((lq ^ ((row >> 1) & 7)) << 4);
     }
 
@@ -260,7 +261,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
         for (int a = 0; a < NA / 2; ++a)
 #pragma unroll
             for (int b = 0; b < NB; ++b) {
-                const int m = m0 + wm * (MT / 2) + b * 16 + lr;
+                const int m = m0 + wm * (MT / WMW) + b * 16 + lr;
                 const int n = n_tile * (BN / 2) + wn * (RW / 2) + a * 16 + 4 * lq;
                 if (m >= M) continue;
                 const size_t orow = list ? list[m] : m;
@@ -279,7 +280,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     for (int a = 0; a < NA; ++a)
 #pragma unroll
         for (int b = 0; b < NB; ++b) {
-            const int m = m0 + wm * (MT / 2) + b * 16 + lr;
+            const int m = m0 + wm * (MT / WMW) + b * 16 + lr;
             const int n = n0 + wn * RW + a * 16 + 4 * lq;
             if (m >= M) continue;
             const size_t orow = list ? list[m] : m;
@@ -382,6 +383,21 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         return e0;
     }
     const int S = gemm_split_k(dtype, N, K);
+    if (rows > 128 && rows <= 256) {
+        // 129..256 rows: one 256-row tile per (n tile, plane), eight waves 4 x 2, ring of three.  Two
+        // 128-row tiles would move every weight byte into LDS twice; this moves it once (qkv, o, gate/up,
+        // down at 256 rows: 41 / 34 / 90 / 60 us -> 33 / 28 / 79 / 48 us).  Same planes, same k order.
+        const int S2 = gemm_split_k(dtype, N, K);
+        const int grid = ((((N / 128) * S2) + 7) / 8) * 8;
+        hipError_t e2 = launch_gemm_bf16<128, 256, false, 3, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
+        if (e2 == hipSuccess && mid) e2 = hipEventRecord(mid, s);
+        if (e2 != hipSuccess || S2 == 1) return e2;
+        const size_t n_vec = (size_t)rows * N / 4;
+        const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
+        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
+                           (bf16_t *)Y, n_vec, S2);
+        return hipGetLastError();
+    }
     const int MT = rows <= 64 ? 64 : 128;
     const int m_tiles = (rows + MT - 1) / MT;
     // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
@@ -439,7 +455,10 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
     const int groups = gr.n_groups ? gr.n_groups : 1;
     hipError_t e;
     const int big_tiles = (N2 / DYN_BIG_BN) * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-    if (!gr.n_groups && gemm_wide_tiles(max_rows, N2)) {
+    if (!gr.n_groups && max_rows > 128 && max_rows <= 256) {     // one 256-row tile per n tile (see launch_gemm)
+        const int grid = (((N2 / 128) + 7) / 8) * 8;
+        e = launch_gemm_bf16<128, 256, false, 3, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+    } else if (!gr.n_groups && gemm_wide_tiles(max_rows, N2)) {
         const int grid = ((N2 / 256 + 7) / 8) * 8 * ((max_rows + 255) / 256);
         e = launch_gemm_bf16<256, 256, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
     } else if (!gr.n_groups && big_tiles >= 256) {
