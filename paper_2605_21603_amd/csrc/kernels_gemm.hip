@@ -356,13 +356,29 @@ int gemm_split_k(int dtype, int N, int K, int groups) {
     return S;
 }
 
-bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K) {
-    if (dtype == 0 || rows <= 0 || gemm_split_k(dtype, N, K) == 1) return false;
-    // many-row launches fold the planes in registers (the rule of launch_gemm)
-    return !(N % DYN_BIG_BN == 0 && (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) >= 256);
+namespace {
+bool gemm_many_rows(int rows, int N) {      // enough 128 x 128 tiles for the many-row regime
+    return N % DYN_BIG_BN == 0 && (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) >= 256;
 }
 
-namespace {
+// Tile height of the tall-tile path for a launch of `rows` rows with split factor S (0: another path).
+int gemm_tall_rows(int rows, int S, int N, int K) {
+    if (rows <= 128 || N % 128) return 0;
+    if (rows <= 256) return 256;
+    if (S == 1) return rows > 320 && rows <= 384 ? 384 : 0;     // 257..320 rows lose slightly; from 448 the 256 x 256 tile
+    if (rows <= 384) return 384;
+    if (rows <= 512) return 512;
+    if (rows > 1024) return 0;
+    // 513..1024 rows with planes.  Folding planes in registers (the many-row path) wins once it is
+    // available, unless its tiles fill only one of the two workgroup slots per CU and the plane
+    // traffic is small next to the contraction (S / K small: the down projection; 1024 rows: 212 ->
+    // 148 us, while qkv and o stay with the folded path: 79 and 66 us against 99 and 81).
+    const bool folded_ok = gemm_many_rows(rows, N);
+    const bool half_filled = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) < 512;
+    if (folded_ok && !(half_filled && K >= 1400 * S)) return 0;
+    return (rows + 383) / 384 <= (rows + 511) / 512 ? 384 : 512;
+}
+
 // 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
 // of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at
 // least two mostly full m tiles and enough tiles to fill the chip (2112 x 28672 x 4096: 519 ->
@@ -370,6 +386,14 @@ namespace {
 // registers: the second accumulator set does not fit.
 bool gemm_wide_tiles(int rows, int N) { return N % 256 == 0 && rows >= 448 && (N / 256) * ((rows + 255) / 256) >= 192; }
 }  // namespace
+
+bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K) {
+    if (dtype == 0 || rows <= 0) return false;
+    const int S = gemm_split_k(dtype, N, K);
+    if (S == 1) return false;
+    // tall and few-row launches write planes; many-row launches fold them in registers (the rules of launch_gemm)
+    return gemm_tall_rows(rows, S, N, K) != 0 || !gemm_many_rows(rows, N);
+}
 
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
                        size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid) {
@@ -383,13 +407,19 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         return e0;
     }
     const int S = gemm_split_k(dtype, N, K);
-    if (rows > 128 && rows <= 256) {
-        // 129..256 rows: one 256-row tile per (n tile, plane), eight waves 4 x 2, ring of three.  Two
-        // 128-row tiles would move every weight byte into LDS twice; this moves it once (qkv, o, gate/up,
-        // down at 256 rows: 41 / 34 / 90 / 60 us -> 33 / 28 / 79 / 48 us).  Same planes, same k order.
+    // 129..512 rows (up to 1024 with planes, see gemm_tall_rows): tall tiles.  Two to four
+    // 128-row tiles would move every weight byte into LDS that many times; one tile of 256, 384
+    // or 512 rows (eight waves 4 x 2) moves it once: qkv / o / gate-up / down at 256 rows 41 / 34 /
+    // 90 / 60 us -> 33 / 28 / 79 / 48 us, o and down at 512 rows 61 / 112 -> 45 / 84 us.  Same planes,
+    // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 448 rows.
+    const int tall = gemm_tall_rows(rows, gemm_split_k(dtype, N, K), N, K);
+    if (tall) {
         const int S2 = gemm_split_k(dtype, N, K);
-        const int grid = ((((N / 128) * S2) + 7) / 8) * 8;
-        hipError_t e2 = launch_gemm_bf16<128, 256, false, 3, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
+        const int grid = ((((N / 128) * S2) + 7) / 8) * 8 * ((rows + tall - 1) / tall);
+        hipError_t e2;
+        if (tall == 256) e2 = launch_gemm_bf16<128, 256, false, 3, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
+        else if (tall == 384) e2 = launch_gemm_bf16<128, 384, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
+        else e2 = launch_gemm_bf16<128, 512, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
         if (e2 == hipSuccess && mid) e2 = hipEventRecord(mid, s);
         if (e2 != hipSuccess || S2 == 1) return e2;
         const size_t n_vec = (size_t)rows * N / 4;
@@ -403,8 +433,7 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
     // workgroups, a shallow ring and two workgroups per CU so that one multiplies while the other
     // waits at its barrier.  Few-row launches are bound by memory: deep ring, one workgroup per CU.
-    const int big_tiles = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-    const bool big = N % DYN_BIG_BN == 0 && big_tiles >= 256;
+    const bool big = gemm_many_rows(rows, N);
     const bool inreg = S > 1 && big;
     hipError_t e;
     if (big) {
@@ -455,9 +484,11 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
     const int groups = gr.n_groups ? gr.n_groups : 1;
     hipError_t e;
     const int big_tiles = (N2 / DYN_BIG_BN) * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-    if (!gr.n_groups && max_rows > 128 && max_rows <= 256) {     // one 256-row tile per n tile (see launch_gemm)
+    const int tall = gr.n_groups ? 0 : gemm_tall_rows(max_rows, 1, N2, K);
+    if (tall) {                                                  // one tall tile per n tile (see launch_gemm)
         const int grid = (((N2 / 128) + 7) / 8) * 8;
-        e = launch_gemm_bf16<128, 256, false, 3, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+        if (tall == 256) e = launch_gemm_bf16<128, 256, false, 3, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+        else e = launch_gemm_bf16<128, 384, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
     } else if (!gr.n_groups && gemm_wide_tiles(max_rows, N2)) {
         const int grid = ((N2 / 256 + 7) / 8) * 8 * ((max_rows + 255) / 256);
         e = launch_gemm_bf16<256, 256, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);

@@ -150,6 +150,14 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 4, 4, 128, 1024)
         seqs = ((300, 300), (1, 77), (20, 400))
         return Workload("pf_mha", sh, seqs, 11, (0, 300, 321))
+    if name == "pf_480":        # 385..512 rows: one 512-row tile per (n tile, plane) of the projections with planes
+        sh = LayerShape("bf16", 1024, 8, 2, 128, 2048)
+        seqs = ((440, 440),) + tuple((1, c) for c in _uniform_ctx(12, 30, 1, 500)) + ((10, 700),)
+        return Workload("pf_480", sh, seqs, 12, (0, 440, 480))
+    if name == "pf_640":        # 513..1024 rows: two tall tiles
+        sh = LayerShape("bf16", 1024, 8, 2, 128, 2048)
+        seqs = ((300, 300), (290, 1400)) + tuple((1, c) for c in _uniform_ctx(13, 50, 1, 400))
+        return Workload("pf_640", sh, seqs, 13, (0, 590, 640))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
