@@ -10,6 +10,7 @@
 #include <vector>
 
 #include "host_error.h"
+#include "kernels.h"
 
 using dyn::fail;
 
@@ -52,12 +53,12 @@ void reset_recording(dyn_scheduler *s, int k) {
 // this library's kernels reach on an MI355X (per-operator events and kernel traces of the
 // benchmark, Llama-3-8B shapes), plus a fixed cost per kernel launch:
 //   projections, few rows     weights stream at about 3.8 TB/s
-//   projections, many rows    128 x 128 output tiles, 512 at a time (two workgroups per CU);
-//                             a tile of depth K takes 2 * 128 * 128 * K * 2 FLOP at 1/256 of
-//                             0.95 PFLOP/s, and a launch takes ceil(tiles / 512) such rounds
-//                             (160-row tiles when they save a round)
+//   projections, more rows    the launcher's own tile and regime (dyn::gemm_path): a launch takes
+//                             ceil(workgroups / resident workgroups) rounds of one tile's duration,
+//                             a CU working at 1/256 of 0.95 PFLOP/s (1.25 with 256 x 256 tiles);
+//                             planes that are not folded in registers are read back at 5 TB/s
 //   decode attention          K/V stream at about 5.0 TB/s
-//   prefill attention         about 0.16 PFLOP/s (keys re-read from L2 per query group)
+//   prefill attention         about 0.45 PFLOP/s
 //   element-wise operators    about 2 TB/s
 //   a dependent kernel in a replayed graph costs about 2 us before it does anything; the
 //   split-K reduce, the split-KV merge and the work-list kernel add their own launches.
@@ -65,7 +66,7 @@ void reset_recording(dyn_scheduler *s, int k) {
 // eighth of the rates; their absolute values are not meaningful.
 // ---------------------------------------------------------------------------------------
 struct Rates {
-    double w_stream = 3.8e12, mfma = 0.95e15, kv_stream = 5.0e12, prefill = 0.16e15, elementwise = 2.0e12;
+    double w_stream = 3.8e12, mfma = 0.95e15, mfma_wide = 1.25e15, kv_stream = 5.0e12, prefill = 0.45e15, elementwise = 2.0e12;
     double launch_us = 2.0;
 };
 
@@ -84,17 +85,36 @@ OpCost estimate(const dyn_scheduler *s, const int32_t *ctx_len, int r0, int r1) 
     const dyn_layer_config &g = s->cfg;
     const double e = g.dtype == DYN_BF16 ? 2.0 : 4.0;
     Rates R;
-    if (g.dtype != DYN_BF16) { R.w_stream /= 8; R.mfma /= 8; R.kv_stream /= 8; R.prefill /= 8; }
+    if (g.dtype != DYN_BF16) { R.w_stream /= 8; R.mfma /= 8; R.mfma_wide /= 8; R.kv_stream /= 8; R.prefill /= 8; }
     const double T = r1 - r0;
     if (T <= 0) return c;
     const double H = g.hidden, D = g.head_dim, NQ = g.n_q_heads, NKV = g.n_kv_heads, I = g.mlp_inter;
     auto gemm = [&](double n, double k, double helper_launches) {
         const double bytes = n * k * e + T * (n + k) * e;
-        const double tiles = std::ceil(n / 128) * std::ceil(T / 128);
-        const double tile_s = 2.0 * (2.0 * 128 * 128 * k) / (R.mfma / 256);
-        // rounds of 128-row tiles, or of 160-row tiles when that saves a round (the launcher's own rule)
-        const double r128 = std::ceil(tiles / 512), r160 = std::ceil(std::ceil(n / 128) * std::ceil(T / 160) / 512) * 1.25;
-        const double compute = tiles >= 256 ? std::min(r128, r160) * tile_s : 2.0 * std::ceil(T / 128) * 128 * n * k / R.mfma;
+        double compute;
+        if (g.dtype == DYN_BF16 && dyn::gemm_supported(1, (int)n, (int)k)) {
+            // the launcher's own choice of tile and regime: a launch takes ceil(workgroups / resident)
+            // rounds, each as long as one workgroup's tile takes at the rate its regime reaches
+            const dyn::GemmPath p = dyn::gemm_path(1, (int)T, (int)n, (int)k);
+            const double depth = p.folded ? k : k / p.split;
+            const double wg_flops = 2.0 * p.bn * p.mt * depth;
+            const double rounds = std::ceil((double)p.workgroups / p.resident);
+            switch (p.kind) {
+                case dyn::GEMM_TALL:    // one workgroup per CU; planes (if any) are read back by the reduce kernel
+                    compute = rounds * (5e-6 + wg_flops / (R.mfma / 256)) + (p.split > 1 ? p.split * T * n * 4 / 5e12 : 0);
+                    break;
+                case dyn::GEMM_WIDE:
+                    compute = rounds * (3e-6 + wg_flops / (R.mfma_wide / 256));
+                    break;
+                case dyn::GEMM_MANY:    // two workgroups share a CU
+                    compute = rounds * 2.0 * wg_flops / (R.mfma / 256);
+                    break;
+                default:
+                    compute = 2.0 * std::ceil(T / 128) * 128 * n * k / R.mfma;
+            }
+        } else {
+            compute = 2.0 * std::ceil(T / 128) * 128 * n * k / R.mfma;
+        }
         return std::max(bytes / R.w_stream, compute) * 1e6 + R.launch_us * (1 + helper_launches);
     };
     auto elementwise = [&](double bytes) { return bytes / R.elementwise * 1e6 + R.launch_us; };
@@ -301,8 +321,9 @@ dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int us
         const double a = estimate(s, ctx_len_host, 0, cut).total(), b = estimate(s, ctx_len_host, cut, T).total();
         t_split = std::max(a, b) + kUnhiddenShare * std::min(a, b);
     }
-    // the model is good to about 10 %: split only for a predicted gain beyond that
-    const bool split = cut > 0 && t_split < 0.9 * t_seq;
+    // the model is good to about 5-8 % on mixes of 256..4096 prefill tokens and 64..256 decodes:
+    // split only for a predicted gain beyond 5 %
+    const bool split = cut > 0 && t_split < 0.95 * t_seq;
     if (choice) {
         choice->split = split;
         choice->cut_row = split ? cut : 0;

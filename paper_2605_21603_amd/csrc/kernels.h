@@ -38,6 +38,19 @@ struct GemmGroups {
 // Expert-grouped projections multiply `groups` matrices in one launch and need fewer planes each.
 int gemm_split_k(int dtype, int N, int K, int groups = 1);
 bool gemm_supported(int dtype, int N, int K);
+// How launch_gemm runs a plain bf16 projection of `rows` rows (the launcher follows this, and the
+// scheduler's cost model prices it).
+enum { GEMM_FEW = 0, GEMM_TALL = 1, GEMM_WIDE = 2, GEMM_MANY = 3 };
+struct GemmPath {
+    int kind;          // GEMM_FEW: 128 x 64|128 tiles, ring of 4; GEMM_TALL: 128 x 256|384|512, eight waves;
+                       // GEMM_WIDE: 256 x 256, eight waves; GEMM_MANY: 128 x 128|160, two workgroups per CU
+    int bn, mt;        // tile: W rows x X rows
+    int split;         // split-K factor S(N, K)
+    bool folded;       // planes accumulated one after another in registers: no plane buffer, no reduce kernel
+    int workgroups;    // tiles x planes spread over the grid
+    int resident;      // workgroups the chip's 256 CUs hold at a time
+};
+GemmPath gemm_path(int dtype, int rows, int N, int K);
 // True if launch_gemm on `rows` rows writes split-K planes to `partial` (false: one plane, or planes folded in registers).
 bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K);
 

@@ -387,12 +387,55 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
 bool gemm_wide_tiles(int rows, int N) { return N % 256 == 0 && rows >= 448 && (N / 256) * ((rows + 255) / 256) >= 192; }
 }  // namespace
 
+GemmPath gemm_path(int dtype, int rows, int N, int K) {
+    GemmPath p{};
+    p.split = gemm_split_k(dtype, N, K);
+    const int S = p.split, nt = N / 128;
+    const int tall = gemm_tall_rows(rows, S, N, K);
+    if (tall) {
+        // 129..512 rows (up to 1024 with planes, see gemm_tall_rows): tall tiles.  Two to four
+        // 128-row tiles would move every weight byte into LDS that many times; one tile of 256, 384
+        // or 512 rows (eight waves 4 x 2) moves it once: qkv / o / gate-up / down at 256 rows 41 / 34 /
+        // 90 / 60 us -> 33 / 28 / 79 / 48 us, o and down at 512 rows 61 / 112 -> 45 / 84 us.  Same planes,
+        // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 448 rows.
+        p.kind = GEMM_TALL; p.bn = 128; p.mt = tall;
+        p.workgroups = nt * S * ((rows + tall - 1) / tall);
+        p.resident = 256;
+        return p;
+    }
+    // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
+    // workgroups, a shallow ring and two workgroups per CU so that one multiplies while the other
+    // waits at its barrier.  Few-row launches are bound by memory: deep ring, one workgroup per CU.
+    if (gemm_many_rows(rows, N)) {
+        p.folded = S > 1;
+        if (S == 1 && gemm_wide_tiles(rows, N)) {
+            p.kind = GEMM_WIDE; p.bn = 256; p.mt = 256;
+            p.workgroups = (N / 256) * ((rows + 255) / 256);
+            p.resident = 256;
+            return p;
+        }
+        // Tile height: two workgroups fit a CU, so 512 tiles run at a time and the launch takes
+        // ceil(tiles / 512) rounds of a duration proportional to the tile height.  A taller
+        // tile that saves a round wins (2112 rows x 4096 columns: 544 tiles of 128 rows need
+        // two rounds, 448 tiles of 160 rows one).  The summation order of an output element
+        // does not depend on the tile height.
+        const long cost128 = (long)((nt * ((rows + 127) / 128) + 511) / 512) * 128;
+        const long cost160 = (long)((nt * ((rows + 159) / 160) + 511) / 512) * 160;
+        p.kind = GEMM_MANY; p.bn = 128; p.mt = cost160 < cost128 ? 160 : 128;
+        p.workgroups = nt * ((rows + p.mt - 1) / p.mt);
+        p.resident = 512;
+        return p;
+    }
+    p.kind = GEMM_FEW; p.bn = 128; p.mt = rows <= 64 ? 64 : 128;
+    p.workgroups = nt * S * ((rows + p.mt - 1) / p.mt);
+    p.resident = 256;
+    return p;
+}
+
 bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K) {
     if (dtype == 0 || rows <= 0) return false;
-    const int S = gemm_split_k(dtype, N, K);
-    if (S == 1) return false;
-    // tall and few-row launches write planes; many-row launches fold them in registers (the rules of launch_gemm)
-    return gemm_tall_rows(rows, S, N, K) != 0 || !gemm_many_rows(rows, N);
+    const GemmPath p = gemm_path(dtype, rows, N, K);
+    return p.split > 1 && !p.folded;
 }
 
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
@@ -406,67 +449,21 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
         return e0;
     }
-    const int S = gemm_split_k(dtype, N, K);
-    // 129..512 rows (up to 1024 with planes, see gemm_tall_rows): tall tiles.  Two to four
-    // 128-row tiles would move every weight byte into LDS that many times; one tile of 256, 384
-    // or 512 rows (eight waves 4 x 2) moves it once: qkv / o / gate-up / down at 256 rows 41 / 34 /
-    // 90 / 60 us -> 33 / 28 / 79 / 48 us, o and down at 512 rows 61 / 112 -> 45 / 84 us.  Same planes,
-    // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 448 rows.
-    const int tall = gemm_tall_rows(rows, gemm_split_k(dtype, N, K), N, K);
-    if (tall) {
-        const int S2 = gemm_split_k(dtype, N, K);
-        const int grid = ((((N / 128) * S2) + 7) / 8) * 8 * ((rows + tall - 1) / tall);
-        hipError_t e2;
-        if (tall == 256) e2 = launch_gemm_bf16<128, 256, false, 3, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
-        else if (tall == 384) e2 = launch_gemm_bf16<128, 384, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
-        else e2 = launch_gemm_bf16<128, 512, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S2, none);
-        if (e2 == hipSuccess && mid) e2 = hipEventRecord(mid, s);
-        if (e2 != hipSuccess || S2 == 1) return e2;
-        const size_t n_vec = (size_t)rows * N / 4;
-        const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
-        hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
-                           (bf16_t *)Y, n_vec, S2);
-        return hipGetLastError();
-    }
-    const int MT = rows <= 64 ? 64 : 128;
-    const int m_tiles = (rows + MT - 1) / MT;
-    // Many-row launches are bound by the matrix cores: enough tiles without spreading planes over
-    // workgroups, a shallow ring and two workgroups per CU so that one multiplies while the other
-    // waits at its barrier.  Few-row launches are bound by memory: deep ring, one workgroup per CU.
-    const bool big = gemm_many_rows(rows, N);
-    const bool inreg = S > 1 && big;
+    const GemmPath p = gemm_path(dtype, rows, N, K);
+    const int S = p.split, m_tiles = (rows + p.mt - 1) / p.mt;
+    // workgroup ids are dealt to the 8 XCDs in turn: (n tile, plane) pairs are padded to a multiple of 8
+    const int grid = (((N / p.bn) * (p.folded ? 1 : S) + 7) / 8) * 8 * m_tiles;
+#define DYN_GEMM(BN, MT, INREG, NS, NW) \
+    launch_gemm_bf16<BN, MT, INREG, NS, false, NW>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none)
     hipError_t e;
-    if (big) {
-        // Tile height: two workgroups fit a CU, so 512 tiles run at a time and the launch takes
-        // ceil(tiles / 512) rounds of a duration proportional to the tile height.  A taller
-        // tile that saves a round wins (2112 rows x 4096 columns: 544 tiles of 128 rows need
-        // two rounds, 448 tiles of 160 rows one).  The summation order of an output element
-        // does not depend on the tile height.
-        if (gemm_wide_tiles(rows, N) && !inreg) {
-            const int grid = ((N / 256 + 7) / 8) * 8 * ((rows + 255) / 256);
-            e = launch_gemm_bf16<256, 256, false, 2, false, 8>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-            if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
-            return e;
-        }
-        const int nt = N / DYN_BIG_BN;
-        const long cost128 = (long)((nt * ((rows + 127) / 128) + 511) / 512) * 128;
-        const long cost160 = (long)((nt * ((rows + 159) / 160) + 511) / 512) * 160;
-        if (cost160 < cost128) {
-            const int grid = ((nt + 7) / 8) * 8 * ((rows + 159) / 160);
-            if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, 160, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-            else e = launch_gemm_bf16<DYN_BIG_BN, 160, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-        } else {
-            const int grid = ((nt + 7) / 8) * 8 * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-            if (inreg) e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-            else e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-        }
-    } else {
-        const int grid = ((((N / 128) * S) + 7) / 8) * 8 * m_tiles;
-        if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-        else e = launch_gemm_bf16<128, 128, false, 4>(grid, s, X, ldx, W, R, Y, partial, plane_stride, rows, N, K, S, none);
-    }
+    if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GEMM(128, 256, false, 3, 8) : p.mt == 384 ? DYN_GEMM(128, 384, false, 2, 8) : DYN_GEMM(128, 512, false, 2, 8);
+    else if (p.kind == GEMM_WIDE) e = DYN_GEMM(256, 256, false, 2, 8);
+    else if (p.kind == GEMM_MANY && p.mt == 160) e = p.folded ? DYN_GEMM(DYN_BIG_BN, 160, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, 160, false, DYN_BIG_NS, 4);
+    else if (p.kind == GEMM_MANY) e = p.folded ? DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, 4);
+    else e = p.mt == 64 ? DYN_GEMM(128, 64, false, 4, 4) : DYN_GEMM(128, 128, false, 4, 4);
+#undef DYN_GEMM
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
-    if (e != hipSuccess || S == 1 || inreg) return e;
+    if (e != hipSuccess || S == 1 || p.folded) return e;
     const size_t n_vec = (size_t)rows * N / 4;
     const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
     hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
@@ -481,27 +478,23 @@ bool gemm_gated_supported(int dtype, int N2, int K) { return dtype == 1 && gemm_
 hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int ldy, const GemmGroups &gr, int max_rows,
                              int N2, int K, hipStream_t s, hipEvent_t mid) {
     if (max_rows <= 0) return hipSuccess;
-    const int groups = gr.n_groups ? gr.n_groups : 1;
     hipError_t e;
-    const int big_tiles = (N2 / DYN_BIG_BN) * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-    const int tall = gr.n_groups ? 0 : gemm_tall_rows(max_rows, 1, N2, K);
-    if (tall) {                                                  // one tall tile per n tile (see launch_gemm)
-        const int grid = (((N2 / 128) + 7) / 8) * 8;
-        if (tall == 256) e = launch_gemm_bf16<128, 256, false, 3, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
-        else e = launch_gemm_bf16<128, 384, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
-    } else if (!gr.n_groups && gemm_wide_tiles(max_rows, N2)) {
-        const int grid = ((N2 / 256 + 7) / 8) * 8 * ((max_rows + 255) / 256);
-        e = launch_gemm_bf16<256, 256, false, 2, true, 8>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
-    } else if (!gr.n_groups && big_tiles >= 256) {
-        const int grid = (((N2 / DYN_BIG_BN) + 7) / 8) * 8 * ((max_rows + DYN_BIG_MT - 1) / DYN_BIG_MT);
-        e = launch_gemm_bf16<DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0,
-                                                                            max_rows, N2, K, 1, gr, ldy);
-    } else {
+#define DYN_GATED(BN, MT, NS, NW) \
+    launch_gemm_bf16<BN, MT, false, NS, true, NW>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy)
+    if (gr.n_groups) {
         const int MT = max_rows <= 64 ? 64 : 128;
-        const int grid = ((((N2 / 128) * groups) + 7) / 8) * 8 * ((max_rows + MT - 1) / MT);
-        if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
-        else e = launch_gemm_bf16<128, 128, false, 4, true>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy);
+        const int grid = ((((N2 / 128) * gr.n_groups) + 7) / 8) * 8 * ((max_rows + MT - 1) / MT);
+        e = MT == 64 ? DYN_GATED(128, 64, 4, 4) : DYN_GATED(128, 128, 4, 4);
+    } else {
+        const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
+        const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
+        const int grid = ((N2 / p.bn + 7) / 8) * 8 * ((max_rows + mt - 1) / mt);
+        if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);
+        else if (p.kind == GEMM_WIDE) e = DYN_GATED(256, 256, 2, 8);
+        else if (p.kind == GEMM_MANY) e = DYN_GATED(DYN_BIG_BN, DYN_BIG_MT, DYN_BIG_NS, 4);
+        else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 4) : DYN_GATED(128, 128, 4, 4);
     }
+#undef DYN_GATED
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     return e;
 }
