@@ -24,8 +24,17 @@ __global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ h, int
     for (int e = 0; e < kMaxExperts; ++e) acc[e] = 0.f;
     for (int k0 = threadIdx.x * 8; k0 < H; k0 += 256 * 8) {
         float x[8];
+        if constexpr (sizeof(T) == 2) {       // one 16-byte load (rows and k0 are 16-byte aligned)
+            const u32x4 raw = *reinterpret_cast<const u32x4 *>(h + (size_t)t * ldh + k0);
 #pragma unroll
-        for (int i = 0; i < 8; ++i) x[i] = to_f32<T>(h[(size_t)t * ldh + k0 + i]);
+            for (int i = 0; i < 4; ++i) {
+                x[2 * i] = __uint_as_float(raw[i] << 16);
+                x[2 * i + 1] = __uint_as_float(raw[i] & 0xffff0000u);
+            }
+        } else {
+#pragma unroll
+            for (int i = 0; i < 8; ++i) x[i] = to_f32<T>(h[(size_t)t * ldh + k0 + i]);
+        }
 #pragma unroll
         for (int e = 0; e < kMaxExperts; ++e)
             if (e < E) {
