@@ -118,7 +118,8 @@ WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
     w.qkv = take(t * qkv_width(c) * e);
     w.attn = take(t * w.ld_attn * e);
     w.x2 = take(t * c.hidden * e);
-    w.gu = take(t * pairs * 2 * c.mlp_inter * e);
+    // the [gate | up] intermediate exists only when the SiLU gate is not applied in the projection's epilogue
+    w.gu = take(dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden) ? 0 : t * pairs * 2 * c.mlp_inter * e);
     w.act = take(t * pairs * w.ld_act * e);
     w.xa = take(c.n_layers > 1 ? t * c.hidden * e : 0);
     w.xb = take(c.n_layers > 2 ? t * c.hidden * e : 0);
