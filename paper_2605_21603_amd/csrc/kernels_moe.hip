@@ -57,24 +57,24 @@ __global__ __launch_bounds__(256) void route_kernel(const T *__restrict__ h, int
     float logit[kMaxExperts];
 #pragma unroll
     for (int e = 0; e < kMaxExperts; ++e) logit[e] = ((part[0][e] + part[1][e]) + part[2][e]) + part[3][e];
-    bool used[kMaxExperts] = {};
-    int pick[kMaxExperts];
-    float mx = -INFINITY;
+    // No array is indexed with a run-time value here: that would move it from registers to scratch
+    // memory, and this single thread's dependent accesses to it were most of the kernel's time.
+    unsigned used = 0;
+    float mx = 0.f, denom = 0.f;
     for (int j = 0; j < top_k; ++j) {
         int best = -1;
+        float best_val = 0.f;
 #pragma unroll
         for (int e = 0; e < kMaxExperts; ++e)
-            if (e < E && !used[e] && (best < 0 || logit[e] > logit[best])) best = e;
-        used[best] = true;
-        pick[j] = best;
-        mx = fmaxf(mx, logit[best]);
+            if (e < E && !((used >> e) & 1u) && (best < 0 || logit[e] > best_val)) { best = e; best_val = logit[e]; }
+        used |= 1u << best;
+        if (j == 0) mx = best_val;            // picks come in descending order: the first is the maximum
+        const float ex = expf(best_val - mx);
+        denom += ex;
+        sel[(size_t)t * top_k + j] = best;
+        wgt[(size_t)t * top_k + j] = ex;
     }
-    float denom = 0.f;
-    for (int j = 0; j < top_k; ++j) denom += expf(logit[pick[j]] - mx);
-    for (int j = 0; j < top_k; ++j) {
-        sel[(size_t)t * top_k + j] = pick[j];
-        wgt[(size_t)t * top_k + j] = expf(logit[pick[j]] - mx) / denom;
-    }
+    for (int j = 0; j < top_k; ++j) wgt[(size_t)t * top_k + j] = wgt[(size_t)t * top_k + j] / denom;
 }
 
 hipError_t launch_route(int dtype, const void *h, int ldh, const float *w_router, int32_t *sel, float *wgt, int rows,
