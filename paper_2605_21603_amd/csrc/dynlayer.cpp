@@ -71,6 +71,7 @@ struct GraphEntry {
     uint64_t key;
     hipGraphExec_t exec;
     hipGraph_t graph;
+    hipEvent_t last_launch;   // recorded on the caller's stream after every replay
 };
 
 }  // namespace
@@ -87,6 +88,7 @@ struct dyn_layer {
     std::vector<hipEvent_t> events;          // dependency events, one per dispatch of a forward
     hipEvent_t fork_event = nullptr;
     std::vector<GraphEntry> graphs;
+    std::vector<GraphEntry> retired;         // evicted from the cache while their last replay may still run
     bool profiling = false;
     std::vector<hipEvent_t> prof_events;     // timing events: fork, then (start, main start, main stop, stop) per dispatch
     std::vector<Dispatch> prof_plan;
@@ -670,7 +672,12 @@ dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights
 void dyn_layer_destroy(dyn_layer *L) {
     if (!L) return;
     (void)hipDeviceSynchronize();
-    for (auto &g : L->graphs) { (void)hipGraphExecDestroy(g.exec); (void)hipGraphDestroy(g.graph); }
+    for (auto *list : {&L->graphs, &L->retired})
+        for (auto &g : *list) {
+            (void)hipGraphExecDestroy(g.exec);
+            (void)hipGraphDestroy(g.graph);
+            (void)hipEventDestroy(g.last_launch);
+        }
     for (auto ev : L->events) (void)hipEventDestroy(ev);
     for (auto ev : L->prof_events) (void)hipEventDestroy(ev);
     if (L->fork_event) (void)hipEventDestroy(L->fork_event);
@@ -741,9 +748,22 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     }
     if (L->profiling) return fail(DYN_ERR_UNSUPPORTED, "profiling records eager schedules only");
     const uint64_t key = graph_key(b, s, plan);
+    // graphs evicted earlier are destroyed once their last replay has finished
+    for (size_t i = 0; i < L->retired.size();) {
+        if (hipEventQuery(L->retired[i].last_launch) == hipSuccess) {
+            (void)hipGraphExecDestroy(L->retired[i].exec);
+            (void)hipGraphDestroy(L->retired[i].graph);
+            (void)hipEventDestroy(L->retired[i].last_launch);
+            L->retired.erase(L->retired.begin() + i);
+        } else {
+            (void)hipGetLastError();       // "not ready" is an answer, not an error to find later
+            ++i;
+        }
+    }
     for (auto &g : L->graphs)
         if (g.key == key) {
             HIP_TRY(hipGraphLaunch(g.exec, origin));
+            HIP_TRY(hipEventRecord(g.last_launch, origin));
             return DYN_OK;
         }
     if (!L->capture_stream) HIP_TRY(hipStreamCreateWithFlags(&L->capture_stream, hipStreamNonBlocking));
@@ -763,13 +783,20 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     hipGraphExec_t exec = nullptr;
     e = hipGraphInstantiate(&exec, graph, nullptr, nullptr, 0);
     if (e != hipSuccess) { (void)hipGraphDestroy(graph); return fail(DYN_ERR_HIP, "hipGraphInstantiate: %s", hipGetErrorString(e)); }
-    if (L->graphs.size() >= 16) {
-        (void)hipGraphExecDestroy(L->graphs.front().exec);
-        (void)hipGraphDestroy(L->graphs.front().graph);
+    hipEvent_t last_launch = nullptr;
+    e = hipEventCreateWithFlags(&last_launch, hipEventDisableTiming);
+    if (e != hipSuccess) {
+        (void)hipGraphExecDestroy(exec);
+        (void)hipGraphDestroy(graph);
+        return fail(DYN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e));
+    }
+    if (L->graphs.size() >= 16) {          // the oldest entry leaves the cache; the forward is asynchronous, so
+        L->retired.push_back(L->graphs.front());   // its last replay may still be running: destroyed later
         L->graphs.erase(L->graphs.begin());
     }
-    L->graphs.push_back(GraphEntry{key, exec, graph});
+    L->graphs.push_back(GraphEntry{key, exec, graph, last_launch});
     HIP_TRY(hipGraphLaunch(exec, origin));
+    HIP_TRY(hipEventRecord(last_launch, origin));
     return DYN_OK;
 }
 

@@ -148,3 +148,29 @@ def test_profiling_reports_every_dispatch():
             run.run(B.sequential(use_graph=True))
         finally:
             run.layer.set_profiling(False)
+
+
+def test_graph_cache_eviction_keeps_replays_correct():
+    """More distinct schedules than the graph cache holds, replayed back to back without a host
+    wait in between: an evicted graph may still be running when it leaves the cache and is
+    destroyed only after its last replay has finished.  Every replay reproduces the sequential
+    result, and a schedule evicted earlier is captured again when it comes back."""
+    w = gen.config("c2_small")
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    md = gen.metadata(w)
+    sch = B.Scheduler(B.make_config(w.shape), md["q_start"])
+    cands = [c for c in sch.tune_candidates(md["ctx_len"], max_k=2) if c.cus_first == 0][:20]
+    assert len(cands) == 20
+    step = B.DeviceStep(run.layer, data, run.device)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        for _ in range(2):                        # second pass: the first entries were evicted by then
+            for c in cands:
+                run.layer.forward(step.batch, sch.tune_record(c, use_graph=True), st)
+                run.layer.forward(step.batch, sch.tune_record(c, use_graph=True), st)
+    st.synchronize()
+    torch.cuda.synchronize()
+    assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8))
+    assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8))
