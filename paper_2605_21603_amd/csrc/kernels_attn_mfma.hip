@@ -2,8 +2,8 @@
 // HBM-bound operator (the paper's memory-bound "decode attention", Section 2), plus the
 // device-side work lists shared with the prefill form (kernels_attn_prefill.hip).
 //
-// A wave serves one token of a single-token sequence against one 256-position chunk of one
-// kv head, all q heads of that kv head's group at once, so K and V are fetched once per kv
+// A wave serves one token of a single-token sequence against one chunk (up to 256 positions;
+// a sequence's chunks are of equal size up to rounding) of one kv head, all q heads of that kv head's group at once, so K and V are fetched once per kv
 // head.  A page of K is 16 rows of 256 bytes, a page of V is 128 rows (one per head-dim
 // index) of 32 bytes; both are loaded straight into MFMA operand layout with fully used
 // 64-byte / 32-byte row segments, no LDS.  The group's scores are a skinny but real
@@ -119,7 +119,8 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
 // busy, 4 of the 16 columns live with four q heads per kv head).
 struct AttnItem {
     int t, c, n_tok;                  // first token row of the query group, chunk, tokens in the group
-    int n_keys, lp_first, seq_pages;  // keys the group's last token attends, first logical page of the chunk, its pages
+    int n_keys, lp_first, seq_pages;  // keys the group's last token attends, first logical page of the chunk, the sequence's pages
+    int lp_last, key_end;             // last logical page of the chunk; first position past the chunk (at most n_keys)
     int n_pair;                       // tile pairs to walk
     const int32_t *bt;                // block-table row of the group's sequence
 };
@@ -153,8 +154,16 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
         m.t = plan[2 + 2 * e];
         m.n_keys = pos_of_token[m.t + m.n_tok - 1] + 1;
         m.seq_pages = (m.n_keys + PS - 1) / PS;
-        m.lp_first = m.c * sh.chunk_pages;
-        const int n_pg = min(sh.chunk_pages, m.seq_pages - m.lp_first);
+        // A sequence of P pages has ceil(P / chunk_pages) chunks, of equal size up to rounding
+        // (ceil(P / chunks) pages, the last one the rest) rather than full ones and a short tail:
+        // equal work items are what lets a static deal to the waves finish together.  The sizes
+        // depend on the sequence's own length only.
+        const int n_chunks = (m.seq_pages + sh.chunk_pages - 1) / sh.chunk_pages;
+        const int cp = (m.seq_pages + n_chunks - 1) / n_chunks;
+        m.lp_first = m.c * cp;
+        const int n_pg = min(cp, m.seq_pages - m.lp_first);
+        m.lp_last = m.lp_first + n_pg - 1;
+        m.key_end = min(m.n_keys, (m.lp_first + n_pg) * PS);
         m.n_pair = (n_pg + 2 * TILE_PAGES - 1) / (2 * TILE_PAGES);          // a trailing odd tile is walked masked
         m.bt = block_table + (size_t)seq_of_token[m.t] * sh.max_pages_per_seq;
         g_out = g;
@@ -166,12 +175,12 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
     bf16x8 qb[NQG][4], qn[NQG][4];
     int nk_cur[NQG], nk_nxt[NQG];                  // keys each column attends (0 for a dead column)
 
-    // tile TL of item M into register buffer B; page indices past the sequence's last page
+    // tile TL of item M into register buffer B; page indices past the chunk's last page
     // are clamped (their scores are masked, the loads hit L2)
 #define DYN_ATTN_LOAD(B, M, GG, TL)                                                                               \
     {                                                                                                             \
         _Pragma("unroll") for (int pi = 0; pi < TILE_PAGES; ++pi) {                                               \
-            const int lp = min((M).lp_first + (TL) * TILE_PAGES + pi, (M).seq_pages - 1);                         \
+            const int lp = min((M).lp_first + (TL) * TILE_PAGES + pi, (M).lp_last);                               \
             const size_t pg = (size_t)(M).bt[lp] * sh.n_kv + (GG);                                                \
             const bf16_t *kp = k_cache + (pg * PS + lr) * HD + 8 * lq;                                            \
             const bf16_t *vp = v_cache + (pg * HD + lr) * PS + 4 * lq;                                            \
@@ -187,7 +196,7 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
     _Pragma("unroll") for (int q = 0; q < NQG; ++q) {                                                             \
         const bool live = q * TG + col_tok < (M).n_tok && col_tok < TG;                                           \
         const int tq = (M).t + (live ? q * TG + col_tok : 0);                                                     \
-        NK[q] = live ? pos_of_token[tq] + 1 : 0;                                                                  \
+        NK[q] = live ? min(pos_of_token[tq] + 1, (M).key_end) : 0;                                                \
         const bf16_t *qp = qkv + (size_t)tq * ((sh.n_q + 2 * sh.n_kv) * HD) + ((GG) * G + col_head) * HD + 8 * lq; \
         _Pragma("unroll") for (int ks = 0; ks < 4; ++ks) {                                                        \
             u32x4 v = *reinterpret_cast<const u32x4 *>(qp + ks * 32);                                             \
@@ -226,7 +235,7 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
             const u32x2 pw = __builtin_bit_cast(u32x2, pb);                                                       \
             l_run[q] += (__uint_as_float(pw[0] << 16) + __uint_as_float(pw[0] & 0xffff0000u)) +                   \
                         (__uint_as_float(pw[1] << 16) + __uint_as_float(pw[1] & 0xffff0000u));                    \
-            const int nvalid = cur.n_keys - (cur.lp_first + (TL) * TILE_PAGES + pi) * PS - 4 * lq;                \
+            const int nvalid = cur.key_end - (cur.lp_first + (TL) * TILE_PAGES + pi) * PS - 4 * lq;               \
             _Pragma("unroll") for (int dt = 0; dt < 8; ++dt) {                                                    \
                 u32x2 vv = vreg[B][pi][dt];                                                                       \
                 if (nvalid < 4) { /* positions past the group's last: keep stale cache bits out of 0 * x */     \
@@ -282,7 +291,7 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
             float l = l_run[q];
             l += __shfl_xor(l, 16, 64);
             l += __shfl_xor(l, 32, 64);
-            if (nk_cur[q] > cur.c * sh.chunk_pages * PS) {       // the chunk exists for this column's token
+            if (nk_cur[q] > cur.lp_first * PS) {                 // the chunk exists for this column's token
                 const size_t pidx =
                     ((size_t)(cur.t + q * TG + col_tok) * sh.n_q + g_cur * G + col_head) * sh.max_chunks + cur.c;
 #pragma unroll
