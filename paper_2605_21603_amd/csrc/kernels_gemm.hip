@@ -97,7 +97,7 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
     // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
 #define DYN_W(N) case N: __builtin_amdgcn_s_waitcnt(0x0f70 | ((N) & 15) | (((N) >> 4) << 14)); break;
     switch (n) {
-        DYN_W(0) DYN_W(6) DYN_W(7) DYN_W(8) DYN_W(9) DYN_W(12) DYN_W(14) DYN_W(16) DYN_W(18) DYN_W(21) DYN_W(24) DYN_W(27) DYN_W(28) DYN_W(32)
+        DYN_W(0) DYN_W(2) DYN_W(3) DYN_W(4) DYN_W(5) DYN_W(6) DYN_W(7) DYN_W(8) DYN_W(9) DYN_W(12) DYN_W(14) DYN_W(16) DYN_W(18) DYN_W(21) DYN_W(24) DYN_W(27) DYN_W(28) DYN_W(32)
         default: __builtin_amdgcn_s_waitcnt(0x0f70); break;       // unknown count: wait for everything
     }
 #undef DYN_W
@@ -460,7 +460,7 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     else if (p.kind == GEMM_WIDE) e = DYN_GEMM(256, 256, false, 2, 8);
     else if (p.kind == GEMM_MANY && p.mt == 160) e = p.folded ? DYN_GEMM(DYN_BIG_BN, 160, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, 160, false, DYN_BIG_NS, 4);
     else if (p.kind == GEMM_MANY) e = p.folded ? DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, 4);
-    else e = p.mt == 64 ? DYN_GEMM(128, 64, false, 4, 4) : DYN_GEMM(128, 128, false, 4, 4);
+    else e = p.mt == 64 ? DYN_GEMM(128, 64, false, 4, 8) : DYN_GEMM(128, 128, false, 4, 8);
 #undef DYN_GEMM
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1 || p.folded) return e;
@@ -484,7 +484,7 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
     if (gr.n_groups) {
         const int MT = max_rows <= 64 ? 64 : 128;
         const int grid = ((((N2 / 128) * gr.n_groups) + 7) / 8) * 8 * ((max_rows + MT - 1) / MT);
-        e = MT == 64 ? DYN_GATED(128, 64, 4, 4) : DYN_GATED(128, 128, 4, 4);
+        e = MT == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
     } else {
         const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
         const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
@@ -492,7 +492,7 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
         if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);
         else if (p.kind == GEMM_WIDE) e = DYN_GATED(256, 256, 2, 8);
         else if (p.kind == GEMM_MANY) e = DYN_GATED(DYN_BIG_BN, DYN_BIG_MT, DYN_BIG_NS, 4);
-        else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 4) : DYN_GATED(128, 128, 4, 4);
+        else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
     }
 #undef DYN_GATED
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
@@ -523,8 +523,8 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
     const int ns = (N / 128) * S * gr.n_groups;
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
     hipError_t e;
-    if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
-    else e = launch_gemm_bf16<128, 128, false, 4>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
+    if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4, false, 8>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
+    else e = launch_gemm_bf16<128, 128, false, 4, false, 8>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1 || gr.force_planes) return e;
     // output rows row0 .. row0 + n_rows - 1 are exactly the rows the groups wrote
