@@ -134,8 +134,15 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         const int i = sub * 4 + q * 128;
         if (i < d) {
             T *o = out + (size_t)t * ld_out + (pair - t * sh.n_q) * d + i;
+            if constexpr (sizeof(T) == 2) {            // one 8-byte store (rows and i are 8-byte aligned)
+                u32x2 w;
+                w[0] = (uint32_t)f2bf(acc[q][0] * inv) | ((uint32_t)f2bf(acc[q][1] * inv) << 16);
+                w[1] = (uint32_t)f2bf(acc[q][2] * inv) | ((uint32_t)f2bf(acc[q][3] * inv) << 16);
+                *reinterpret_cast<u32x2 *>(o) = w;
+            } else {
 #pragma unroll
-            for (int r = 0; r < 4; ++r) o[r] = from_f32<T>(acc[q][r] * inv);
+                for (int r = 0; r < 4; ++r) o[r] = from_f32<T>(acc[q][r] * inv);
+            }
         }
     }
 }
