@@ -28,8 +28,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # WRITE_SIZE in runs of their own, scaled by a 1 GiB copy probe).  Counters cannot be read
 # from inside this process, so the figure of the committed counter summary is repeated here.
 ROCPROF_TRAFFIC = {
-    "c2": {"bytes": 1274151116 + 21838745,
-           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 622,144 x 2.0 KiB + WRITE_SIZE 21,327 KiB)"},
+    "c2": {"bytes": 1274151526 + 21834035,
+           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 622,144 x 2.0 KiB + WRITE_SIZE 21,322 KiB)"},
 }
 
 
