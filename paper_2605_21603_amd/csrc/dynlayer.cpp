@@ -72,6 +72,7 @@ struct GraphEntry {
     hipGraphExec_t exec;
     hipGraph_t graph;
     hipEvent_t last_launch;   // recorded on the caller's stream after every replay
+    int side_streams;         // streams of the schedule besides the caller's: parallel branches of the graph
 };
 
 }  // namespace
@@ -790,11 +791,26 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
         (void)hipGraphDestroy(graph);
         return fail(DYN_ERR_HIP, "hipEventCreateWithFlags: %s", hipGetErrorString(e));
     }
-    if (L->graphs.size() >= 16) {          // the oldest entry leaves the cache; the forward is asynchronous, so
-        L->retired.push_back(L->graphs.front());   // its last replay may still be running: destroyed later
+    int side_streams = 0;
+    {
+        bool seen[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS] = {};
+        for (const Dispatch &d : plan)
+            if (d.key() != 0 && !seen[d.key()]) { seen[d.key()] = true; ++side_streams; }
+    }
+    // The oldest entries leave the cache at 16 graphs, and earlier when the cached graphs together
+    // have many parallel branches: both segmentation faults seen inside hipGraphLaunch came with
+    // 26 or more side branches among the instantiated graphs, none with 20 or fewer.  The forward
+    // is asynchronous, so an evicted graph's last replay may still be running: destroyed later.
+    auto branches = [&]() {
+        int n = side_streams;
+        for (const GraphEntry &g : L->graphs) n += g.side_streams;
+        return n;
+    };
+    while (!L->graphs.empty() && (L->graphs.size() >= 16 || branches() > 16)) {
+        L->retired.push_back(L->graphs.front());
         L->graphs.erase(L->graphs.begin());
     }
-    L->graphs.push_back(GraphEntry{key, exec, graph, last_launch});
+    L->graphs.push_back(GraphEntry{key, exec, graph, last_launch, side_streams});
     HIP_TRY(hipGraphLaunch(exec, origin));
     HIP_TRY(hipEventRecord(last_launch, origin));
     return DYN_OK;
