@@ -68,8 +68,8 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 }
 
 // ------------------------------------------------------------------ bf16 MFMA path
-// Workgroup = 4 waves on a BN (W rows) x MT (X rows) output tile and one K plane (or, INREG,
-// all planes in turn).  What bounds this kernel below a few hundred rows is not the matrix
+// Workgroup = NW waves (4 or 8) on a BN (W rows) x MT (X rows) output tile and one K plane (or,
+// INREG, all planes in turn).  What bounds this kernel below a few hundred rows is not the matrix
 // cores and not even HBM alone but the L2 -> CU path: every byte of W must cross it once and
 // the X tile crosses it once per W tile, so both operands are fetched exactly once per
 // workgroup, with fully coalesced 128-byte row segments (8 lanes per row), by direct
@@ -79,7 +79,10 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // 1 KB window, so rows sit at a 128-byte pitch; bank conflicts of the MFMA-layout reads
 // (lane l: row l%16, 8 consecutive k at 8*(l/16)) are avoided by an XOR swizzle of the
 // 16-byte column with bits 1..3 of the row, applied to the global column a lane fetches.
-// Waves sit 2 x 2 on the tile.  D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).
+// Waves sit 2 (along X rows; 4 on the tall tiles) x NW/2 (along W rows) on the tile.
+// D[i][j]: i = W row (4*(l/16)+r), j = X row (l%16).  Which tile a launch uses is gemm_path's
+// decision: 128 x 64|128 with a ring of 4 for few rows, 128 x 256|384|512 for 129..512 rows,
+// 256 x 256 for many rows without planes, 128 x 128|160 with two workgroups per CU otherwise.
 //
 // INREG: one workgroup walks all S planes of its tile and adds the plane sums in registers
 // (same order, same bits as the plane buffers + gemm_reduce_kernel) - for many-row launches,
