@@ -115,6 +115,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     constexpr int WMW = (NW == 8 && BN < MT) ? 4 : 2;   // waves along m
     constexpr int WNW = NW / WMW, RW = BN / WNW;     // waves along n; W rows per wave column
     constexpr int LPS = ROWS / (NW * 8);            // direct loads per thread and stage (8 rows per wave instruction)
+    static_assert(ROWS % (NW * 8) == 0, "the stage's rows must divide among the waves' direct loads");
     constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
     constexpr int NA = RW / 16, NB = MT / (16 * WMW);       // 16-row operand tiles per wave
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
