@@ -158,6 +158,14 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 1024, 8, 2, 128, 2048)
         seqs = ((300, 300), (290, 1400)) + tuple((1, c) for c in _uniform_ctx(13, 50, 1, 400))
         return Workload("pf_640", sh, seqs, 13, (0, 590, 640))
+    if name == "bf16_hd64":     # head_dim 64: outside the matrix-core attention kernels, the generic path in bf16
+        sh = LayerShape("bf16", 256, 4, 2, 64, 512)
+        seqs = ((23, 23), (1, 70), (1, 200), (9, 41), (1, 1))
+        return Workload("bf16_hd64", sh, seqs, 14, (0, 24, 35))
+    if name == "bf16_ps32":     # 32-position pages with head_dim 128: also the generic attention path
+        sh = LayerShape("bf16", 512, 4, 2, 128, 512, page_size=32)
+        seqs = ((1, 33), (40, 100), (1, 64), (1, 129))
+        return Workload("bf16_ps32", sh, seqs, 15, (0, 41, 43))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
