@@ -166,6 +166,10 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 4, 2, 128, 512, page_size=32)
         seqs = ((1, 33), (40, 100), (1, 64), (1, 129))
         return Workload("bf16_ps32", sh, seqs, 15, (0, 41, 43))
+    if name == "bf16_max":      # the largest head_dim and expert count the layer accepts, 64-position pages
+        sh = LayerShape("bf16", 256, 2, 1, 256, 128, n_experts=16, top_k=4, page_size=64)
+        seqs = ((1, 65), (17, 17), (1, 300), (5, 130), (1, 1), (1, 64))
+        return Workload("bf16_max", sh, seqs, 16, (0, 18, 26))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
