@@ -351,7 +351,8 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
                                         (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
                                         (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
-                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 2) * 4, d.any_multi, sh, rows, st, mid, pre);
+                                        (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 2) * 4, d.any_multi, sh, rows, st, mid, pre,
+                                        d.layer > 0);   // every layer dispatches the same row ranges: layer 0 built the work lists
             break;
         case DYN_OP_OPROJ:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),

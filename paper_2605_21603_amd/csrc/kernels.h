@@ -102,7 +102,8 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
                             float *part_o, float *part_ml, int32_t *plan, bool any_multi, const AttnShape &sh,
                             int rows, hipStream_t s, hipEvent_t mid = nullptr,    // mid: recorded between the chunk kernel and the combine
-                            hipEvent_t pre = nullptr);  // pre: recorded after the work-list kernel, before the chunk kernel
+                            hipEvent_t pre = nullptr,   // pre: recorded after the work-list kernel, before the chunk kernel
+                            bool plan_ready = false);   // `plan` already holds the lists of these rows (built by an earlier layer's call)
 
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
 hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s);

@@ -82,7 +82,11 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
                                                            const float *__restrict__ part_ml,
                                                            const int32_t *__restrict__ pos_of_token,
                                                            const int32_t *__restrict__ ct_of_token,
-                                                           T *__restrict__ out, int ld_out, AttnShape sh, int n_pairs) {
+                                                           T *__restrict__ out, int ld_out, AttnShape sh, int n_pairs,
+                                                           int32_t *__restrict__ counter_reset) {
+    // the query-block kernel that ran before this one has drained its work counter: zero it for the
+    // next launch that walks the same work list (the next layer of the forward)
+    if (counter_reset && blockIdx.x == 0 && threadIdx.x == 0) *counter_reset = 0;
     const int pair = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
     if (pair >= n_pairs) return;
     const int t = pair / sh.n_q;
@@ -149,15 +153,15 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
                                     const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
-                                    const AttnShape &sh, int rows, hipStream_t s) {
+                                    const AttnShape &sh, int rows, hipStream_t s, int32_t *counter_reset) {
     const int n_pairs = rows * sh.n_q;
     const dim3 grid((n_pairs + 7) / 8), block(256);
     if (dtype == 0) {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs);
-        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs, counter_reset);
+        else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs, counter_reset);
     } else {
-        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
-        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs);
+        if (base2) hipLaunchKernelGGL((attn_combine_kernel<bf16_t, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs, counter_reset);
+        else hipLaunchKernelGGL((attn_combine_kernel<bf16_t, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (bf16_t *)out, ld_out, sh, n_pairs, counter_reset);
     }
     return hipGetLastError();
 }
@@ -177,7 +181,7 @@ hipError_t launch_attention_generic(int dtype, const void *qkv, const int32_t *s
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, nullptr, out, ld_out, sh, rows, s);
+    return launch_attention_combine(dtype, false, part_o, part_ml, pos_of_token, nullptr, out, ld_out, sh, rows, s, nullptr);
 }
 
 }  // namespace dyn

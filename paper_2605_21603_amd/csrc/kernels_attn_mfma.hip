@@ -24,7 +24,7 @@ namespace dyn {
 
 hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
                                     const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
-                                    const AttnShape &sh, int rows, hipStream_t s);
+                                    const AttnShape &sh, int rows, hipStream_t s, int32_t *counter_reset);
 int attn_prefill_block_tokens(const AttnShape &sh);
 hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                                     const int32_t *block_table, const void *k_cache, const void *v_cache, float *part_o,
@@ -331,7 +331,7 @@ bool attention_mfma_supported(int dtype, const AttnShape &sh) {
 hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                             const int32_t *block_table, const void *k_cache, const void *v_cache, void *out, int ld_out,
                             float *part_o, float *part_ml, int32_t *plan, bool any_multi, const AttnShape &sh, int rows,
-                            hipStream_t s, hipEvent_t mid, hipEvent_t pre) {
+                            hipStream_t s, hipEvent_t mid, hipEvent_t pre, bool plan_ready) {
     if (rows <= 0) return hipSuccess;
     if (!attention_mfma_supported(dtype, sh))
         return launch_attention_generic(dtype, qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, out, ld_out,
@@ -340,8 +340,11 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     int32_t *plan0 = plan, *plan1 = plan + 2 + 2 * (size_t)rows * sh.max_chunks;
     int32_t *ct_of_token = plan + 4 + 4 * (size_t)rows * sh.max_chunks;
     const int ct1 = kPrefillChunkPages * PS;
-    hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
-                       attn_prefill_block_tokens(sh), ct1, plan0, plan1, ct_of_token);
+    // The lists depend on the rows' sequences and positions only: the first layer of a forward
+    // builds them, the others walk them again (plan_ready).
+    if (!plan_ready)
+        hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
+                           attn_prefill_block_tokens(sh), ct1, plan0, plan1, ct_of_token);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
@@ -359,7 +362,7 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
                                      plan1, kPrefillChunkPages, max_items, groups, s);
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
-    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, ct_of_token, out, ld_out, sh, rows, s);
+    return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, ct_of_token, out, ld_out, sh, rows, s, plan1 + 1);
 }
 
 }  // namespace dyn
