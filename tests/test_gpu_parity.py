@@ -12,7 +12,7 @@ from gpu_util import GpuRun, check_against_oracle, say
 pytestmark = pytest.mark.gpu
 
 SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small", "c4_small", "f32_moe_small", "c3_mid", "pf_long", "pf_g8",
-         "pf_mha", "pf_480", "pf_640", "bf16_hd64", "bf16_ps32", "bf16_max"]
+         "pf_mha", "pf_480", "pf_640", "bf16_hd64", "bf16_ps32", "bf16_max", "stack_mixed"]
 
 
 def schedules_for(w):
@@ -94,7 +94,7 @@ def cu_masks_halves():
     return [lo, hi]
 
 
-@pytest.mark.parametrize("name", ["c2_small", "c5_small"])
+@pytest.mark.parametrize("name", ["c2_small", "c5_small", "stack_mixed"])
 def test_cu_partitioned_streams_and_graph_replay(name):
     """Micro-batches on CU-masked streams, eager and captured into a HIP graph; the graph is
     replayed several times with eager forwards and synchronisations in between and every

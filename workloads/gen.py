@@ -138,6 +138,10 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536, n_layers=3)
         ctx = _uniform_ctx(4, 24, 1, 520)
         return Workload("c5_small", sh, tuple((1, c) for c in ctx), 4, (0, 5, 11, 18, 24))
+    if name == "stack_mixed":   # three layers over prefill chunks and decodes: later layers walk layer 0's attention work lists
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024, n_layers=3)
+        seqs = ((90, 1300), (1, 700), (1, 20), (40, 40), (1, 1), (1, 1025), (6, 300))
+        return Workload("stack_mixed", sh, seqs, 17, (0, 92, 140))
     if name == "pf_long":       # a prefill chunk after 2300 cached positions: several 1024-position chunks per query block
         sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
         seqs = ((200, 2500), (1, 1100), (70, 70), (1, 33), (3, 1027))
