@@ -154,6 +154,14 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 4, 4, 128, 1024)
         seqs = ((300, 300), (1, 77), (20, 400))
         return Workload("pf_mha", sh, seqs, 11, (0, 300, 321))
+    if name == "pf_g16":        # sixteen q heads on one kv head: one token per 16-column set
+        sh = LayerShape("bf16", 512, 16, 1, 128, 512)
+        seqs = ((21, 21), (1, 500), (1, 16), (18, 1040), (1, 1), (1, 257))
+        return Workload("pf_g16", sh, seqs, 18, (0, 22, 43))
+    if name == "pf_g2":         # two q heads per kv head: eight tokens per set, 128-token query blocks
+        sh = LayerShape("bf16", 512, 4, 2, 128, 512)
+        seqs = ((1, 333), (140, 140), (1, 17), (70, 1200), (1, 1024))
+        return Workload("pf_g2", sh, seqs, 19, (0, 141, 213))
     if name == "pf_480":        # 385..512 rows: one 512-row tile per (n tile, plane) of the projections with planes
         sh = LayerShape("bf16", 1024, 8, 2, 128, 2048)
         seqs = ((440, 440),) + tuple((1, c) for c in _uniform_ctx(12, 30, 1, 500)) + ((10, 700),)
