@@ -30,6 +30,8 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 ROCPROF_TRAFFIC = {
     "c2": {"bytes": 1274151526 + 21834035,
            "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 622,144 x 2.0 KiB + WRITE_SIZE 21,322 KiB)"},
+    "c5": {"bytes": 5060041114 + 86052864,
+           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,470,723 x 2.0 KiB + WRITE_SIZE 84,036 KiB)"},
 }
 
 
