@@ -55,6 +55,7 @@ struct Dispatch {
     bool any_multi;          // some sequence contributes more than one token to rows r0..r1
     bool noop;               // launches nothing: no rows, or the gate when the projection's epilogue applied it
     std::vector<int> deps;   // dispatches (indices into the plan) whose output rows this one reads
+    bool lists_ready = false;   // MoE down projection: the gate/up dispatch of the same rows already built its expert lists
     int key() const { return partition * DYN_MAX_STREAMS + stream; }
 };
 
@@ -271,6 +272,17 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
             }
             plan.push_back(std::move(d));
         }
+    // The expert lists of a dispatch depend on its rows' routing only: a down projection over
+    // exactly the rows of one gate/up dispatch (which it follows in its micro-batches' chain)
+    // reads that dispatch's lists instead of building its own.
+    if (L->cfg.n_experts)
+        for (size_t i = 0; i < plan.size(); ++i) {
+            Dispatch &d = plan[i];
+            if (d.op != DYN_OP_DOWN || d.noop) continue;
+            const int first = d.layer * n_slots;
+            for (int j = first; j < first + n_slots; ++j)
+                if (plan[j].op == DYN_OP_GATE_UP && !plan[j].noop && plan[j].r0 == d.r0 && plan[j].r1 == d.r1) d.lists_ready = true;
+        }
     return DYN_OK;
 }
 
@@ -405,9 +417,9 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
         case DYN_OP_DOWN:
             if (c.n_experts) {
                 const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
-                int32_t *counts = (int32_t *)(base + ws.lists_down) + (size_t)pair0 * 2 * c.n_experts;
+                int32_t *counts = (int32_t *)(base + (d.lists_ready ? ws.lists_gu : ws.lists_down)) + (size_t)pair0 * 2 * c.n_experts;
                 int32_t *lists = counts + c.n_experts;
-                err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
+                if (!d.lists_ready) err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
                 if (err != hipSuccess) break;
                 const int Sd = dyn::gemm_split_k(c.dtype, H, I, c.n_experts);
                 const size_t plane = T * c.top_k * H;
