@@ -365,11 +365,25 @@ bool gemm_many_rows(int rows, int N) {      // enough 128 x 128 tiles for the ma
     return N % DYN_BIG_BN == 0 && (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) >= 256;
 }
 
+// 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
+// of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at
+// least two m tiles and enough tiles to fill the chip (2112 x 28672 x 4096: 519 -> 432 us; 512
+// rows: 164 -> 121 us; 400 rows: 128 us with a 512-row tall tile, 120 us here).  Not for planes
+// folded in registers: the second accumulator set does not fit.
+bool gemm_wide_tiles(int rows, int N) { return N % 256 == 0 && rows >= 385 && (N / 256) * ((rows + 255) / 256) >= 192; }
+
 // Tile height of the tall-tile path for a launch of `rows` rows with split factor S (0: another path).
 int gemm_tall_rows(int rows, int S, int N, int K) {
     if (rows <= 128 || N % 128) return 0;
     if (rows <= 256) return 256;
-    if (S == 1) return rows > 320 && rows <= 384 ? 384 : 0;     // 257..320 rows lose slightly; from 448 the 256 x 256 tile
+    if (S == 1) {
+        // Without planes because the n tiles alone fill the chip (gate/up): one tall tile up to 384
+        // rows (at 264..320 rows 134-137 us with three 128-row tiles, 108-111 us with one of 384),
+        // then the 256 x 256 tile where it applies (400..440 rows: 140-144 us -> 120; a 512-row tall
+        // tile 128).  Without planes because the depth is too short to split: as measured before.
+        if (N / 128 < 192) return rows > 320 && rows <= 384 ? 384 : 0;
+        return rows <= 384 ? 384 : (rows < 448 && !gemm_wide_tiles(rows, N)) ? 512 : 0;
+    }
     if (rows <= 384) return 384;
     if (rows <= 512) return 512;
     if (rows > 1024) return 0;
@@ -383,12 +397,6 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
     return (rows + 383) / 384 <= (rows + 511) / 512 ? 384 : 512;
 }
 
-// 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
-// of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at
-// least two mostly full m tiles and enough tiles to fill the chip (2112 x 28672 x 4096: 519 ->
-// 432 us; 512 rows: 164 -> 121 us; 320 rows and fewer lose).  Not for planes folded in
-// registers: the second accumulator set does not fit.
-bool gemm_wide_tiles(int rows, int N) { return N % 256 == 0 && rows >= 448 && (N / 256) * ((rows + 255) / 256) >= 192; }
 }  // namespace
 
 GemmPath gemm_path(int dtype, int rows, int N, int K) {
@@ -401,7 +409,7 @@ GemmPath gemm_path(int dtype, int rows, int N, int K) {
         // 128-row tiles would move every weight byte into LDS that many times; one tile of 256, 384
         // or 512 rows (eight waves 4 x 2) moves it once: qkv / o / gate-up / down at 256 rows 41 / 34 /
         // 90 / 60 us -> 33 / 28 / 79 / 48 us, o and down at 512 rows 61 / 112 -> 45 / 84 us.  Same planes,
-        // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 448 rows.
+        // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 385 rows.
         p.kind = GEMM_TALL; p.bn = 128; p.mt = tall;
         p.workgroups = nt * S * ((rows + tall - 1) / tall);
         p.resident = 256;
@@ -493,7 +501,7 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
         const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
         const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
         const int grid = ((N2 / p.bn + 7) / 8) * 8 * ((max_rows + mt - 1) / mt);
-        if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);
+        if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : p.mt == 384 ? DYN_GATED(128, 384, 2, 8) : DYN_GATED(128, 512, 2, 8);
         else if (p.kind == GEMM_WIDE) e = DYN_GATED(256, 256, 2, 8);
         else if (p.kind == GEMM_MANY) e = DYN_GATED(DYN_BIG_BN, DYN_BIG_MT, DYN_BIG_NS, 4);
         else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
