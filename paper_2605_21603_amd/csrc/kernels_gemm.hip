@@ -380,9 +380,9 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
         // Without planes because the n tiles alone fill the chip (gate/up): one tall tile up to 384
         // rows (at 264..320 rows 134-137 us with three 128-row tiles, 108-111 us with one of 384),
         // then the 256 x 256 tile where it applies (400..440 rows: 140-144 us -> 120; a 512-row tall
-        // tile 128).  Without planes because the depth is too short to split: as measured before.
+        // tile took 128).  Without planes because the depth is too short to split: as measured before.
         if (N / 128 < 192) return rows > 320 && rows <= 384 ? 384 : 0;
-        return rows <= 384 ? 384 : (rows < 448 && !gemm_wide_tiles(rows, N)) ? 512 : 0;
+        return rows <= 384 ? 384 : 0;
     }
     if (rows <= 384) return 384;
     if (rows <= 512) return 512;
@@ -501,7 +501,7 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
         const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
         const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
         const int grid = ((N2 / p.bn + 7) / 8) * 8 * ((max_rows + mt - 1) / mt);
-        if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : p.mt == 384 ? DYN_GATED(128, 384, 2, 8) : DYN_GATED(128, 512, 2, 8);
+        if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);
         else if (p.kind == GEMM_WIDE) e = DYN_GATED(256, 256, 2, 8);
         else if (p.kind == GEMM_MANY) e = DYN_GATED(DYN_BIG_BN, DYN_BIG_MT, DYN_BIG_NS, 4);
         else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);

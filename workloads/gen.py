@@ -118,6 +118,9 @@ def config(name: str) -> Workload:
         ctx = _uniform_ctx(0, 256, 1024, 8192)
         sh = dataclasses.replace(LLAMA3_8B, n_layers=32)
         return Workload("c5", sh, tuple((1, c) for c in ctx), 0, (0, 128, 256))
+    if name == "d300":          # full layer shape at 300 rows: the 384-row projection tile next to 256-row tiles when split
+        ctx = _uniform_ctx(20, 300, 1, 300)
+        return Workload("d300", LLAMA3_8B, tuple((1, c) for c in ctx), 20, (0, 150, 300))
     if name == "c2_small":
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
         ctx = _uniform_ctx(1, 13, 1, 700)
