@@ -91,11 +91,15 @@ OpCost estimate(const dyn_scheduler *s, const int32_t *ctx_len, int r0, int r1) 
     const double H = g.hidden, D = g.head_dim, NQ = g.n_q_heads, NKV = g.n_kv_heads, I = g.mlp_inter;
     auto gemm = [&](double n, double k, double helper_launches) {
         const double bytes = n * k * e + T * (n + k) * e;
-        double compute;
+        double compute, tail = 0;
         if (g.dtype == DYN_BF16 && dyn::gemm_supported(1, (int)n, (int)k)) {
             // the launcher's own choice of tile and regime: a launch takes ceil(workgroups / resident)
             // rounds, each as long as one workgroup's tile takes at the rate its regime reaches
             const dyn::GemmPath p = dyn::gemm_path(1, (int)T, (int)n, (int)k);
+            if (p.tail_rows) {   // the wide tiles' last rows as a launch of one round of n / 128 tall or few-row tiles
+                const dyn::GemmPath q = dyn::gemm_path(1, p.tail_rows, (int)n, (int)k);
+                tail = std::max(n * k * e / R.w_stream, 5e-6 + 2.0 * q.bn * q.mt * k / (R.mfma / 256)) + R.launch_us * 1e-6;
+            }
             const double depth = p.folded ? k : k / p.split;
             const double wg_flops = 2.0 * p.bn * p.mt * depth;
             const double rounds = std::ceil((double)p.workgroups / p.resident);
@@ -115,7 +119,7 @@ OpCost estimate(const dyn_scheduler *s, const int32_t *ctx_len, int r0, int r1) 
         } else {
             compute = 2.0 * std::ceil(T / 128) * 128 * n * k / R.mfma;
         }
-        return std::max(bytes / R.w_stream, compute) * 1e6 + R.launch_us * (1 + helper_launches);
+        return (std::max(bytes / R.w_stream, compute) + tail) * 1e6 + R.launch_us * (1 + helper_launches);
     };
     auto elementwise = [&](double bytes) { return bytes / R.elementwise * 1e6 + R.launch_us; };
     // attention: decode sequences stream their K/V once per kv head; multi-token sequences are priced by FLOPs

@@ -422,7 +422,12 @@ GemmPath gemm_path(int dtype, int rows, int N, int K) {
         p.folded = S > 1;
         if (S == 1 && gemm_wide_tiles(rows, N)) {
             p.kind = GEMM_WIDE; p.bn = 256; p.mt = 256;
-            p.workgroups = (N / 256) * ((rows + 255) / 256);
+            // 256 tiles run at a time.  When the last m tile alone costs a further round of them,
+            // its rows go to a launch of their own on 128-row-wide tiles (one round of N / 128
+            // workgroups, shorter than a round here): 520..768 rows of gate/up 208-223 us -> ~180.
+            const int m = (rows + 255) / 256, per_m = N / 256;
+            if (m >= 3 && (per_m * m + 255) / 256 > (per_m * (m - 1) + 255) / 256) p.tail_rows = rows - 256 * (m - 1);
+            p.workgroups = per_m * (p.tail_rows ? m - 1 : m);
             p.resident = 256;
             return p;
         }
@@ -462,6 +467,13 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         return e0;
     }
     const GemmPath p = gemm_path(dtype, rows, N, K);
+    if (p.tail_rows) {         // wide tiles only (no planes): the last rows in a launch of their own
+        const int head = rows - p.tail_rows;
+        hipError_t et = launch_gemm(dtype, (const bf16_t *)X + (size_t)head * ldx, ldx, W, R ? (const bf16_t *)R + (size_t)head * N : nullptr,
+                                    (bf16_t *)Y + (size_t)head * N, partial, plane_stride, p.tail_rows, N, K, s, nullptr);
+        if (et != hipSuccess) return et;
+        rows = head;
+    }
     const int S = p.split, m_tiles = (rows + p.mt - 1) / p.mt;
     // workgroup ids are dealt to the 8 XCDs in turn: (n tile, plane) pairs are padded to a multiple of 8
     const int grid = (((N / p.bn) * (p.folded ? 1 : S) + 7) / 8) * 8 * m_tiles;
@@ -499,6 +511,13 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
         e = MT == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
     } else {
         const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
+        if (p.tail_rows) {     // the last rows in a launch of their own (never a wide one: at most 256 rows)
+            const int head = max_rows - p.tail_rows;
+            e = launch_gemm_gated((const bf16_t *)X + (size_t)head * ldx, ldx, W, (bf16_t *)Y + (size_t)head * ldy, ldy, gr,
+                                  p.tail_rows, N2, K, s, nullptr);
+            if (e != hipSuccess) return e;
+            max_rows = head;
+        }
         const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
         const int grid = ((N2 / p.bn + 7) / 8) * 8 * ((max_rows + mt - 1) / mt);
         if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);

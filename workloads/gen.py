@@ -121,6 +121,9 @@ def config(name: str) -> Workload:
     if name == "d300":          # full layer shape at 300 rows: the 384-row projection tile next to 256-row tiles when split
         ctx = _uniform_ctx(20, 300, 1, 300)
         return Workload("d300", LLAMA3_8B, tuple((1, c) for c in ctx), 20, (0, 150, 300))
+    if name == "d600":          # 600 rows of the full layer shape: two 256 x 256 m tiles and the last 88 rows in a launch of their own
+        ctx = _uniform_ctx(21, 600, 1, 200)
+        return Workload("d600", LLAMA3_8B, tuple((1, c) for c in ctx), 21, (0, 300, 600))
     if name == "c2_small":
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
         ctx = _uniform_ctx(1, 13, 1, 700)
