@@ -96,9 +96,11 @@ OpCost estimate(const dyn_scheduler *s, const int32_t *ctx_len, int r0, int r1) 
             // the launcher's own choice of tile and regime: a launch takes ceil(workgroups / resident)
             // rounds, each as long as one workgroup's tile takes at the rate its regime reaches
             const dyn::GemmPath p = dyn::gemm_path(1, (int)T, (int)n, (int)k);
-            if (p.tail_rows) {   // the wide tiles' last rows as a launch of one round of n / 128 tall or few-row tiles
+            if (p.tail_rows) {   // the last rows as a launch of their own: at most 256 rows, tall or few-row tiles
                 const dyn::GemmPath q = dyn::gemm_path(1, p.tail_rows, (int)n, (int)k);
-                tail = std::max(n * k * e / R.w_stream, 5e-6 + 2.0 * q.bn * q.mt * k / (R.mfma / 256)) + R.launch_us * 1e-6;
+                const double q_rounds = std::ceil((double)q.workgroups / q.resident);
+                tail = std::max(n * k * e / R.w_stream, q_rounds * (5e-6 + 2.0 * q.bn * q.mt * (k / q.split) / (R.mfma / 256))) +
+                       (q.split > 1 ? q.split * p.tail_rows * n * 4 / 5e12 : 0) + R.launch_us * 1e-6 * (q.split > 1 ? 2 : 1);
             }
             const double depth = p.folded ? k : k / p.split;
             const double wg_flops = 2.0 * p.bn * p.mt * depth;

@@ -49,7 +49,8 @@ struct GemmPath {
     bool folded;       // planes accumulated one after another in registers: no plane buffer, no reduce kernel
     int workgroups;    // tiles x planes spread over the grid
     int resident;      // workgroups the chip's 256 CUs hold at a time
-    int tail_rows;     // GEMM_WIDE: this many last rows run as a launch of their own (its path: gemm_path of that many rows)
+    int tail_rows;     // this many last rows run as a launch of their own (its path: gemm_path of that many rows);
+                       // workgroups counts the first launch only
 };
 GemmPath gemm_path(int dtype, int rows, int N, int K);
 // True if launch_gemm on `rows` rows writes split-K planes to `partial` (false: one plane, or planes folded in registers).

@@ -386,7 +386,7 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
     }
     if (rows <= 384) return 384;
     if (rows <= 512) return 512;
-    if (rows > 1024) return 0;
+    if (rows > 1280) return 0;                  // 1025..1280 rows: two 512-row tiles and a launch for the rest (gemm_path)
     // 513..1024 rows with planes.  Folding planes in registers (the many-row path) wins once it is
     // available, unless its tiles fill only one of the two workgroup slots per CU and the plane
     // traffic is small next to the contraction (S / K small: the down projection; 1024 rows: 212 ->
@@ -394,6 +394,7 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
     const bool folded_ok = gemm_many_rows(rows, N);
     const bool half_filled = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) < 512;
     if (folded_ok && !(half_filled && K >= 1400 * S)) return 0;
+    if (rows > 1024) return folded_ok ? 512 : 0;
     return (rows + 383) / 384 <= (rows + 511) / 512 ? 384 : 512;
 }
 
@@ -411,6 +412,10 @@ GemmPath gemm_path(int dtype, int rows, int N, int K) {
         // 90 / 60 us -> 33 / 28 / 79 / 48 us, o and down at 512 rows 61 / 112 -> 45 / 84 us.  Same planes,
         // same k order, so the same bits.  Without planes the 256 x 256 tile takes over at 385 rows.
         p.kind = GEMM_TALL; p.bn = 128; p.mt = tall;
+        // past 1024 rows (the down projection only, see gemm_tall_rows): a third 512-row tile would
+        // be a third round of workgroups for at most 256 rows, so those run as a launch of their own
+        // (1032 / 1280 rows: 209 / 211 us with planes folded in registers, ~170 this way)
+        if (rows > 1024) { p.tail_rows = rows - 1024; rows = 1024; }
         p.workgroups = nt * S * ((rows + tall - 1) / tall);
         p.resident = 256;
         return p;
@@ -467,10 +472,11 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
         return e0;
     }
     const GemmPath p = gemm_path(dtype, rows, N, K);
-    if (p.tail_rows) {         // wide tiles only (no planes): the last rows in a launch of their own
+    if (p.tail_rows) {         // the last rows in a launch of their own (own tiles, own planes and reduce)
         const int head = rows - p.tail_rows;
         hipError_t et = launch_gemm(dtype, (const bf16_t *)X + (size_t)head * ldx, ldx, W, R ? (const bf16_t *)R + (size_t)head * N : nullptr,
-                                    (bf16_t *)Y + (size_t)head * N, partial, plane_stride, p.tail_rows, N, K, s, nullptr);
+                                    (bf16_t *)Y + (size_t)head * N, partial ? partial + (size_t)head * N : nullptr, plane_stride,
+                                    p.tail_rows, N, K, s, nullptr);
         if (et != hipSuccess) return et;
         rows = head;
     }

@@ -33,7 +33,7 @@ def sample_ids(w, n):
     return sorted(ids)
 
 
-@pytest.mark.parametrize("name,n_sample", [("c2", 6), ("c4", 6), ("d300", 6), ("d600", 6)])
+@pytest.mark.parametrize("name,n_sample", [("c2", 6), ("c4", 6), ("d300", 6), ("d600", 6), ("d1100", 6)])
 def test_decode_configs_full_size(name, n_sample):
     say("case %s: generating" % name)
     w = gen.config(name)

@@ -124,6 +124,9 @@ def config(name: str) -> Workload:
     if name == "d600":          # 600 rows of the full layer shape: two 256 x 256 m tiles and the last 88 rows in a launch of their own
         ctx = _uniform_ctx(21, 600, 1, 200)
         return Workload("d600", LLAMA3_8B, tuple((1, c) for c in ctx), 21, (0, 300, 600))
+    if name == "d1100":         # 1100 rows of the full layer shape: down as two 512-row tiles + 76 rows, gate/up as four wide m tiles + 76 rows
+        ctx = _uniform_ctx(22, 1100, 1, 120)
+        return Workload("d1100", LLAMA3_8B, tuple((1, c) for c in ctx), 22, (0, 500, 1100))
     if name == "c2_small":
         sh = LayerShape("bf16", 512, 8, 2, 128, 1536)
         ctx = _uniform_ctx(1, 13, 1, 700)
