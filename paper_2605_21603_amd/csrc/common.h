@@ -45,4 +45,17 @@ __device__ __forceinline__ float wave_max(float v) {
     return v;
 }
 
+// Split-KV chunk size (cached positions per work item) of a query block of a multi-token
+// sequence, from `reach` = the largest key count a token of its aligned position block can
+// attend.  1024 positions, doubled until the block has at most 8 chunks, up to 8192: behind a
+// long cached prefix fixed 1024-position chunks leave one fp32 partial set per 1024 keys and
+// token for the merge to read back.  A function of the block's positions alone, so a token's
+// chunks - and the order its partials are merged in - do not depend on the batch around it.
+__host__ __device__ inline int prefill_chunk_positions(int reach) {
+    int ct = 1024;
+    while (reach > 8 * ct && ct < 8192) ct *= 2;
+    return ct;
+}
+constexpr int kPrefillChunkPagesMax = 8192 / 16;     // in 16-position pages
+
 }  // namespace dyn

@@ -28,14 +28,13 @@ hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, 
 int attn_prefill_block_tokens(const AttnShape &sh);
 hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                                     const int32_t *block_table, const void *k_cache, const void *v_cache, float *part_o,
-                                    float *part_ml, const AttnShape &sh, int32_t *plan, int chunk_pages, long max_items,
-                                    int max_groups, hipStream_t s);
+                                    float *part_ml, const AttnShape &sh, int32_t *plan, long max_items, int max_groups,
+                                    hipStream_t s);
 
 typedef __bf16 bf16x4 __attribute__((ext_vector_type(4)));
 
 constexpr int HD = 128, PS = 16, TILE_PAGES = 2;
 constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of the 256 CUs
-constexpr int kPrefillChunkPages = 64;   // multi-token sequences: chunks of 1024 positions per work item
 
 // Work lists, built on the device from the positions (contexts differ by 8x inside a batch, so
 // a dense token x max_chunks grid would be mostly empty workgroups).  A wave serves a query
@@ -43,12 +42,12 @@ constexpr int kPrefillChunkPages = 64;   // multi-token sequences: chunks of 102
 // positions, all of them against one pass over the keys.  List 0 holds the tokens that are
 // alone in their sequence this step (decode: groups of one, 4 of 16 MFMA columns live), list 1
 // the tokens of multi-token sequences (prefill chunks) in query blocks of up to tg1 tokens, against
-// chunks of ct1 positions.
+// chunks of prefill_chunk_positions() positions (1024 unless the block reaches past 8192 keys).
 // One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
 // (first token row, chunk | tokens << 20) at list[2 + 2 i].
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
                                                          const int32_t *__restrict__ pos_of_token, int rows, int ct,
-                                                         int tg1, int ct1, int32_t *__restrict__ plan0,
+                                                         int tg1, int32_t *__restrict__ plan0,
                                                          int32_t *__restrict__ plan1, int32_t *__restrict__ ct_of_token) {
     // One workgroup of 16 waves walks the rows 1024 at a time.  A sequence's tokens are adjacent
     // rows with consecutive positions, so a token leads its group iff it starts its sequence or
@@ -76,10 +75,10 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
                     else hi = mid - 1;
                 }
                 n_tok = lo;
-                const int ctw = which ? ct1 : ct;
+                const int ctw = which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;
                 nc = (p + n_tok - 1 + ctw) / ctw;            // chunks the group's last token reaches
             }
-            ct_of_token[t] = which ? ct1 : ct;               // the chunk size this token's partials are indexed by
+            ct_of_token[t] = which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;   // the chunk size this token's partials are indexed by
         }
         int v0 = which ? 0 : nc, v1 = which ? nc : 0;        // inclusive wave scans of both lists
 #pragma unroll
@@ -339,12 +338,11 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     // two work lists per dispatch: single-token sequences, multi-token sequences
     int32_t *plan0 = plan, *plan1 = plan + 2 + 2 * (size_t)rows * sh.max_chunks;
     int32_t *ct_of_token = plan + 4 + 4 * (size_t)rows * sh.max_chunks;
-    const int ct1 = kPrefillChunkPages * PS;
     // The lists depend on the rows' sequences and positions only: the first layer of a forward
     // builds them, the others walk them again (plan_ready).
     if (!plan_ready)
         hipLaunchKernelGGL(attn_plan_kernel, dim3(1), dim3(1024), 0, s, seq_of_token, pos_of_token, rows, sh.chunk_pages * PS,
-                           attn_prefill_block_tokens(sh), ct1, plan0, plan1, ct_of_token);
+                           attn_prefill_block_tokens(sh), plan0, plan1, ct_of_token);
     hipError_t e = hipGetLastError();
     if (e == hipSuccess && pre) e = hipEventRecord(pre, s);
     if (e != hipSuccess) return e;
@@ -359,7 +357,7 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
     e = hipGetLastError();
     if (e == hipSuccess && any_multi)
         e = launch_attention_prefill(qkv, seq_of_token, pos_of_token, block_table, k_cache, v_cache, part_o, part_ml, sh,
-                                     plan1, kPrefillChunkPages, max_items, groups, s);
+                                     plan1, max_items, groups, s);
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess) return e;
     return launch_attention_combine(dtype, true, part_o, part_ml, pos_of_token, ct_of_token, out, ld_out, sh, rows, s, plan1 + 1);

@@ -3,8 +3,8 @@
 // Section 2), bf16 caches, head_dim 128, 16-position pages.
 //
 // An 8-wave workgroup serves one query block - up to 8 * 8 tokens of one sequence whose
-// positions fall in one aligned block - against one chunk of up to 1024 cached positions of
-// one kv head.  K and V tiles of 32 positions (two pages, 16 KB) go from global memory
+// positions fall in one aligned block - against one chunk of cached positions (1024, more behind
+// a long prefix: prefill_chunk_positions) of one kv head.  K and V tiles of 32 positions (two pages, 16 KB) go from global memory
 // straight into an LDS ring with direct loads, once per workgroup, and all eight waves read
 // their MFMA operands from there: a key is fetched once per 64 query tokens and q-head
 // group, and the waves hold no K/V staging registers.  A wave owns two sets of 16 columns
@@ -50,8 +50,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
                                                               const bf16_t *__restrict__ k_cache,
                                                               const bf16_t *__restrict__ v_cache,
                                                               float *__restrict__ part_o, float *__restrict__ part_ml,
-                                                              AttnShape sh, const int32_t *__restrict__ plan, int32_t *__restrict__ counter,
-                                                              int chunk_pages) {
+                                                              AttnShape sh, const int32_t *__restrict__ plan, int32_t *__restrict__ counter) {
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     int32_t *pid = reinterpret_cast<int32_t *>(lds + kRing * kTile);      // physical pages of the chunk
     const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -67,7 +66,7 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
     // longest first: the list is in token order, a block's keys grow with its position, so it is
     // walked from the back.  A few hundred claims per launch; which workgroup computes an item
     // does not touch its result.
-    int32_t *claim = reinterpret_cast<int32_t *>(lds + kRing * kTile) + 64;
+    int32_t *claim = reinterpret_cast<int32_t *>(lds + kRing * kTile) + kPrefillChunkPagesMax;
     for (;;) {
         __builtin_amdgcn_s_waitcnt(0x0f70);                               // the previous item's stores and trailing tile loads
         __syncthreads();                                                  // everyone has read the previous claim and left the ring
@@ -81,6 +80,8 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
         const int c = packed & 0xfffff, n_tok = packed >> 20;
         const int n_keys = pos_of_token[t0 + n_tok - 1] + 1;             // keys the block's last token attends
         const int seq_pages = (n_keys + PS - 1) / PS;
+        const int block_tokens = kWaves * kSets * TG;                     // the aligned position block this item's tokens share
+        const int chunk_pages = prefill_chunk_positions((pos_of_token[t0] / block_tokens + 1) * block_tokens) / PS;
         const int lp0 = c * chunk_pages;
         const int n_pg = min(chunk_pages, seq_pages - lp0);
         const int n_tile = (n_pg + kTP - 1) / kTP;
@@ -281,10 +282,10 @@ int attn_prefill_block_tokens(const AttnShape &sh) { return kWaves * kSets * (16
 
 hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token, const int32_t *pos_of_token,
                                     const int32_t *block_table, const void *k_cache, const void *v_cache, float *part_o,
-                                    float *part_ml, const AttnShape &sh, int32_t *plan, int chunk_pages, long max_items,
-                                    int max_groups, hipStream_t s) {
-    if (chunk_pages > 64) return hipErrorInvalidValue;
-    const int lds_bytes = kRing * kTile + (64 + 4) * (int)sizeof(int32_t);   // ring, page ids of a chunk, the claimed item
+                                    float *part_ml, const AttnShape &sh, int32_t *plan, long max_items, int max_groups,
+                                    hipStream_t s) {
+    static_assert(kPrefillChunkPagesMax <= kWaves * 64, "one thread per page id of a chunk");
+    const int lds_bytes = kRing * kTile + (kPrefillChunkPagesMax + 4) * (int)sizeof(int32_t);   // ring, page ids of a chunk, the claimed item
     static bool attr_set = false;
     if (!attr_set) {
         hipError_t e = hipFuncSetAttribute((const void *)attn_prefill_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, lds_bytes);
@@ -294,7 +295,7 @@ hipError_t launch_attention_prefill(const void *qkv, const int32_t *seq_of_token
     const int grid = (int)(max_items < max_groups ? max_items : max_groups);
     hipLaunchKernelGGL(attn_prefill_kernel, dim3(grid), dim3(kWaves * 64), lds_bytes, s, (const bf16_t *)qkv, seq_of_token,
                        pos_of_token, block_table, (const bf16_t *)k_cache, (const bf16_t *)v_cache, part_o, part_ml, sh, plan,
-                       plan + 1, chunk_pages);
+                       plan + 1);
     return hipGetLastError();
 }
 

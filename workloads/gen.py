@@ -155,6 +155,11 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
         seqs = ((200, 2500), (1, 1100), (70, 70), (1, 33), (3, 1027))
         return Workload("pf_long", sh, seqs, 9, (0, 200, 275))
+    if name == "pf_deep":       # prefill chunks behind 8..66 thousand cached positions: split-KV chunks of 2048, 4096 and 8192 positions,
+                                # and a sequence whose blocks straddle the 8192-key step (1024- and 2048-position chunks side by side)
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
+        seqs = ((100, 9000), (1, 8200), (30, 17000), (70, 8230), (3, 66000), (1, 40))
+        return Workload("pf_deep", sh, seqs, 23, (0, 101, 205))
     if name == "pf_g8":         # eight q heads per kv head: two tokens per 16-column set, 32-token query blocks
         sh = LayerShape("bf16", 1024, 8, 1, 128, 1024)
         seqs = ((45, 45), (1, 300), (33, 1090), (1, 1))
