@@ -501,6 +501,23 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     return hipGetLastError();
 }
 
+namespace {
+// Tile of an expert-grouped launch, from the average number of rows per group (the lists' capacity
+// holds every row once).  Few rows per expert stream the weights through 128-row tiles; from about
+// 100 rows a second 128-row tile per expert would move its weights into LDS again, so the tile
+// grows with the rows: one 256-row tall tile up to about 200 rows, 256 x 256 tiles beyond (eight
+// experts' gate/up at 512 / 1024 / 2048 tokens: 593 / 989 / 1847 us with 128-row tiles).  The
+// grid still covers max_rows per group; tiles past a group's count exit at once.
+struct GroupTile { int bn, mt; };
+GroupTile gemm_group_tile(const GemmGroups &gr, int max_rows, int N) {
+    if (max_rows <= 64) return {128, 64};
+    const int avg = gr.cap / (gr.n_groups > 0 ? gr.n_groups : 1);
+    if (avg <= 100 || max_rows <= 128) return {128, 128};
+    if (avg <= 200 || N % 256) return {128, 256};
+    return {256, 256};
+}
+}  // namespace
+
 bool gemm_gated_supported(int dtype, int N2, int K) { return dtype == 1 && gemm_split_k(dtype, N2, K) == 1; }
 
 // act[rows or listed rows, N2/2] = silu(X Wg^T) * (X Wu^T) with W = [gate rows; up rows] ([N2, K]),
@@ -512,9 +529,9 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
 #define DYN_GATED(BN, MT, NS, NW) \
     launch_gemm_bf16<BN, MT, false, NS, true, NW>(grid, s, X, ldx, W, nullptr, Y, nullptr, 0, max_rows, N2, K, 1, gr, ldy)
     if (gr.n_groups) {
-        const int MT = max_rows <= 64 ? 64 : 128;
-        const int grid = ((((N2 / 128) * gr.n_groups) + 7) / 8) * 8 * ((max_rows + MT - 1) / MT);
-        e = MT == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
+        const GroupTile t = gemm_group_tile(gr, max_rows, N2);
+        const int grid = ((((N2 / t.bn) * gr.n_groups) + 7) / 8) * 8 * ((max_rows + t.mt - 1) / t.mt);
+        e = t.bn == 256 ? DYN_GATED(256, 256, 2, 8) : t.mt == 256 ? DYN_GATED(128, 256, 3, 8) : t.mt == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
     } else {
         const GemmPath p = gemm_path(1, max_rows, N2, K);          // split factor 1: no planes on any path
         if (p.tail_rows) {     // the last rows in a launch of their own (never a wide one: at most 256 rows)
@@ -555,13 +572,15 @@ hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W,
         return e0;
     }
     const int S = gemm_split_k(dtype, N, K, gr.n_groups);
-    const int MT = max_rows <= 64 ? 64 : 128;
-    const int m_tiles = (max_rows + MT - 1) / MT;
-    const int ns = (N / 128) * S * gr.n_groups;
+    GroupTile t = gemm_group_tile(gr, max_rows, N);
+    if (S > 1 && t.bn == 256) t = {128, 256};          // the 256 x 256 tile has no planes
+    const int m_tiles = (max_rows + t.mt - 1) / t.mt;
+    const int ns = (N / t.bn) * S * gr.n_groups;
     const int grid = ((ns + 7) / 8) * 8 * m_tiles;
     hipError_t e;
-    if (MT == 64) e = launch_gemm_bf16<128, 64, false, 4, false, 8>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
-    else e = launch_gemm_bf16<128, 128, false, 4, false, 8>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr);
+#define DYN_GROUPED(BN, MT, NS) launch_gemm_bf16<BN, MT, false, NS, false, 8>(grid, s, X, ldx, W, nullptr, Y, partial, plane_stride, max_rows, N, K, S, gr)
+    e = t.bn == 256 ? DYN_GROUPED(256, 256, 2) : t.mt == 256 ? DYN_GROUPED(128, 256, 3) : t.mt == 64 ? DYN_GROUPED(128, 64, 4) : DYN_GROUPED(128, 128, 4);
+#undef DYN_GROUPED
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
     if (e != hipSuccess || S == 1 || gr.force_planes) return e;
     // output rows row0 .. row0 + n_rows - 1 are exactly the rows the groups wrote

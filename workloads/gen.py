@@ -196,6 +196,15 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 256, 2, 1, 256, 128, n_experts=16, top_k=4, page_size=64)
         seqs = ((1, 65), (17, 17), (1, 300), (5, 130), (1, 1), (1, 64))
         return Workload("bf16_max", sh, seqs, 16, (0, 18, 26))
+    if name == "moe_mid":       # about 150 rows per expert: one 256-row tile per expert and n tile
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024, n_experts=4, top_k=2)
+        return Workload("moe_mid", sh, tuple((1, c) for c in _uniform_ctx(24, 300, 1, 60)), 24, (0, 140, 300))
+    if name == "moe_many_a":    # about 350 rows per expert: 256 x 256 tiles for the gated gate/up, planes for down
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024, n_experts=4, top_k=2)
+        return Workload("moe_many_a", sh, tuple((1, c) for c in _uniform_ctx(25, 700, 1, 40)), 25, (0, 300, 700))
+    if name == "moe_many_b":    # the other way round: gate/up with planes (not gated), 256 x 256 tiles for down
+        sh = LayerShape("bf16", 1024, 8, 2, 128, 512, n_experts=4, top_k=2)
+        return Workload("moe_many_b", sh, tuple((1, c) for c in _uniform_ctx(26, 700, 1, 40)), 26, (0, 300, 700))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
