@@ -77,6 +77,75 @@ __global__ __launch_bounds__(64) void attn_generic_kernel(const T *__restrict__ 
 // head-dim indices.  Partials are merged in chunk order: M = max m_c,
 // out = sum_c e(m_c - M) o_c / sum_c e(m_c - M) l_c, where e is exp or exp2 according to the
 // domain the producing kernel kept m in.
+// A token with more than kMergeSegment chunks (contexts beyond 16384 positions in decode) is
+// merged in two levels: first every segment of kMergeSegment chunks into one partial of the same
+// (m, l, o) form, stored over the segment's first chunk, then the segments.  Which way a token goes
+// depends on its own chunk count only, so its bits do not depend on the batch; the one-level merge
+// of a 131072-position context was a 512-step chain on 32 lanes (126 us for one token).
+constexpr int kMergeSegment = 64;
+
+template <bool BASE2>
+__global__ __launch_bounds__(256) void attn_combine_segments_kernel(float *__restrict__ part_o, float *__restrict__ part_ml,
+                                                                    const int32_t *__restrict__ pos_of_token,
+                                                                    const int32_t *__restrict__ ct_of_token, AttnShape sh,
+                                                                    int n_pairs, int max_segments) {
+    const int unit = blockIdx.x * 8 + (threadIdx.x >> 5), sub = threadIdx.x & 31;
+    const int pair = unit / max_segments, seg = unit % max_segments;
+    if (pair >= n_pairs) return;
+    const int t = pair / sh.n_q;
+    const int d = sh.head_dim, ct = ct_of_token ? ct_of_token[t] : sh.chunk_pages * sh.page_size;
+    const int n_chunks = (pos_of_token[t] + ct) / ct;
+    const int c0 = seg * kMergeSegment;
+    if (n_chunks <= kMergeSegment || c0 >= n_chunks) return;
+    const int n = min(kMergeSegment, n_chunks - c0);
+    float *ml = part_ml + ((size_t)pair * sh.max_chunks + c0) * 2;
+    float *po = part_o + ((size_t)pair * sh.max_chunks + c0) * d;
+    float M = -INFINITY;
+    for (int c = sub; c < n; c += 32) M = fmaxf(M, ml[c * 2]);
+#pragma unroll
+    for (int off = 16; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 32));
+    float L = 0.f;
+    f32x4 acc[2] = {f32x4{0.f, 0.f, 0.f, 0.f}, f32x4{0.f, 0.f, 0.f, 0.f}};
+    for (int cb = 0; cb < n; cb += 32) {
+        const int c = cb + sub;
+        float wgt = 0.f, wl = 0.f;
+        if (c < n) {
+            const float dm = ml[c * 2] - M;
+            wgt = BASE2 ? exp2f(dm) : expf(dm);
+            wl = wgt * ml[c * 2 + 1];
+        }
+#pragma unroll
+        for (int off = 16; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 32);
+        L += wl;
+        const int nb = min(32, n - cb);
+        for (int j0 = 0; j0 < nb; j0 += 4) {
+            f32x4 v[4][2];
+#pragma unroll
+            for (int j = 0; j < 4; ++j)
+#pragma unroll
+                for (int q = 0; q < 2; ++q) {
+                    const int i = sub * 4 + q * 128;
+                    v[j][q] = (j0 + j < nb && i < d) ? *reinterpret_cast<const f32x4 *>(po + (size_t)(cb + j0 + j) * d + i)
+                                                      : f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+#pragma unroll
+            for (int j = 0; j < 4; ++j) {
+                const float wj = __shfl(wgt, j0 + j, 32);
+#pragma unroll
+                for (int q = 0; q < 2; ++q) acc[q] += v[j][q] * wj;
+            }
+        }
+    }
+    // every lane has read what it needs of the segment (its own four columns of each chunk, and
+    // lane 0 the first chunk's (m, l)): the merged partial replaces the segment's first chunk
+#pragma unroll
+    for (int q = 0; q < 2; ++q) {
+        const int i = sub * 4 + q * 128;
+        if (i < d) *reinterpret_cast<f32x4 *>(po + i) = acc[q];
+    }
+    if (sub == 0) { ml[0] = M; ml[1] = L; }
+}
+
 template <typename T, bool BASE2>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml,
@@ -91,11 +160,14 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     if (pair >= n_pairs) return;
     const int t = pair / sh.n_q;
     const int d = sh.head_dim, ct = ct_of_token ? ct_of_token[t] : sh.chunk_pages * sh.page_size;   // per-token chunk size if given
-    const int n_chunks = (pos_of_token[t] + ct) / ct;     // ceil((pos + 1) / ct)
+    const int all_chunks = (pos_of_token[t] + ct) / ct;     // ceil((pos + 1) / ct)
+    // beyond kMergeSegment chunks the segments kernel has merged every segment into its first chunk
+    const int step = all_chunks > kMergeSegment ? kMergeSegment : 1;
+    const int n_chunks = (all_chunks + step - 1) / step;
     const float *ml = part_ml + (size_t)pair * sh.max_chunks * 2;
     const float *po = part_o + (size_t)pair * sh.max_chunks * d;
     float M = -INFINITY;
-    for (int c = sub; c < n_chunks; c += 32) M = fmaxf(M, ml[c * 2]);
+    for (int c = sub; c < n_chunks; c += 32) M = fmaxf(M, ml[c * step * 2]);
 #pragma unroll
     for (int off = 16; off >= 1; off >>= 1) M = fmaxf(M, __shfl_xor(M, off, 32));
     // Lane `sub` weighs chunk cb + sub; the weights travel by shuffle so that the value loads
@@ -106,9 +178,9 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         const int c = cb + sub;
         float wgt = 0.f, wl = 0.f;
         if (c < n_chunks) {
-            const float dm = ml[c * 2] - M;
+            const float dm = ml[c * step * 2] - M;
             wgt = BASE2 ? exp2f(dm) : expf(dm);
-            wl = wgt * ml[c * 2 + 1];
+            wl = wgt * ml[c * step * 2 + 1];
         }
 #pragma unroll
         for (int off = 16; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 32);
@@ -121,7 +193,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int i = sub * 4 + q * 128;
-                    v[j][q] = (j0 + j < nb && i < d) ? *reinterpret_cast<const f32x4 *>(po + (size_t)(cb + j0 + j) * d + i)
+                    v[j][q] = (j0 + j < nb && i < d) ? *reinterpret_cast<const f32x4 *>(po + (size_t)(cb + j0 + j) * step * d + i)
                                                       : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
@@ -151,11 +223,19 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
     }
 }
 
-hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
+hipError_t launch_attention_combine(int dtype, bool base2, float *part_o, float *part_ml,
                                     const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
                                     const AttnShape &sh, int rows, hipStream_t s, int32_t *counter_reset) {
     const int n_pairs = rows * sh.n_q;
     const dim3 grid((n_pairs + 7) / 8), block(256);
+    if (sh.max_chunks > kMergeSegment) {       // some token may have that many chunks: first level of the merge
+        const int max_segments = (sh.max_chunks + kMergeSegment - 1) / kMergeSegment;
+        const dim3 seg_grid((unsigned)(((size_t)n_pairs * max_segments + 7) / 8));
+        if (base2) hipLaunchKernelGGL(attn_combine_segments_kernel<true>, seg_grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, sh, n_pairs, max_segments);
+        else hipLaunchKernelGGL(attn_combine_segments_kernel<false>, seg_grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, sh, n_pairs, max_segments);
+        hipError_t e = hipGetLastError();
+        if (e != hipSuccess) return e;
+    }
     if (dtype == 0) {
         if (base2) hipLaunchKernelGGL((attn_combine_kernel<float, true>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs, counter_reset);
         else hipLaunchKernelGGL((attn_combine_kernel<float, false>), grid, block, 0, s, part_o, part_ml, pos_of_token, ct_of_token, (float *)out, ld_out, sh, n_pairs, counter_reset);

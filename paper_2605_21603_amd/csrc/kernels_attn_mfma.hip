@@ -22,7 +22,7 @@
 
 namespace dyn {
 
-hipError_t launch_attention_combine(int dtype, bool base2, const float *part_o, const float *part_ml,
+hipError_t launch_attention_combine(int dtype, bool base2, float *part_o, float *part_ml,
                                     const int32_t *pos_of_token, const int32_t *ct_of_token, void *out, int ld_out,
                                     const AttnShape &sh, int rows, hipStream_t s, int32_t *counter_reset);
 int attn_prefill_block_tokens(const AttnShape &sh);

@@ -160,6 +160,10 @@ def config(name: str) -> Workload:
         sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
         seqs = ((100, 9000), (1, 8200), (30, 17000), (70, 8230), (3, 66000), (1, 40))
         return Workload("pf_deep", sh, seqs, 23, (0, 101, 205))
+    if name == "dec_deep":      # decodes behind 16 to 70 thousand cached positions: 64, 65, 79 and 274 split-KV chunks (two-level merge above 64)
+        sh = LayerShape("bf16", 512, 8, 2, 128, 1024)
+        seqs = ((1, 20000), (1, 70000), (1, 16384), (1, 16385), (1, 300), (5, 130))
+        return Workload("dec_deep", sh, seqs, 27, (0, 2, 10))
     if name == "pf_g8":         # eight q heads per kv head: two tokens per 16-column set, 32-token query blocks
         sh = LayerShape("bf16", 1024, 8, 1, 128, 1024)
         seqs = ((45, 45), (1, 300), (33, 1090), (1, 1))
