@@ -1,19 +1,23 @@
 """Benchmark of the decoder-layer forward step on one MI355X.
 
-    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c2]
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload c5]
 
-A step is one pass of the whole layer (norms, projections, rotary + cache append, paged
-attention, gated MLP) over one batch of seeded synthetic input that is resident in HBM
-before the timed region.  The default workload is the Llama-3-8B-shaped decode layer at
-batch 128 with contexts uniform in [512, 4096].  The step is timed under the sequential
-schedule and under overlapped two-micro-batch schedules; `value` is the tokens/s of the
-fastest of them (the method falls back to the sequential order when splitting does not pay),
-`config.schedule` names it, and the sequential and best overlapped figures are reported
-beside it.  Prints one JSON line.
+A step is one pass of the whole hot path (per layer: norms, projections, rotary + cache
+append, paged attention, gated MLP) over one batch of seeded synthetic input that is resident
+in HBM before the timed region.  The default workload is the largest configuration one GPU
+holds: the 32-layer Llama-3-8B-shaped decode step at batch 256 with contexts uniform in
+[1024, 8192] (c5), replayed as HIP graphs; c2, c3 and c4 are the single-layer workloads.  The
+step is timed under the sequential schedule and under overlapped micro-batch schedules, every
+step between two events on the stream the forward is called on; `value` is tokens / median
+step time of the fastest schedule (the method falls back to the sequential order when
+splitting does not pay), `config.schedule` names it, and per schedule the median, minimum,
+maximum and the wall-clock mean over the K steps are reported beside it.  Prints one JSON line.
 """
 import argparse
+import hashlib
 import json
 import os
+import statistics
 import sys
 import time
 
@@ -26,13 +30,21 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 
 # HBM bytes per launch of the attention kernel, read with rocprofv3 counters (FETCH_SIZE and
 # WRITE_SIZE in runs of their own, scaled by a 1 GiB copy probe).  Counters cannot be read
-# from inside this process, so the figure of the committed counter summary is repeated here.
+# from inside this process, so the figure of the committed counter summary is repeated here,
+# together with the hash of the kernel's source it was measured on: if the source has changed
+# since, the figure is withheld (traffic = null) instead of going stale silently.
+ATTN_SOURCE = os.path.join(ROOT, "paper_2605_21603_amd", "csrc", "kernels_attn_mfma.hip")
 ROCPROF_TRAFFIC = {
-    "c2": {"bytes": 1274151526 + 21834035,
+    "c2": {"bytes": 1274151526 + 21834035, "source_sha256_16": "178a3104454bc3b6",
            "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 622,144 x 2.0 KiB + WRITE_SIZE 21,322 KiB)"},
-    "c5": {"bytes": 5060041114 + 86052864,
+    "c5": {"bytes": 5060041114 + 86052864, "source_sha256_16": "178a3104454bc3b6",
            "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,470,723 x 2.0 KiB + WRITE_SIZE 84,036 KiB)"},
 }
+
+
+def source_hash(path):
+    with open(path, "rb") as f:
+        return hashlib.sha256(f.read()).hexdigest()[:16]
 
 
 def log(msg):
@@ -66,17 +78,43 @@ def candidate_schedules(B, w, use_graph):
 
 
 def time_schedule(layer, step, sched, stream, steps, warmup):
+    """W untimed forwards, then K forwards issued back to back, each between two events recorded
+    on the stream the forward is called on (the end event of one step is the start event of the
+    next), the whole loop between two device synchronisations.  Per-step times in ms."""
     import torch
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(steps + 1)]
     with torch.cuda.stream(stream):
         for _ in range(warmup):
             layer.forward(step.batch, sched, stream)
         torch.cuda.synchronize()
         t0 = time.perf_counter()
-        for _ in range(steps):
+        evs[0].record(stream)
+        for i in range(steps):
             layer.forward(step.batch, sched, stream)
+            evs[i + 1].record(stream)
         torch.cuda.synchronize()
         t1 = time.perf_counter()
-    return (t1 - t0) * 1e3 / steps
+    per = [evs[i].elapsed_time(evs[i + 1]) for i in range(steps)]
+    return {"median_ms": statistics.median(per), "min_ms": min(per), "max_ms": max(per), "mean_ms": sum(per) / steps,
+            "wall_mean_ms": (t1 - t0) * 1e3 / steps, "slowest_step": per.index(max(per))}
+
+
+def measure_stream_read(B, buf, stream, reps=7):
+    """GB/s of the library's read-only streaming kernel over up to 2 GiB of a resident buffer."""
+    import torch
+    nbytes = min(buf.numel() * buf.element_size(), 2 << 30) & ~15
+    sink = torch.empty(8192, dtype=torch.int32, device=buf.device)
+    evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+    with torch.cuda.stream(stream):
+        B.probe_hbm_read(buf, nbytes, sink, stream)
+        evs[0].record(stream)
+        for i in range(reps):
+            B.probe_hbm_read(buf, nbytes, sink, stream)
+            evs[i + 1].record(stream)
+    torch.cuda.synchronize()
+    ms = statistics.median(evs[i].elapsed_time(evs[i + 1]) for i in range(reps))
+    return {"GB/s": nbytes / 1e9 / (ms * 1e-3), "bytes": nbytes, "median_ms": ms,
+            "kernel": "stream_read_kernel (16-byte loads, read only, 2048 x 256 threads, grid-strided)"}
 
 
 def attention_bytes(w):
@@ -171,8 +209,8 @@ def policy_sweep(args):
                     if r:
                         sch.execute([(r[0], b)], stream=b)
             split = sch.finish(use_graph=True)
-            t_seq = time_schedule(layer, step, B.sequential(use_graph=True), stream, args.steps, args.warmup)
-            t_split = time_schedule(layer, step, split, stream, args.steps, args.warmup)
+            t_seq = time_schedule(layer, step, B.sequential(use_graph=True), stream, args.steps, args.warmup)["median_ms"]
+            t_split = time_schedule(layer, step, split, stream, args.steps, args.warmup)["median_ms"]
             rows.append({"prefill_tokens": P, "decodes": D, "decode_ctx": Cx, "sequential_us": t_seq * 1e3,
                          "split_us": t_split * 1e3, "est_sequential_us": choice["est_sequential_us"],
                          "est_split_us": choice["est_split_us"], "policy_split": choice["split"],
@@ -233,9 +271,9 @@ def trace_overlap(db_path):
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--steps", type=int, default=100)
     ap.add_argument("--warmup", type=int, default=20)
-    ap.add_argument("--workload", default="c2")
+    ap.add_argument("--workload", default="c5", help="c5 (default: the largest configuration), c2, c3, c4")
     ap.add_argument("--no-graph", action="store_true", help="eager launches instead of HIP-graph replay")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--schedules", default="all",
@@ -287,16 +325,22 @@ def main():
     stream = torch.cuda.Stream()
     use_graph = not args.no_graph
 
-    results = {}
+    stats = {}
     seq = B.sequential(use_graph=use_graph)
-    results["sequential"] = time_schedule(layer, step, seq, stream, args.steps, args.warmup)
-    log("sequential: %.1f us/step" % (results["sequential"] * 1e3))
     cands = candidate_schedules(B, w, use_graph)
     if args.schedules != "all":
         cands = {k: v for k, v in cands.items() if k in args.schedules.split(",")}
+    for sched in cands.values():            # side streams (CU-masked ones synchronise the device) exist before anything is timed
+        layer.prepare(sched)
+    stats["sequential"] = time_schedule(layer, step, seq, stream, args.steps, args.warmup)
     for name, sched in cands.items():
-        results[name] = time_schedule(layer, step, sched, stream, args.steps, args.warmup)
-        log("%s: %.1f us/step" % (name, results[name] * 1e3))
+        stats[name] = time_schedule(layer, step, sched, stream, args.steps, args.warmup)
+    for name, r in stats.items():
+        log("%s: median %.1f us/step (min %.1f, max %.1f at step %d, wall mean %.1f)"
+            % (name, r["median_ms"] * 1e3, r["min_ms"] * 1e3, r["max_ms"] * 1e3, r["slowest_step"], r["wall_mean_ms"] * 1e3))
+    results = {k: r["median_ms"] for k, r in stats.items()}
+    stream_read = measure_stream_read(B, step.k_cache, stream)
+    log("streaming read of resident cache: %.0f GB/s" % stream_read["GB/s"])
     # the library's measured tuner: unequal micro-batch sizes, forms, staggers, CU shares
     md = gen.metadata(w)
     tuned = None
@@ -314,7 +358,8 @@ def main():
         log("tuner: chose %s; fastest overlapped candidate %s; sequential %.1f us" % (t_res["best"], t_fastest,
                                                                                       t_res["us_sequential"]))
         if t_res["best"]["form"] != "sequential":
-            results["tuned"] = time_schedule(layer, step, t_sched, stream, args.steps, args.warmup)
+            stats["tuned"] = time_schedule(layer, step, t_sched, stream, args.steps, args.warmup)
+            results["tuned"] = stats["tuned"]["median_ms"]
             log("tuned: %.1f us/step" % (results["tuned"] * 1e3))
     # what the library's own policy would run for this batch, and its cost estimates
     _, policy = B.Scheduler(B.make_config(w.shape), md["q_start"]).auto(md["ctx_len"], use_graph=use_graph)
@@ -327,7 +372,8 @@ def main():
     eager = B.sequential(use_graph=False)
     attn_ms, gu_ms, op_ms = [], [], {}
     with torch.cuda.stream(stream):
-        for i in range(0 if args.no_event_profile else args.steps + 5):
+        n_prof = min(args.steps, 20 if w.shape.n_layers > 1 else 200)
+        for i in range(0 if args.no_event_profile else n_prof + 5):
             layer.forward(step.batch, eager, stream)
             torch.cuda.synchronize()
             if i < 5:
@@ -362,13 +408,18 @@ def main():
                         "avg_launch_ms": gu_avg_ms}
 
     traffic = ROCPROF_TRAFFIC.get(w.name)
+    if traffic and traffic["source_sha256_16"] != source_hash(ATTN_SOURCE):
+        log("the attention kernel's source changed since its counters were read: traffic withheld")
+        traffic = None
     byts, flops = layer_bytes_flops(w)
     t_roof_ms = max(byts / (HBM_PEAK_GBS * 1e9), flops / (MFMA_BF16_PEAK_TFLOPS * 1e12)) * 1e3
     T = w.n_tokens
     out = {
         "metric": "layer-forward tokens/s on 1 MI355X (overlapped vs sequential); % of roofline",
         "value": T / (results[best] * 1e-3), "unit": "tokens/s", "n_gpus": 1, "steps": args.steps,
-        "warmup": args.warmup, "ms_per_step": results[best], "higher_is_better": True, "scaling": "weak",
+        "warmup": args.warmup, "ms_per_step": results[best], "timing": "median of per-step HIP-event times on the origin stream",
+        "ms_per_step_min": stats[best]["min_ms"], "ms_per_step_max": stats[best]["max_ms"],
+        "ms_per_step_wall_mean": stats[best]["wall_mean_ms"], "higher_is_better": True, "scaling": "weak",
         "vs_baseline": None, "dtype": w.shape.dtype, "data": "synthetic",
         "config": {"workload": "%s: %d-layer decoder forward, %d tokens / %d sequences, hidden %d, heads %d/%d x %d, "
                                "mlp %d, page %d" % (w.name, w.shape.n_layers, T, w.n_seqs, w.shape.hidden, w.shape.n_q,
@@ -380,6 +431,8 @@ def main():
         "best_overlapped_ms_per_step": results[best_ovl],
         "overlap_speedup": results["sequential"] / results[best_ovl],
         "schedules_ms": results,
+        "schedules_stats_ms": stats,
+        "hbm": {"peak_GB/s": HBM_PEAK_GBS, "measured_stream_read": stream_read},
         "tuned": tuned,
         "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",
                    "est_sequential_ms_per_layer": policy["est_sequential_us"] * 1e-3,
@@ -392,7 +445,7 @@ def main():
     }
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample ...")
-        out["cpu_baseline"] = cpu_baseline(w, data, 128 if w.shape.n_layers == 1 else 6)
+        out["cpu_baseline"] = cpu_baseline(w, data, 128 if w.shape.n_layers == 1 else 16)
     print(json.dumps(out), flush=True)
 
 

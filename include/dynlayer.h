@@ -146,12 +146,30 @@ size_t dyn_layer_workspace_bytes(const dyn_layer *layer, int max_tokens, int max
  * Section 3.2.2); stream / partition ids in range.  batch->workspace may be NULL here. */
 dyn_status dyn_schedule_validate(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched);
 
+/* Creates ahead of time the GPU state a schedule's forwards need: its side streams.  A
+ * CU-masked stream (partition >= 1) is a hardware queue that is only ever created while the
+ * device is idle, so this call SYNCHRONISES THE DEVICE whenever it has to create one; masked
+ * streams are shared by all handles of the process, keyed by (stream id, mask), and live
+ * until the process ends.  Section 2.1 ("Overlapping") names partitioned contexts as the
+ * second way to overlap beside plain streams; this is their set-up step.  Optional: a
+ * forward creates what is missing itself (see below).  sched may be NULL or sequential
+ * (nothing to create). */
+dyn_status dyn_layer_prepare(dyn_layer *layer, const dyn_schedule *sched);
+
 /* Runs all layers.  Asynchronous: work is forked from hip_stream (a hipStream_t, not the
  * null stream when use_graph is set) and joined back to it; the host does not wait and
- * nothing is allocated on the device.  Cross-stream dependencies are inserted by the
+ * nothing is allocated on the device.  One exception to "the host does not wait": the first
+ * forward that names a (stream id, CU mask) pair no earlier forward or dyn_layer_prepare
+ * call of the process has used creates that masked stream, which synchronises the device
+ * once (and would invalidate a stream capture the caller has open on hip_stream): call
+ * dyn_layer_prepare with the schedule beforehand to keep every forward asynchronous.
+ * Cross-stream dependencies are inserted by the
  * library (the backend, not the scheduler author, owns data flow; Section 3.2.2).
  * Output rows land at their global row index whatever the split (zero-copy merge,
- * Section 3.3.1).  Any legal schedule gives bit-identical y and cache contents. */
+ * Section 3.3.1).  Any legal schedule gives bit-identical y and cache contents.
+ * With use_graph the captured step is cached and replayed while the batch's pointers,
+ * sizes, q_start_host contents, cut points and slots stay the same; the contents of device
+ * arrays (positions, block table, activations, caches) may change between replays. */
 dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, void *hip_stream);
 
 /* Profiling (eager schedules only): when on, every dispatch is bracketed by events on its
@@ -338,6 +356,16 @@ dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_
 dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const int32_t *ctx_len_host, const dyn_tune_options *opt,
                     void *hip_stream, dyn_scheduler *s, dyn_schedule *out, dyn_tune_result *result,
                     dyn_tune_candidate *table, int capacity);
+
+/* ---- Measurement aid -----------------------------------------------------------------
+ *
+ * The layer's dominant operators are bound by HBM bandwidth (the memory-bound operator class
+ * of Section 2), and a fraction of the datasheet peak says little without the rate the memory
+ * system actually delivers.  This launches one read-only kernel that loads every 16-byte word
+ * of buf[0 .. bytes) once (DEVICE pointer, 16-byte aligned, bytes a multiple of 16) and folds
+ * them into sink (DEVICE, at least 32768 bytes, overwritten).  Asynchronous on hip_stream; the
+ * caller times it with events.  Allocates nothing. */
+dyn_status dyn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *hip_stream);
 
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *dyn_last_error(void);

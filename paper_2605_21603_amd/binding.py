@@ -94,10 +94,10 @@ class dyn_slot_time(C.Structure):
 
 
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
-           "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
+           "dyn_layer_prepare", "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
-           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory"]
+           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_probe_hbm_read"]
 
 _lib = None
 
@@ -117,6 +117,8 @@ def lib() -> C.CDLL:
         l.dyn_layer_destroy.restype = None
         l.dyn_schedule_validate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_layer_prepare.argtypes = [C.c_void_p, C.c_void_p]
+        l.dyn_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
         l.dyn_layer_get_slot_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_scheduler_create.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -377,6 +379,11 @@ class DynLayer:
         _check(lib().dyn_schedule_memory(self.handle, C.addressof(batch), C.addressof(sc), C.byref(rep)))
         return rep.as_dict()
 
+    def prepare(self, sched: Schedule) -> None:
+        """Creates the schedule's side streams now (synchronises the device for CU-masked ones)."""
+        sc = sched.to_c()
+        _check(lib().dyn_layer_prepare(self.handle, C.addressof(sc)))
+
     def forward(self, batch: dyn_batch, sched: Schedule, stream: Optional[torch.cuda.Stream] = None) -> None:
         sc = sched.to_c()
         s = stream if stream is not None else torch.cuda.current_stream()
@@ -393,6 +400,12 @@ class DynLayer:
         return [dict(layer=a.layer, op=a.op, nano=a.nano, n_nano=a.n_nano, stream=a.stream, partition=a.partition,
                      start_ms=a.start_ms, main_start_ms=a.main_start_ms, main_stop_ms=a.main_stop_ms,
                      stop_ms=a.stop_ms) for a in arr[:n.value]]
+
+
+def probe_hbm_read(buf: torch.Tensor, nbytes: int, sink: torch.Tensor, stream: torch.cuda.Stream) -> None:
+    """One launch of the library's read-only streaming kernel over the first nbytes of buf."""
+    assert sink.numel() * sink.element_size() >= 32768
+    _check(lib().dyn_probe_hbm_read(_ptr(buf), nbytes, _ptr(sink), C.c_void_p(stream.cuda_stream)))
 
 
 def make_config(sh) -> dyn_layer_config:

@@ -69,7 +69,7 @@ struct WsLayout {
 };
 
 struct GraphEntry {
-    uint64_t key;
+    std::vector<unsigned char> key;   // everything the captured launches were derived from (graph_key)
     hipGraphExec_t exec;
     hipGraph_t graph;
     hipEvent_t last_launch;   // recorded on the caller's stream after every replay
@@ -161,6 +161,24 @@ const char *op_name(int op) {
     return op >= 0 && op < DYN_N_OPS ? n[op] : "?";
 }
 
+// Checks of an explicit schedule that need no batch: counts in range, arrays present, masks not empty.
+dyn_status check_schedule_fields(const dyn_schedule *s) {
+    if (s->k < 1 || s->k > DYN_MAX_NANO) return fail(DYN_ERR_SCHEDULE, "k = %d outside 1..%d", s->k, DYN_MAX_NANO);
+    if (!s->nano_rows || !s->slots || s->n_slots < 1) return fail(DYN_ERR_SCHEDULE, "nano_rows or slots missing");
+    if (s->n_streams < 1 || s->n_streams > DYN_MAX_STREAMS)
+        return fail(DYN_ERR_SCHEDULE, "n_streams = %d outside 1..%d", s->n_streams, DYN_MAX_STREAMS);
+    if (s->n_partitions < 0 || s->n_partitions > DYN_MAX_PARTITIONS)
+        return fail(DYN_ERR_SCHEDULE, "n_partitions = %d outside 0..%d", s->n_partitions, DYN_MAX_PARTITIONS);
+    if (s->n_partitions > 0 && (!s->cu_masks || s->cu_mask_words < 1 || s->cu_mask_words > 32))
+        return fail(DYN_ERR_SCHEDULE, "partitions need cu_masks with 1..32 words each");
+    for (int p = 0; p < s->n_partitions; ++p) {
+        uint32_t any = 0;
+        for (int i = 0; i < s->cu_mask_words; ++i) any |= s->cu_masks[p * s->cu_mask_words + i];
+        if (!any) return fail(DYN_ERR_SCHEDULE, "CU mask of partition %d is empty", p + 1);
+    }
+    return DYN_OK;
+}
+
 // Checks batch shapes and the schedule, and expands it into the per-forward dispatch list
 // with producer edges.
 dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, std::vector<Dispatch> &plan) {
@@ -190,20 +208,9 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
         slots = seq_slots.data();
         n_slots = n_chain;
     } else if (s->mode == DYN_SCHED_EXPLICIT) {
+        dyn_status rc = check_schedule_fields(s);
+        if (rc != DYN_OK) return rc;
         k = s->k;
-        if (k < 1 || k > DYN_MAX_NANO) return fail(DYN_ERR_SCHEDULE, "k = %d outside 1..%d", k, DYN_MAX_NANO);
-        if (!s->nano_rows || !s->slots || s->n_slots < 1) return fail(DYN_ERR_SCHEDULE, "nano_rows or slots missing");
-        if (s->n_streams < 1 || s->n_streams > DYN_MAX_STREAMS)
-            return fail(DYN_ERR_SCHEDULE, "n_streams = %d outside 1..%d", s->n_streams, DYN_MAX_STREAMS);
-        if (s->n_partitions < 0 || s->n_partitions > DYN_MAX_PARTITIONS)
-            return fail(DYN_ERR_SCHEDULE, "n_partitions = %d outside 0..%d", s->n_partitions, DYN_MAX_PARTITIONS);
-        if (s->n_partitions > 0 && (!s->cu_masks || s->cu_mask_words < 1 || s->cu_mask_words > 32))
-            return fail(DYN_ERR_SCHEDULE, "partitions need cu_masks with 1..32 words each");
-        for (int p = 0; p < s->n_partitions; ++p) {
-            uint32_t any = 0;
-            for (int i = 0; i < s->cu_mask_words; ++i) any |= s->cu_masks[p * s->cu_mask_words + i];
-            if (!any) return fail(DYN_ERR_SCHEDULE, "CU mask of partition %d is empty", p + 1);
-        }
         rows = s->nano_rows;
         if (rows[0] != 0 || rows[k] != T) return fail(DYN_ERR_SCHEDULE, "nano_rows must run from 0 to n_tokens");
         for (int i = 0; i < k; ++i) {
@@ -511,26 +518,33 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
     return DYN_OK;
 }
 
-uint64_t fnv(uint64_t h, const void *p, size_t n) {
-    const unsigned char *c = (const unsigned char *)p;
-    for (size_t i = 0; i < n; ++i) { h ^= c[i]; h *= 1099511628211ull; }
-    return h;
-}
-
-uint64_t graph_key(const dyn_batch *b, const dyn_schedule *s, const std::vector<Dispatch> &plan) {
-    uint64_t h = 1469598103934665603ull;
+// Everything a captured forward's launches are derived from on the host: the batch's pointers
+// and sizes, the sequence structure (q_start_host decides which attention kernels a dispatch
+// launches), every dispatch with the flags that change what it launches, and the CU masks.
+// Cached graphs are matched on the whole record, not on a hash of it.  What the kernels read
+// from device memory (positions, block table, activations) may change between replays.
+std::vector<unsigned char> graph_key(const dyn_batch *b, const dyn_schedule *s, const std::vector<Dispatch> &plan) {
+    std::vector<unsigned char> key;
+    auto put = [&](const void *p, size_t n) {
+        const unsigned char *c = (const unsigned char *)p;
+        key.insert(key.end(), c, c + n);
+    };
     const void *ptrs[] = {b->x, b->y, b->seq_of_token, b->pos_of_token, b->block_table, b->k_cache, b->v_cache, b->workspace};
-    h = fnv(h, ptrs, sizeof ptrs);
+    put(ptrs, sizeof ptrs);
     const int64_t dims[] = {b->n_tokens, b->n_seqs, b->max_pages_per_seq, (int64_t)b->kv_layer_stride,
-                            (int64_t)b->workspace_bytes};
-    h = fnv(h, dims, sizeof dims);
+                            (int64_t)b->workspace_bytes, (int64_t)plan.size()};
+    put(dims, sizeof dims);
+    put(b->q_start_host, sizeof(int32_t) * ((size_t)b->n_seqs + 1));
     for (const Dispatch &d : plan) {
-        const int f[] = {d.layer, d.op, d.r0, d.r1, d.stream, d.partition};
-        h = fnv(h, f, sizeof f);
+        const int f[] = {d.layer, d.op, d.r0, d.r1, d.stream, d.partition, d.any_multi, d.noop, d.lists_ready};
+        put(f, sizeof f);
     }
-    if (s->mode == DYN_SCHED_EXPLICIT && s->n_partitions > 0)
-        h = fnv(h, s->cu_masks, sizeof(uint32_t) * s->n_partitions * s->cu_mask_words);
-    return h;
+    if (s->mode == DYN_SCHED_EXPLICIT && s->n_partitions > 0) {
+        const int m[] = {s->n_partitions, s->cu_mask_words};
+        put(m, sizeof m);
+        put(s->cu_masks, sizeof(uint32_t) * s->n_partitions * s->cu_mask_words);
+    }
+    return key;
 }
 
 // Static data-flow analysis of one plan (Section 3.3.1, Algorithm 1): reference counts and
@@ -656,6 +670,14 @@ dyn_status check_config(const dyn_layer_config *c) {
     return DYN_OK;
 }
 
+dyn_status check_batch_tensors(const dyn_layer *L, const dyn_batch *b) {
+    if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table || !b->k_cache || !b->v_cache)
+        return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
+    if (b->x == b->y) return fail(DYN_ERR_INVALID_ARG, "y must not alias x");
+    if (L->cfg.n_layers > 1 && b->kv_layer_stride == 0) return fail(DYN_ERR_INVALID_ARG, "kv_layer_stride is 0 with several layers");
+    return DYN_OK;
+}
+
 }  // namespace
 
 extern "C" {
@@ -738,10 +760,7 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     dyn_status rc = build_plan(L, b, s, plan);
     if (rc != DYN_OK) return rc;
     if (b->n_tokens == 0) return DYN_OK;
-    if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table || !b->k_cache || !b->v_cache)
-        return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
-    if (b->x == b->y) return fail(DYN_ERR_INVALID_ARG, "y must not alias x");
-    if (L->cfg.n_layers > 1 && b->kv_layer_stride == 0) return fail(DYN_ERR_INVALID_ARG, "kv_layer_stride is 0 with several layers");
+    if ((rc = check_batch_tensors(L, b)) != DYN_OK) return rc;
     const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
     if (!b->workspace || ((uintptr_t)b->workspace & 255)) return fail(DYN_ERR_WORKSPACE, "workspace missing or not 256-byte aligned");
     if (b->workspace_bytes < ws.total)
@@ -761,7 +780,7 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
         return rc;
     }
     if (L->profiling) return fail(DYN_ERR_UNSUPPORTED, "profiling records eager schedules only");
-    const uint64_t key = graph_key(b, s, plan);
+    std::vector<unsigned char> key = graph_key(b, s, plan);
     // graphs evicted earlier are destroyed once their last replay has finished
     for (size_t i = 0; i < L->retired.size();) {
         if (hipEventQuery(L->retired[i].last_launch) == hipSuccess) {
@@ -823,9 +842,34 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
         L->retired.push_back(L->graphs.front());
         L->graphs.erase(L->graphs.begin());
     }
-    L->graphs.push_back(GraphEntry{key, exec, graph, last_launch, side_streams});
+    L->graphs.push_back(GraphEntry{std::move(key), exec, graph, last_launch, side_streams});
     HIP_TRY(hipGraphLaunch(exec, origin));
     HIP_TRY(hipEventRecord(last_launch, origin));
+    return DYN_OK;
+}
+
+dyn_status dyn_layer_prepare(dyn_layer *L, const dyn_schedule *s) {
+    if (!L) return fail(DYN_ERR_INVALID_ARG, "NULL layer");
+    dyn_status rc = DYN_OK;
+    if (!s || s->mode == DYN_SCHED_SEQUENTIAL) return DYN_OK;
+    if (s->mode != DYN_SCHED_EXPLICIT) return fail(DYN_ERR_SCHEDULE, "unknown schedule mode %d", s->mode);
+    if ((rc = check_schedule_fields(s)) != DYN_OK) return rc;
+    for (int i = 0; i < s->n_slots; ++i) {
+        const dyn_slot &sl = s->slots[i];
+        if (sl.stream >= s->n_streams || sl.partition > s->n_partitions)
+            return fail(DYN_ERR_SCHEDULE, "slot %d: stream %d / partition %d out of range", i, sl.stream, sl.partition);
+        const int key = sl.partition * DYN_MAX_STREAMS + sl.stream;
+        hipStream_t tmp;
+        if (key != 0 && (rc = ensure_stream(L, s, key, &tmp)) != DYN_OK) return rc;
+    }
+    return DYN_OK;
+}
+
+dyn_status dyn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *hip_stream) {
+    if (!buf || !sink || bytes < 16 || (bytes & 15) || ((uintptr_t)buf & 15) || ((uintptr_t)sink & 3))
+        return fail(DYN_ERR_INVALID_ARG, "probe needs a 16-byte aligned buffer of a multiple of 16 bytes and a sink");
+    hipError_t e = dyn::launch_stream_read(buf, bytes, (uint32_t *)sink, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(DYN_ERR_HIP, "launch of the read probe failed: %s", hipGetErrorString(e));
     return DYN_OK;
 }
 

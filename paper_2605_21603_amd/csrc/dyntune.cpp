@@ -83,6 +83,12 @@ extern "C" dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const i
         return fail(DYN_ERR_HIP, "cannot create timing events");
     hipStream_t stream = (hipStream_t)hip_stream;
     result->n_tried = result->n_skipped = 0;
+    // every side stream of every candidate exists before the first one is timed: creating a
+    // CU-masked stream synchronises the device, which must not land inside a timed replay loop
+    for (int i = 0; i < n; ++i) {
+        dyn_schedule sched;
+        if (dyn_tune_record(s, &cand[i], n_cus, opt.use_graph, &sched) == DYN_OK) (void)dyn_layer_prepare(layer, &sched);
+    }
     int best = 0;
     for (int i = 0; i < n; ++i) {
         dyn_schedule sched;

@@ -110,4 +110,7 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
 hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s);
 
+// Measurement aid: reads `bytes` (a multiple of 16, 16-byte aligned) of buf once; sink receives 8192 words.
+hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t s);
+
 }  // namespace dyn

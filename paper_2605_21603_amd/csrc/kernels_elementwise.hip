@@ -213,4 +213,26 @@ hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int
     return hipGetLastError();
 }
 
+// Read-only streaming probe: every 16-byte word of a buffer is loaded once (a workgroup reads
+// 4 KB contiguously per step of a grid-wide stride; eight workgroups per CU keep the loads of
+// different steps in flight) and folded into one word per wave so that the loads cannot be
+// dropped.  What it reaches is the rate this GPU's memory system delivers to a kernel that does
+// nothing else: the practical ceiling next to the datasheet peak.
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4 *__restrict__ p, size_t n_vec, uint32_t *__restrict__ sink) {
+    const size_t stride = (size_t)gridDim.x * 256;
+    u32x4 acc = u32x4{0u, 0u, 0u, 0u};
+    for (size_t i = (size_t)blockIdx.x * 256 + threadIdx.x; i < n_vec; i += stride) acc ^= p[i];
+    uint32_t v = acc[0] ^ acc[1] ^ acc[2] ^ acc[3];
+#pragma unroll
+    for (int off = 32; off >= 1; off >>= 1) v ^= __shfl_xor(v, off, 64);
+    if ((threadIdx.x & 63) == 0) sink[blockIdx.x * 4 + (threadIdx.x >> 6)] = v;
+}
+
+constexpr int kProbeBlocks = 2048;      // eight workgroups for each of the 256 CUs
+
+hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t s) {
+    hipLaunchKernelGGL(stream_read_kernel, dim3(kProbeBlocks), dim3(256), 0, s, (const u32x4 *)buf, bytes / 16, sink);
+    return hipGetLastError();
+}
+
 }  // namespace dyn

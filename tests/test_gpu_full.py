@@ -2,6 +2,8 @@
 (HIP-graph replay, sequential and overlapped schedules), checked on sampled sequences the
 oracle can compute one by one (rows are independent per sequence), and bit for bit between
 schedules over the whole batch."""
+import dataclasses
+
 import numpy as np
 import pytest
 import torch
@@ -10,7 +12,7 @@ from oracle import oracle as orc
 from paper_2605_21603_amd import binding as B
 from workloads import gen
 
-from gpu_util import TOL, GpuRun, as_f64, row_rel_err, say, stack_tol
+from gpu_util import TOL, GpuRun, as_f64, row_rel_err, say
 
 pytestmark = pytest.mark.gpu
 
@@ -23,6 +25,18 @@ def bench_schedules(w):
             "k2_mlp_merged_stagger2": B.nano_schedule(w.nano_rows, chain, merged_ops=mlp, stagger=2, use_graph=True)}
 
 
+def c5_sample_ids(w):
+    """Shortest and longest context, and one sequence for every split-KV chunk count that
+    occurs (a sequence of P pages has ceil(P / 16) chunks of 256 positions)."""
+    ctx = np.array([c for _, c in w.seqs])
+    order = np.argsort(ctx, kind="stable")
+    ids = {int(order[0]), int(order[-1])}
+    chunks = (((ctx + 15) // 16) + 15) // 16
+    for n in np.unique(chunks):
+        ids.add(int(np.nonzero(chunks == n)[0][0]))
+    return sorted(ids)
+
+
 def sample_ids(w, n):
     ctx = np.array([c for _, c in w.seqs])
     order = np.argsort(ctx, kind="stable")
@@ -33,8 +47,10 @@ def sample_ids(w, n):
     return sorted(ids)
 
 
-@pytest.mark.parametrize("name,n_sample", [("c2", 6), ("c4", 6), ("d300", 6), ("d600", 6), ("d1100", 6)])
-def test_decode_configs_full_size(name, n_sample):
+@pytest.mark.parametrize("name", ["c2", "c4", "d300", "d600", "d1100"])
+def test_decode_configs_full_size(name):
+    """Every sequence of the batch against the oracle (the oracle's loops are parallel over
+    rows), and every schedule against the sequential one bit for bit."""
     say("case %s: generating" % name)
     w = gen.config(name)
     data = gen.generate(w)
@@ -48,28 +64,34 @@ def test_decode_configs_full_size(name, n_sample):
         assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
         assert torch.equal(kc.view(torch.uint8), k0.view(torch.uint8)), label
         assert torch.equal(vc.view(torch.uint8), v0.view(torch.uint8)), label
-    ids = sample_ids(w, n_sample)
-    say("case %s: oracle on sequences %s" % (name, ids))
-    w2, d2 = gen.sub_batch(w, data, ids)
+    say("case %s: oracle on all %d sequences" % (name, w.n_seqs))
     routing = [] if w.shape.n_experts else None
-    y_ref, kcs, _ = orc.forward(w2, d2, routing_out=routing)
-    y_got = as_f64(y0)[d2["rows"]]
+    y_ref, kcs, vcs = orc.forward(w, data, routing_out=routing)
+    y_got = as_f64(y0)
+    rows = np.arange(w.n_tokens)
     if routing:
-        logits = routing[0]["logits"]
-        srt = np.sort(logits, axis=1)[:, ::-1]
-        assert (srt[:, w.shape.top_k - 1] - srt[:, w.shape.top_k]).min() > 1e-3, "pick other samples: router near tie"
-    err = row_rel_err(y_got, y_ref)
-    say("case %s: max rel err %.3e on %d sampled rows" % (name, err, len(ids)))
+        # two selections are both correct where the router's 2nd and 3rd logits nearly tie: such rows are
+        # counted and left out (the small MoE cases re-check them against the other selection)
+        srt = np.sort(routing[0]["logits"], axis=1)[:, ::-1]
+        clear = srt[:, w.shape.top_k - 1] - srt[:, w.shape.top_k] > 1e-3
+        say("case %s: %d of %d rows have a router near tie and are skipped" % (name, int((~clear).sum()), w.n_tokens))
+        assert clear.sum() >= 0.98 * w.n_tokens
+        rows = rows[clear]
+    err = row_rel_err(y_got[rows], y_ref[rows])
+    say("case %s: max rel err %.3e on %d of %d rows" % (name, err, len(rows), w.n_tokens))
     assert err <= TOL[w.shape.dtype]
-    # appended cache entries of the sampled sequences
+    # the cache entries every sequence appended, and nothing else touched
     ps = w.shape.page_size
-    k_ref = orc.widen(kcs[0], orc.dtype_code(w.shape.dtype))
-    k_got = as_f64(k0[0])
-    for s in ids:
-        p = w.seqs[s][1] - 1
-        page, slot = data["block_table"][s, p // ps], p % ps
-        scale = np.abs(k_ref[page, :, slot, :]).max()
-        assert np.abs(k_got[page, :, slot, :] - k_ref[page, :, slot, :]).max() <= TOL[w.shape.dtype] * scale
+    dt = orc.dtype_code(w.shape.dtype)
+    k_ref, v_ref = orc.widen(kcs[0], dt), orc.widen(vcs[0], dt)
+    k_got, v_got = as_f64(k0[0]), as_f64(v0[0])
+    pages = np.array([data["block_table"][s, (c - 1) // ps] for s, (_, c) in enumerate(w.seqs)])
+    slots = np.array([(c - 1) % ps for _, c in w.seqs])
+    for got, ref in ((k_got[pages, :, slots, :], k_ref[pages, :, slots, :]), (v_got[pages, :, :, slots], v_ref[pages, :, :, slots])):
+        assert np.abs(got - ref).max() <= TOL[w.shape.dtype] * np.abs(ref).max()
+    touched_k = np.zeros(k_got.shape, bool)
+    touched_k[pages, :, slots, :] = True
+    assert np.array_equal(k_got[~touched_k], as_f64(data["k_cache"][0])[~touched_k])
 
 
 def test_prefill_decode_mix_full_size():
@@ -102,8 +124,12 @@ def test_prefill_decode_mix_full_size():
     v = kv[:, nkv * d:].reshape(-1, nkv, d)
     kc, vc = orc.to_storage(data["k_cache"][0]).copy(), orc.to_storage(data["v_cache"][0]).copy()
     orc.cache_append(cfg, k, v, data["seq_of_token"], data["pos_of_token"], data["block_table"], kc, vc)
-    rows = np.array(sorted({0, 1, 15, 16, 255, 256, 1000, 2046, 2047, 2048, 2049, 2111} |
-                           {int(r) for r in np.random.default_rng(5).integers(0, w.n_tokens, 12)}))
+    # first and last token of every 64-token query block, both sides of every 1024-key chunk edge,
+    # random rows of the chunk, and all 64 decodes
+    rows = {64 * b for b in range(32)} | {64 * b + 63 for b in range(32)} | {1, 15, 16, 17, 1022, 1025, 2046}
+    rows |= {int(r) for r in np.random.default_rng(5).integers(0, 2048, 200)} | set(range(2048, 2112))
+    rows = np.array(sorted(rows))
+    assert len(rows) >= 256 + 64
     say("case c3: oracle layer for %d sampled rows" % len(rows))
     q = orc.rope(orc.linear(h1[rows], wt["w_qkv"][:nq * d], dt).reshape(-1, nq, d), data["pos_of_token"][rows], sh.rope_base)
     o = orc.attention(cfg, q, np.ascontiguousarray(data["seq_of_token"][rows]),
@@ -121,11 +147,12 @@ def test_prefill_decode_mix_full_size():
     assert np.abs(k_got[pages] - k_ref[pages]).max() <= TOL[sh.dtype] * scale
 
 
+@pytest.mark.timeout(600)
 def test_32_layer_decode_step_full_size():
     """c5: 32 layers, batch 256, contexts up to 8192 (about 155 GB of cache, generated in
     device memory).  Sequential, 2 and 4 micro-batches on CU-partitioned streams, all as HIP
-    graphs; outputs and appended cache entries bit for bit; the oracle runs 4 sampled
-    sequences through all 32 layers."""
+    graphs; outputs and appended cache entries bit for bit; every layer against the oracle on
+    sampled sequences."""
     free, total = torch.cuda.mem_get_info()
     if total < 200 * 2 ** 30:
         pytest.skip("needs a 288 GB device")
@@ -162,11 +189,48 @@ def test_32_layer_decode_step_full_size():
         assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
         assert torch.equal(kk.view(torch.uint8), k0.view(torch.uint8)), label
         assert torch.equal(vv.view(torch.uint8), v0.view(torch.uint8)), label
-    ids = sample_ids(w, 4)
-    say("case c5: oracle on sequences %s through 32 layers" % ids)
-    # the step has already appended this token's keys; the oracle overwrites them with its own
+    # ---- against the oracle, layer by layer (teacher-forced)
+    # A stack of random layers amplifies storage roundings from layer to layer (about sqrt(L); the
+    # end-to-end figure is printed below and is not the gate).  The stated bound is a per-layer
+    # one, so every layer is checked on its own: layer l runs alone, through a one-layer handle,
+    # on the input the 32-layer step gave it, and is compared with the oracle's layer on that
+    # same input; the chain of one-layer calls must reproduce the 32-layer call bit for bit,
+    # which ties the per-layer checks to the step that is benchmarked.
+    ids = c5_sample_ids(w)
+    say("case c5: %d sampled sequences (shortest, longest, one per split-KV chunk count): %s" % (len(ids), ids))
     w2, d2 = gen.extract_sequences(w, data, ids)
-    y_ref, _, _ = orc.forward(w2, d2)
-    err = row_rel_err(as_f64(y0)[d2["rows"]], y_ref)
-    say("case c5: max rel err %.3e on %d sampled rows" % (err, len(ids)))
-    assert err <= stack_tol(w.shape.dtype, w.shape.n_layers)
+    rows = d2["rows"]
+    sh1 = dataclasses.replace(w.shape, n_layers=1)
+    dt = orc.dtype_code(sh1.dtype)
+    x_l = step.x
+    stride = step.batch.kv_layer_stride
+    worst, worst_layer = 0.0, -1
+    x_ref_chain = orc.widen(orc.to_storage(d2["x"]), dt)           # the oracle's own 32-layer chain, for the reported figure
+    for l in range(w.shape.n_layers):
+        one = B.DynLayer(B.make_config(sh1), [data["weights"][l]])
+        y_l = torch.empty_like(x_l)
+        batch = B.dyn_batch.from_buffer_copy(step.batch)
+        batch.x, batch.y = x_l.data_ptr(), y_l.data_ptr()
+        batch.k_cache = step.batch.k_cache + l * stride
+        batch.v_cache = step.batch.v_cache + l * stride
+        with torch.cuda.stream(st):
+            one.forward(batch, B.sequential(), st)
+        st.synchronize()
+        wts = {k: orc.to_storage(v) for k, v in d2["weights"][l].items()}
+        x_in = orc.widen(orc.to_storage(x_l[torch.as_tensor(rows, device=x_l.device)].cpu()), dt)
+        kc, vc = orc.to_storage(d2["k_cache"][l]).copy(), orc.to_storage(d2["v_cache"][l]).copy()
+        y_ref = orc.layer_forward(sh1, wts, x_in, d2["seq_of_token"], d2["pos_of_token"], d2["block_table"], kc, vc)
+        err = row_rel_err(as_f64(y_l[torch.as_tensor(rows, device=x_l.device)].cpu()), y_ref)
+        kc2, vc2 = orc.to_storage(d2["k_cache"][l]).copy(), orc.to_storage(d2["v_cache"][l]).copy()
+        x_ref_chain = orc.layer_forward(sh1, wts, x_ref_chain, d2["seq_of_token"], d2["pos_of_token"], d2["block_table"], kc2, vc2)
+        say("case c5: layer %2d alone on the step's own input: max rel err %.3e" % (l, err))
+        if err > worst:
+            worst, worst_layer = err, l
+        assert err <= TOL[w.shape.dtype], "layer %d: %.3e" % (l, err)
+        one.close()
+        x_l = y_l
+    assert torch.equal(x_l.cpu().view(torch.uint8), y0.view(torch.uint8)), "chained one-layer calls differ from the 32-layer call"
+    end_to_end = row_rel_err(as_f64(y0)[rows], x_ref_chain)
+    say("case c5: worst single layer %.3e (layer %d, bound %.0e); end to end through 32 layers %.3e (reported, not a gate)"
+        % (worst, worst_layer, TOL[w.shape.dtype], end_to_end))
+    assert end_to_end < 0.25          # a sanity bound only: an error of this size means a broken layer, not rounding drift

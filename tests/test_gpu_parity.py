@@ -174,3 +174,43 @@ def test_graph_cache_eviction_keeps_replays_correct():
     torch.cuda.synchronize()
     assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8))
     assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8))
+
+
+def test_cached_graph_is_not_replayed_for_another_sequence_structure():
+    """Two batches that agree in every pointer, in n_tokens, n_seqs and the cut row, and differ
+    only in where the two-token sequence sits: (2,1,1) against (1,1,2), cut at row 2.  Which
+    attention kernels a micro-batch launches follows from that structure, so a graph captured for
+    one must not be replayed for the other.  Same buffers throughout, contents swapped in place."""
+    import dataclasses
+    sh = gen.LayerShape("bf16", 512, 8, 2, 128, 1024)
+    wa = gen.Workload("swap_a", sh, ((2, 40), (1, 70), (1, 100)), 31, (0, 2, 4))
+    wb = gen.Workload("swap_b", sh, ((1, 100), (1, 70), (2, 40)), 32, (0, 2, 4))
+    da, db = gen.generate(wa), gen.generate(wb)
+    db["weights"] = da["weights"]            # one layer handle serves both batches
+    assert da["block_table"].shape == db["block_table"].shape and da["n_pages"] == db["n_pages"]
+    run = GpuRun(wa, da)
+    step = B.DeviceStep(run.layer, da)
+    step.q_start_host = step.q_start_host.copy()          # a host array of the step's own, rewritten in place below
+    step.batch.q_start_host = step.q_start_host.ctypes.data
+    sched = B.nano_schedule((0, 2, 4), stagger=1, use_graph=True)
+    st = torch.cuda.Stream()
+
+    def load(data):
+        step.x.copy_(data["x"])
+        step.k_cache.copy_(torch.stack(data["k_cache"]))
+        step.v_cache.copy_(torch.stack(data["v_cache"]))
+        step.seq_of_token.copy_(torch.from_numpy(data["seq_of_token"]))
+        step.pos_of_token.copy_(torch.from_numpy(data["pos_of_token"]))
+        step.block_table.copy_(torch.from_numpy(np.ascontiguousarray(data["block_table"])))
+        step.q_start_host[:] = data["q_start"]
+        step.y.zero_()
+        torch.cuda.synchronize()
+
+    for label, (w, data) in (("a", (wa, da)), ("b", (wb, db)), ("a again", (wa, da)), ("b again", (wb, db))):
+        say("case swap: structure %s under the same buffers" % label)
+        load(data)
+        with torch.cuda.stream(st):
+            run.layer.forward(step.batch, sched, st)
+        st.synchronize()
+        err = check_against_oracle(w, data, step.y.cpu(), step.k_cache.cpu(), step.v_cache.cpu())
+        say("case swap %s: max rel err %.3e" % (label, err))
