@@ -153,7 +153,8 @@ dyn_status dyn_schedule_validate(const dyn_layer *layer, const dyn_batch *batch,
  * until the process ends.  Section 2.1 ("Overlapping") names partitioned contexts as the
  * second way to overlap beside plain streams; this is their set-up step.  Optional: a
  * forward creates what is missing itself (see below).  sched may be NULL or sequential
- * (nothing to create). */
+ * (no stream to create).  Also resolves the current device's copy of the static workspace
+ * of dyn_layer_forward_noalloc. */
 dyn_status dyn_layer_prepare(dyn_layer *layer, const dyn_schedule *sched);
 
 /* Runs all layers.  Asynchronous: work is forked from hip_stream (a hipStream_t, not the
@@ -171,6 +172,24 @@ dyn_status dyn_layer_prepare(dyn_layer *layer, const dyn_schedule *sched);
  * sizes, q_start_host contents, cut points and slots stay the same; the contents of device
  * arrays (positions, block table, activations, caches) may change between replays. */
 dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, void *hip_stream);
+
+/* For callers that cannot allocate device memory or create GPU objects at the point of the
+ * call: code running under a HIP graph capture of their own, tight serving loops, harnesses
+ * that forbid hipMalloc.  The same forward as dyn_layer_forward with the sequential schedule,
+ * except that batch->workspace / workspace_bytes are ignored: the workspace is a static device
+ * array inside the library (DYN_NOALLOC_MAX_WORKSPACE bytes, held by every GPU the library
+ * runs on until the process ends).  All operators are issued in chain order on hip_stream;
+ * no stream, event or graph is created, nothing is allocated or freed, by the library or
+ * through any allocating routine.  (The array's device address is resolved once per device,
+ * at the first call on it or by dyn_layer_prepare; that first resolution loads the library's
+ * code object if no kernel of it has run yet.)
+ *   DYN_ERR_WORKSPACE  the batch needs more than DYN_NOALLOC_MAX_WORKSPACE bytes
+ *                      (dyn_layer_workspace_bytes tells): use dyn_layer_forward.
+ * Every call on a GPU uses that GPU's one array, which keeps the previous call's contents
+ * (nothing in it has to start at zero).  Calls that overlap in time on one GPU - from two
+ * streams or two handles - race on it: keep them on one stream or order them with events. */
+enum { DYN_NOALLOC_MAX_WORKSPACE = 96 << 20 };
+dyn_status dyn_layer_forward_noalloc(dyn_layer *layer, const dyn_batch *batch, void *hip_stream);
 
 /* Profiling (eager schedules only): when on, every dispatch is bracketed by events on its
  * own stream.  After the caller has synchronised, dyn_layer_get_slot_times returns, for

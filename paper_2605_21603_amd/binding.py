@@ -20,6 +20,7 @@ DYN_F32, DYN_BF16 = 0, 1
 DYN_N_OPS = 10
 DYN_SCHED_SEQUENTIAL, DYN_SCHED_EXPLICIT = 0, 1
 DYN_MAX_NANO, DYN_MAX_STREAMS, DYN_MAX_PARTITIONS = 8, 8, 4
+DYN_NOALLOC_MAX_WORKSPACE = 96 << 20
 DYN_FORM_SEQUENTIAL, DYN_FORM_SPLIT, DYN_FORM_MLP_MERGED, DYN_FORM_ATTN_SPLIT, DYN_FORM_MLP_SPLIT = 0, 1, 2, 3, 4
 FORM_NAMES = ["sequential", "split", "mlp_merged", "attn_split", "mlp_split"]
 OP_NAMES = ["norm1", "qkv", "rope_kv", "attn", "oproj", "norm2", "route", "gate_up", "silu", "down"]
@@ -94,7 +95,7 @@ class dyn_slot_time(C.Structure):
 
 
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
-           "dyn_layer_prepare", "dyn_layer_forward", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
+           "dyn_layer_prepare", "dyn_layer_forward", "dyn_layer_forward_noalloc", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
            "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_probe_hbm_read"]
@@ -118,6 +119,7 @@ def lib() -> C.CDLL:
         l.dyn_schedule_validate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_prepare.argtypes = [C.c_void_p, C.c_void_p]
+        l.dyn_layer_forward_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
         l.dyn_layer_get_slot_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
@@ -388,6 +390,11 @@ class DynLayer:
         sc = sched.to_c()
         s = stream if stream is not None else torch.cuda.current_stream()
         _check(lib().dyn_layer_forward(self.handle, C.addressof(batch), C.addressof(sc), C.c_void_p(s.cuda_stream)))
+
+    def forward_noalloc(self, batch: dyn_batch, stream: Optional[torch.cuda.Stream] = None) -> None:
+        """Sequential forward on the library's static workspace (batch.workspace is ignored)."""
+        s = stream if stream is not None else torch.cuda.current_stream()
+        _check(lib().dyn_layer_forward_noalloc(self.handle, C.addressof(batch), C.c_void_p(s.cuda_stream)))
 
     def set_profiling(self, on: bool) -> None:
         _check(lib().dyn_layer_set_profiling(self.handle, int(on)))

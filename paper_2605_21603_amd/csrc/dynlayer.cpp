@@ -670,6 +670,33 @@ dyn_status check_config(const dyn_layer_config *c) {
     return DYN_OK;
 }
 
+// Workspace of dyn_layer_forward_noalloc: a device array that is part of the library's code
+// object, so callers that must not allocate need no workspace of their own.  Each GPU the
+// library runs on holds its own copy at its own address until the process ends; the name below
+// is only the host-side handle of the symbol, the address comes from hipGetSymbolAddress, once
+// per device, and everything (kernel arguments included) uses that pointer.
+constexpr size_t kScratchBytes = DYN_NOALLOC_MAX_WORKSPACE;
+static __device__ __align__(256) unsigned char scratch[kScratchBytes];
+
+constexpr int kMaxDevices = 64;
+void *g_scratch_ptr[kMaxDevices] = {};
+std::mutex g_scratch_mutex;
+
+dyn_status scratch_pointer(void **out) {
+    int dev = -1;
+    HIP_TRY(hipGetDevice(&dev));
+    if (dev < 0 || dev >= kMaxDevices) return fail(DYN_ERR_UNSUPPORTED, "device index %d outside 0..%d", dev, kMaxDevices - 1);
+    std::lock_guard<std::mutex> lock(g_scratch_mutex);
+    if (!g_scratch_ptr[dev]) {
+        void *ptr = nullptr;
+        HIP_TRY(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+        if (!ptr || ((uintptr_t)ptr & 255)) return fail(DYN_ERR_HIP, "static scratch array resolved to a bad address %p", ptr);
+        g_scratch_ptr[dev] = ptr;
+    }
+    *out = g_scratch_ptr[dev];
+    return DYN_OK;
+}
+
 dyn_status check_batch_tensors(const dyn_layer *L, const dyn_batch *b) {
     if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table || !b->k_cache || !b->v_cache)
         return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
@@ -850,7 +877,9 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
 
 dyn_status dyn_layer_prepare(dyn_layer *L, const dyn_schedule *s) {
     if (!L) return fail(DYN_ERR_INVALID_ARG, "NULL layer");
-    dyn_status rc = DYN_OK;
+    void *unused = nullptr;
+    dyn_status rc = scratch_pointer(&unused);      // resolves this device's copy of the static scratch array as part of set-up
+    if (rc != DYN_OK) return rc;
     if (!s || s->mode == DYN_SCHED_SEQUENTIAL) return DYN_OK;
     if (s->mode != DYN_SCHED_EXPLICIT) return fail(DYN_ERR_SCHEDULE, "unknown schedule mode %d", s->mode);
     if ((rc = check_schedule_fields(s)) != DYN_OK) return rc;
@@ -861,6 +890,34 @@ dyn_status dyn_layer_prepare(dyn_layer *L, const dyn_schedule *s) {
         const int key = sl.partition * DYN_MAX_STREAMS + sl.stream;
         hipStream_t tmp;
         if (key != 0 && (rc = ensure_stream(L, s, key, &tmp)) != DYN_OK) return rc;
+    }
+    return DYN_OK;
+}
+
+dyn_status dyn_layer_forward_noalloc(dyn_layer *L, const dyn_batch *b, void *hip_stream) {
+    dyn_schedule seq{};
+    seq.mode = DYN_SCHED_SEQUENTIAL;
+    std::vector<Dispatch> plan;
+    dyn_status rc = build_plan(L, b, &seq, plan);
+    if (rc != DYN_OK) return rc;
+    if (b->n_tokens == 0) return DYN_OK;
+    if ((rc = check_batch_tensors(L, b)) != DYN_OK) return rc;
+    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    if (ws.total > kScratchBytes)
+        return fail(DYN_ERR_WORKSPACE, "this batch needs %zu bytes of workspace, the static scratch array holds %zu: use dyn_layer_forward with a workspace of the caller's",
+                    ws.total, kScratchBytes);
+    void *ptr = nullptr;
+    if ((rc = scratch_pointer(&ptr)) != DYN_OK) return rc;
+    dyn_batch local = *b;
+    local.workspace = ptr;                  // the device address of this GPU's copy, never the symbol's name
+    local.workspace_bytes = kScratchBytes;
+    // Chain order on the caller's stream: no side stream, no event, no graph, nothing created.
+    // Nothing in the workspace has to start at zero: every region is written by the operator
+    // before the one that reads it, and the work lists' counters are set by the kernel that
+    // builds the lists.
+    for (const Dispatch &d : plan) {
+        if (d.noop) continue;
+        if ((rc = launch_op(L, &local, &seq, ws, d, (hipStream_t)hip_stream, nullptr, nullptr)) != DYN_OK) return rc;
     }
     return DYN_OK;
 }
