@@ -168,7 +168,10 @@ dyn_status dyn_layer_prepare(dyn_layer *layer, const dyn_schedule *sched);
  * library (the backend, not the scheduler author, owns data flow; Section 3.2.2).
  * Output rows land at their global row index whatever the split (zero-copy merge,
  * Section 3.3.1).  Any legal schedule gives bit-identical y and cache contents.
- * With use_graph the captured step is cached and replayed while the batch's pointers,
+ * With use_graph the captured step is cached (16 graphs, fewer when they have many parallel
+ * branches; the oldest is evicted and destroyed once its last replay has finished; a burst of
+ * more than 8 evictions whose replays are all still running makes the call wait for the oldest)
+ * and replayed while the batch's pointers,
  * sizes, q_start_host contents, cut points and slots stay the same; the contents of device
  * arrays (positions, block table, activations, caches) may change between replays. */
 dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, void *hip_stream);
@@ -190,6 +193,13 @@ dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn
  * streams or two handles - race on it: keep them on one stream or order them with events. */
 enum { DYN_NOALLOC_MAX_WORKSPACE = 96 << 20 };
 dyn_status dyn_layer_forward_noalloc(dyn_layer *layer, const dyn_batch *batch, void *hip_stream);
+
+/* Destroys every HIP graph the handle has captured (the cached ones and those evicted from the
+ * cache whose last replay had not finished), after waiting for each one's last replay: BLOCKS
+ * the host.  A schedule run with use_graph afterwards is captured again.  For callers that try
+ * many schedules once each - the measured search of dyn_tune calls it after every candidate,
+ * so that at most one multi-stream executable is alive while candidates are timed. */
+dyn_status dyn_layer_release_graphs(dyn_layer *layer);
 
 /* Profiling (eager schedules only): when on, every dispatch is bracketed by events on its
  * own stream.  After the caller has synchronised, dyn_layer_get_slot_times returns, for

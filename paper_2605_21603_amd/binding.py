@@ -95,7 +95,7 @@ class dyn_slot_time(C.Structure):
 
 
 EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes", "dyn_schedule_validate",
-           "dyn_layer_prepare", "dyn_layer_forward", "dyn_layer_forward_noalloc", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
+           "dyn_layer_prepare", "dyn_layer_release_graphs", "dyn_layer_forward", "dyn_layer_forward_noalloc", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
            "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_probe_hbm_read"]
@@ -119,6 +119,7 @@ def lib() -> C.CDLL:
         l.dyn_schedule_validate.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_forward.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_layer_prepare.argtypes = [C.c_void_p, C.c_void_p]
+        l.dyn_layer_release_graphs.argtypes = [C.c_void_p]
         l.dyn_layer_forward_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
@@ -385,6 +386,10 @@ class DynLayer:
         """Creates the schedule's side streams now (synchronises the device for CU-masked ones)."""
         sc = sched.to_c()
         _check(lib().dyn_layer_prepare(self.handle, C.addressof(sc)))
+
+    def release_graphs(self) -> None:
+        """Waits for and destroys every captured graph of the handle."""
+        _check(lib().dyn_layer_release_graphs(self.handle))
 
     def forward(self, batch: dyn_batch, sched: Schedule, stream: Optional[torch.cuda.Stream] = None) -> None:
         sc = sched.to_c()

@@ -59,6 +59,8 @@ struct Dispatch {
     int key() const { return partition * DYN_MAX_STREAMS + stream; }
 };
 
+constexpr int kMaxRetiredGraphs = 8, kMaxRetiredBranches = 8;   // evicted executables still waiting for their last replay
+
 struct WsLayout {
     size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, plan, total;
     size_t sel, wgt, lists_gu, lists_down, moe_planes;   // MoE: routing, per-dispatch expert lists, down-projection planes
@@ -291,6 +293,12 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
                 if (plan[j].op == DYN_OP_GATE_UP && !plan[j].noop && plan[j].r0 == d.r0 && plan[j].r1 == d.r1) d.lists_ready = true;
         }
     return DYN_OK;
+}
+
+void destroy_graph_entry(GraphEntry &g) {
+    (void)hipGraphExecDestroy(g.exec);
+    (void)hipGraphDestroy(g.graph);
+    (void)hipEventDestroy(g.last_launch);
 }
 
 // CU-masked streams are hardware queues whose mask is set through the driver.  They are made
@@ -736,11 +744,7 @@ void dyn_layer_destroy(dyn_layer *L) {
     if (!L) return;
     (void)hipDeviceSynchronize();
     for (auto *list : {&L->graphs, &L->retired})
-        for (auto &g : *list) {
-            (void)hipGraphExecDestroy(g.exec);
-            (void)hipGraphDestroy(g.graph);
-            (void)hipEventDestroy(g.last_launch);
-        }
+        for (auto &g : *list) destroy_graph_entry(g);
     for (auto ev : L->events) (void)hipEventDestroy(ev);
     for (auto ev : L->prof_events) (void)hipEventDestroy(ev);
     if (L->fork_event) (void)hipEventDestroy(L->fork_event);
@@ -811,14 +815,25 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     // graphs evicted earlier are destroyed once their last replay has finished
     for (size_t i = 0; i < L->retired.size();) {
         if (hipEventQuery(L->retired[i].last_launch) == hipSuccess) {
-            (void)hipGraphExecDestroy(L->retired[i].exec);
-            (void)hipGraphDestroy(L->retired[i].graph);
-            (void)hipEventDestroy(L->retired[i].last_launch);
+            destroy_graph_entry(L->retired[i]);
             L->retired.erase(L->retired.begin() + i);
         } else {
             (void)hipGetLastError();       // "not ready" is an answer, not an error to find later
             ++i;
         }
+    }
+    // A burst of distinct schedules issued without a host wait can pile evicted executables up
+    // behind their last replays.  The number alive at once is bounded: beyond it this call
+    // waits for the oldest one's last replay (the only place a graph forward blocks the host).
+    auto retired_branches = [&]() {
+        int n = 0;
+        for (const GraphEntry &g : L->retired) n += g.side_streams;
+        return n;
+    };
+    while (!L->retired.empty() && ((int)L->retired.size() > kMaxRetiredGraphs || retired_branches() > kMaxRetiredBranches)) {
+        HIP_TRY(hipEventSynchronize(L->retired.front().last_launch));
+        destroy_graph_entry(L->retired.front());
+        L->retired.erase(L->retired.begin());
     }
     for (auto &g : L->graphs)
         if (g.key == key) {
@@ -872,6 +887,18 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     L->graphs.push_back(GraphEntry{std::move(key), exec, graph, last_launch, side_streams});
     HIP_TRY(hipGraphLaunch(exec, origin));
     HIP_TRY(hipEventRecord(last_launch, origin));
+    return DYN_OK;
+}
+
+dyn_status dyn_layer_release_graphs(dyn_layer *L) {
+    if (!L) return fail(DYN_ERR_INVALID_ARG, "NULL layer");
+    for (auto *list : {&L->graphs, &L->retired}) {
+        for (auto &g : *list) {
+            HIP_TRY(hipEventSynchronize(g.last_launch));     // recorded behind its last replay
+            destroy_graph_entry(g);
+        }
+        list->clear();
+    }
     return DYN_OK;
 }
 

@@ -94,6 +94,9 @@ extern "C" dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const i
         dyn_schedule sched;
         dyn_status rc = dyn_tune_record(s, &cand[i], n_cus, opt.use_graph, &sched);
         if (rc == DYN_OK) cand[i].us = time_candidate(layer, batch, &sched, stream, ev, warmup, iters, &rc);
+        // a candidate is used once: its graph goes before the next one is captured, so at most one
+        // multi-stream executable is alive at any time during the search
+        if (opt.use_graph) (void)dyn_layer_release_graphs(layer);
         if (rc != DYN_OK) {
             if (i == 0) return rc;       // the sequential order must run; the error text is the forward's
             cand[i].us = -1.f;

@@ -214,3 +214,29 @@ def test_cached_graph_is_not_replayed_for_another_sequence_structure():
         st.synchronize()
         err = check_against_oracle(w, data, step.y.cpu(), step.k_cache.cpu(), step.v_cache.cpu())
         say("case swap %s: max rel err %.3e" % (label, err))
+
+
+def test_released_graphs_are_captured_again():
+    """dyn_layer_release_graphs waits for and destroys every captured graph; the same schedules
+    then capture afresh and reproduce the same bits."""
+    w = gen.config("c3_small")
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    scheds = [B.sequential(use_graph=True), B.nano_schedule(w.nano_rows, stagger=1, use_graph=True),
+              B.nano_schedule(w.nano_rows, stagger=2, merged_ops=[B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN], use_graph=True)]
+    step = B.DeviceStep(run.layer, data)
+    st = torch.cuda.Stream()
+    for rnd in range(3):
+        for sched in scheds:
+            step.y.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(st):
+                run.layer.forward(step.batch, sched, st)
+                run.layer.forward(step.batch, sched, st)
+            if rnd == 1:
+                run.layer.release_graphs()          # replays still in flight: the call waits for them
+            st.synchronize()
+            assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8)), rnd
+        run.layer.release_graphs()
+    assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8))

@@ -28,7 +28,7 @@ def test_tuning_with_four_micro_batches():
 
 
 @pytest.mark.parametrize("name,max_k,partitions", [("c2_small", 2, 1), ("c3_small", 2, 1), ("c4_small", 2, 0),
-                                                   ("c5_small", 2, 0)])
+                                                   ("c5_small", 2, 0), ("c2_small", 3, 0), ("c5_small", 3, 1)])
 def test_tuned_schedule_is_bit_exact_and_the_table_is_consistent(name, max_k, partitions):
     _tune_and_check(name, max_k, partitions)
 
