@@ -94,7 +94,8 @@ typedef struct {
                                       q_start_host[s] .. q_start_host[s+1]-1, in position order */
     void *k_cache, *v_cache;       /* layer 0; MUTATED: this step's k', v are stored */
     size_t kv_layer_stride;        /* bytes from layer l's cache to layer l+1's (both caches) */
-    void *workspace;               /* >= dyn_layer_workspace_bytes(...), 256-byte aligned */
+    void *workspace;               /* >= dyn_schedule_workspace_bytes(...) for the schedule run (dyn_layer_workspace_bytes
+                                      covers every schedule), 256-byte aligned */
     size_t workspace_bytes;
 } dyn_batch;
 
@@ -133,10 +134,10 @@ dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights
 /* Releases streams, events, graphs.  Outstanding work must have been synchronised. */
 void dyn_layer_destroy(dyn_layer *layer);
 
-/* Bytes of workspace a forward of up to max_tokens tokens needs when no sequence has more
- * than max_pages_per_seq pages.  Independent of the schedule: overlap buffers results of
- * concurrently running micro-batches (the paper's peak-memory remark, Section 2.1), and
- * because a micro-batch is a row range of batch-sized buffers the bound is the same. */
+/* Bytes of workspace that suffice for ANY legal schedule of a forward of up to max_tokens
+ * tokens when no sequence has more than max_pages_per_seq pages: every intermediate and every
+ * operator's scratch for the whole batch at once, nothing shared.  A particular schedule
+ * usually needs much less: see dyn_schedule_workspace_bytes. */
 size_t dyn_layer_workspace_bytes(const dyn_layer *layer, int max_tokens, int max_pages_per_seq);
 
 /* Host-only check of a schedule against a batch's shapes (no device memory is read):
@@ -299,7 +300,7 @@ dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int us
  * it: overlap buffers the results of concurrently running micro-batches, which is the
  * peak-memory cost the paper names.  Host only. */
 typedef struct {
-    size_t workspace_bytes;             /* dyn_layer_workspace_bytes for this batch: every buffer at batch size, no reuse */
+    size_t workspace_bytes;             /* dyn_layer_workspace_bytes for this batch: enough for any schedule, nothing shared */
     size_t peak_live_bytes;             /* largest sum over live regions plus the running dispatch's scratch (split-K
                                            planes, split-KV partials and work lists, expert lists), this schedule */
     size_t peak_live_bytes_sequential;  /* the same for the sequential order */
@@ -308,10 +309,51 @@ typedef struct {
     int max_ref_count;                  /* most dispatches reading one region */
     int n_resharded;                    /* regions written and read at different numbers of micro-batches (split form ->
                                            merge form or back): served in place, zero copies */
+    size_t workspace_bytes_schedule;    /* dyn_schedule_workspace_bytes: what a forward with this schedule really needs */
 } dyn_memory_report;
 
 dyn_status dyn_schedule_memory(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched,
                                dyn_memory_report *out);
+
+/* The workspace one schedule needs for one batch shape (host only; 0 if the schedule is not
+ * legal).  The backend knows every intermediate's producers and consumers (Section 3.3.1,
+ * Algorithm 1), hence when its memory is free again: each intermediate tensor lives from its
+ * first producer to the end of its last consumer over all micro-batches, a dispatch's scratch
+ * (split-K planes, split-KV partials, expert lists) while that dispatch may run - both as the
+ * streams allow: what a dispatch is the last to touch stays alive until the next dispatch on
+ * its stream is issued - and regions that are never alive together share bytes (placed largest
+ * first at the lowest free offset).  dyn_layer_forward lays the workspace out this way and
+ * accepts any workspace of at least this size; the more micro-batches run side by side, the
+ * less is shared (the peak-memory cost of overlapping, Section 2.1). */
+size_t dyn_schedule_workspace_bytes(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched);
+
+/* The regions of that layout, for inspection and tests.  live_slots bit t = alive while slot t
+ * of the layer's issue order (dyn_schedule.slots; the sequential order's chain) runs, in any
+ * layer; stream = partition * DYN_MAX_STREAMS + stream of the dispatch a scratch region belongs
+ * to, -1 for tensors.  Two regions never overlap in memory if their live_slots intersect, or if
+ * they are scratch of dispatches on different streams (which may run at the same time whatever
+ * the issue order).  With more than one stream every tensor is alive throughout.  Writes at most
+ * capacity records, *n_out = number of regions. */
+enum {
+    DYN_REGION_H = 0,          /* RMSNorm outputs (both norms share it) */
+    DYN_REGION_QKV = 1, DYN_REGION_ATTN = 2, DYN_REGION_X2 = 3,
+    DYN_REGION_GU = 4,         /* [gate | up] when the SiLU gate is a kernel of its own */
+    DYN_REGION_ACT = 5,
+    DYN_REGION_ROUTING = 6,    /* MoE: selected experts and weights */
+    DYN_REGION_XA = 7, DYN_REGION_XB = 8,   /* outputs of odd / even layers feeding the next layer */
+    DYN_REGION_PLAN = 9,       /* attention work lists */
+    DYN_REGION_PLANES = 10, DYN_REGION_PART_O = 11, DYN_REGION_PART_ML = 12, DYN_REGION_LISTS = 13,
+    DYN_REGION_MOE_PLANES = 14,   /* scratch of one dispatch (slot >= 0) */
+    DYN_REGION_KINDS = 15
+};
+typedef struct {
+    int kind, slot;            /* slot = -1 for tensors */
+    int stream;
+    size_t offset, bytes;
+    uint64_t live_slots[2];
+} dyn_region;
+dyn_status dyn_schedule_regions(const dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, dyn_region *out,
+                                int capacity, int *n_out);
 
 /* ---- Measured tuning of micro-batch sizes and CU partitions (Section 2.1; Section 5.3.4) -
  *
@@ -344,7 +386,7 @@ typedef struct {
 } dyn_tune_candidate;
 
 typedef struct {
-    int max_k;          /* largest number of micro-batches tried, 2..4 (0 = 2) */
+    int max_k;          /* largest number of micro-batches enumerated, 2..4 (0 = 2); dyn_tune itself times two */
     int partitions;     /* CU-partition sizes tried: 0 none, 1 half | half, 2 adds 3/4 | 1/4, 3 adds 1/4 | 3/4 */
     int n_cus;          /* CUs of the device (0 = 256); dyn_tune overwrites it with the device's count */
     int warmup, iters;  /* per candidate: untimed forwards, then three timed runs of iters forwards issued
@@ -380,8 +422,9 @@ dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_
  * as one forward leaves them) and records the winner into s / *out.  s must have been
  * created for this batch's structure.  table (may be NULL) receives the candidates with
  * their times, at most capacity of them.  DYN_ERR_HIP if even the sequential order fails;
- * DYN_ERR_UNSUPPORTED for opt->max_k > 3 (four micro-batches can be enumerated and
- * recorded with the two calls above, but are not part of the device search). */
+ * DYN_ERR_UNSUPPORTED for opt->max_k > 2 (three and four micro-batches can be enumerated and
+ * recorded with the two calls above and run as explicit schedules, but are not part of the
+ * device search). */
 dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const int32_t *ctx_len_host, const dyn_tune_options *opt,
                     void *hip_stream, dyn_scheduler *s, dyn_schedule *out, dyn_tune_result *result,
                     dyn_tune_candidate *table, int capacity);

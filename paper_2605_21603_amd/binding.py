@@ -64,10 +64,20 @@ class dyn_policy_choice(C.Structure):
 
 class dyn_memory_report(C.Structure):
     _fields_ = [("workspace_bytes", C.c_size_t), ("peak_live_bytes", C.c_size_t), ("peak_live_bytes_sequential", C.c_size_t),
-                ("peak_at_dispatch", C.c_int), ("n_regions", C.c_int), ("max_ref_count", C.c_int), ("n_resharded", C.c_int)]
+                ("peak_at_dispatch", C.c_int), ("n_regions", C.c_int), ("max_ref_count", C.c_int), ("n_resharded", C.c_int),
+                ("workspace_bytes_schedule", C.c_size_t)]
 
     def as_dict(self) -> dict:
         return {n: getattr(self, n) for n, _ in self._fields_}
+
+
+class dyn_region(C.Structure):
+    _fields_ = [("kind", C.c_int), ("slot", C.c_int), ("stream", C.c_int), ("offset", C.c_size_t), ("bytes", C.c_size_t),
+                ("live_slots", C.c_uint64 * 2)]
+
+
+REGION_NAMES = ["h", "qkv", "attn", "x2", "gu", "act", "routing", "xa", "xb", "plan", "planes", "part_o", "part_ml", "lists",
+                "moe_planes"]
 
 
 class dyn_tune_candidate(C.Structure):
@@ -98,7 +108,8 @@ EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes",
            "dyn_layer_prepare", "dyn_layer_release_graphs", "dyn_layer_forward", "dyn_layer_forward_noalloc", "dyn_layer_set_profiling", "dyn_layer_get_slot_times", "dyn_last_error",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
-           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_probe_hbm_read"]
+           "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_schedule_workspace_bytes",
+           "dyn_schedule_regions", "dyn_probe_hbm_read"]
 
 _lib = None
 
@@ -134,6 +145,9 @@ def lib() -> C.CDLL:
         l.dyn_scheduler_finish.argtypes = [C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_policy_auto.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p, C.c_void_p]
         l.dyn_schedule_memory.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_schedule_workspace_bytes.restype = C.c_size_t
+        l.dyn_schedule_workspace_bytes.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
+        l.dyn_schedule_regions.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_tune_candidates.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_int]
         l.dyn_tune_record.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_int, C.c_void_p]
         l.dyn_tune.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p, C.c_void_p,
@@ -382,6 +396,21 @@ class DynLayer:
         _check(lib().dyn_schedule_memory(self.handle, C.addressof(batch), C.addressof(sc), C.byref(rep)))
         return rep.as_dict()
 
+    def schedule_workspace_bytes(self, batch: dyn_batch, sched: Schedule) -> int:
+        """Workspace bytes a forward of this batch shape with this schedule needs (host only)."""
+        sc = sched.to_c()
+        return lib().dyn_schedule_workspace_bytes(self.handle, C.addressof(batch), C.addressof(sc))
+
+    def schedule_regions(self, batch: dyn_batch, sched: Schedule) -> List[dict]:
+        """The regions of that layout: kind, slot, offset, bytes, set of issue slots during which it is alive."""
+        sc = sched.to_c()
+        n = C.c_int(0)
+        _check(lib().dyn_schedule_regions(self.handle, C.addressof(batch), C.addressof(sc), None, 0, C.addressof(n)))
+        arr = (dyn_region * max(1, n.value))()
+        _check(lib().dyn_schedule_regions(self.handle, C.addressof(batch), C.addressof(sc), C.cast(arr, C.c_void_p), n.value, C.addressof(n)))
+        return [dict(kind=REGION_NAMES[a.kind], slot=a.slot, stream=a.stream, offset=a.offset, bytes=a.bytes,
+                     live=a.live_slots[0] | (a.live_slots[1] << 64)) for a in arr[:n.value]]
+
     def prepare(self, sched: Schedule) -> None:
         """Creates the schedule's side streams now (synchronises the device for CU-masked ones)."""
         sc = sched.to_c()
@@ -430,7 +459,9 @@ class DeviceStep:
     """Device copies of one generated step (workloads.gen.generate output) and the dyn_batch
     describing them.  Layer caches are stacked so that kv_layer_stride is uniform."""
 
-    def __init__(self, layer: DynLayer, data: dict, device="cuda:0"):
+    def __init__(self, layer: DynLayer, data: dict, device="cuda:0", sched: Optional["Schedule"] = None, guard: int = 0):
+        """sched: size the workspace for this schedule alone (dyn_schedule_workspace_bytes) instead of
+        for any schedule; guard: extra bytes behind the workspace that the library is not told about."""
         dev = torch.device(device)
         self.x = data["x"].to(dev)
         self.y = torch.empty_like(self.x)
@@ -442,13 +473,16 @@ class DeviceStep:
         self.q_start_host = np.ascontiguousarray(data["q_start"], dtype=np.int32)
         n_tokens, n_seqs = self.x.shape[0], len(self.q_start_host) - 1
         max_pages = int(data["block_table"].shape[1])
-        nbytes = layer.workspace_bytes(n_tokens, max_pages)
-        self.workspace = torch.empty(nbytes + 256, dtype=torch.uint8, device=dev)
-        ws_ptr = (self.workspace.data_ptr() + 255) & ~255
         stride = self.k_cache[0].numel() * self.k_cache.element_size()
         self.batch = dyn_batch(n_tokens, n_seqs, _ptr(self.x), _ptr(self.y), _ptr(self.seq_of_token),
                                _ptr(self.pos_of_token), _ptr(self.block_table), max_pages, _ptr(self.q_start_host),
-                               _ptr(self.k_cache), _ptr(self.v_cache), stride, ws_ptr, nbytes)
+                               _ptr(self.k_cache), _ptr(self.v_cache), stride, None, 0)
+        nbytes = layer.workspace_bytes(n_tokens, max_pages) if sched is None else layer.schedule_workspace_bytes(self.batch, sched)
+        self.workspace = torch.empty(nbytes + 256 + guard, dtype=torch.uint8, device=dev)
+        ws_ptr = (self.workspace.data_ptr() + 255) & ~255
+        self.workspace_offset = ws_ptr - self.workspace.data_ptr()
+        self.batch.workspace = ws_ptr
+        self.batch.workspace_bytes = nbytes
         # uploads were queued on torch's current stream; forwards run on other, non-blocking
         # streams, so wait here until the inputs have landed
         torch.cuda.synchronize(dev)

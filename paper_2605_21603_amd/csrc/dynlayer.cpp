@@ -61,13 +61,30 @@ struct Dispatch {
 
 constexpr int kMaxRetiredGraphs = 8, kMaxRetiredBranches = 8;   // evicted executables still waiting for their last replay
 
+// Where everything lives inside the caller's workspace for one forward.  Row-indexed tensors
+// ([tokens, width], a micro-batch is a row range) have one region each; scratch that exists only
+// while a dispatch runs (split-K planes, split-KV partials, expert lists) has one region per slot
+// of the layer's issue order, the same in every layer.  Regions whose lifetimes never overlap
+// under the schedule share bytes (plan_layout).
+struct SlotScratch {
+    size_t planes, part_o, part_ml, lists, moe_planes;   // byte offsets; unused ones are 0
+};
+
 struct WsLayout {
-    size_t h, qkv, attn, x2, gu, act, xa, xb, part_o, part_ml, plan, total;
-    size_t sel, wgt, lists_gu, lists_down, moe_planes;   // MoE: routing, per-dispatch expert lists, down-projection planes
+    size_t h, qkv, attn, x2, gu, act, xa, xb, plan, total;
+    size_t sel, wgt;             // MoE routing: selected experts and their weights per token
     int ld_h, ld_attn, ld_act;   // padded row strides (elements) of the buffers the projections read
-    size_t gemm_partial[4];   // split-K planes of the qkv, o, gate/up and down projections: operators of
-                              // different micro-batches run concurrently, so each has its own
     int max_chunks;
+    std::vector<SlotScratch> slot;
+};
+
+// One region of the layout, for dyn_schedule_regions and the placement itself.
+struct Region {
+    int kind, slot;              // DYN_REGION_*; slot of the issue order for scratch, -1 for tensors
+    size_t bytes, offset;
+    std::vector<char> live;      // per slot of the issue order (lifetimes folded over the layers)
+    bool always = false;         // alive for the whole forward
+    int stream_key = -1;         // scratch: the stream its dispatch runs on
 };
 
 struct GraphEntry {
@@ -106,51 +123,104 @@ size_t esize(const dyn_layer_config &c) { return c.dtype == DYN_F32 ? 4 : 2; }
 
 int qkv_width(const dyn_layer_config &c) { return (c.n_q_heads + 2 * c.n_kv_heads) * c.head_dim; }
 
-WsLayout ws_layout(const dyn_layer *L, int T, int max_pages) {
+struct Sizes {                  // bytes of each whole-batch tensor, and the row strides
+    size_t h, qkv, attn, x2, gu, act, xa, xb, plan, sel, wgt;
+    int ld_h, ld_attn, ld_act, max_chunks;
+};
+
+Sizes tensor_sizes(const dyn_layer *L, int T, int max_pages) {
     const dyn_layer_config &c = L->cfg;
     const size_t e = esize(c), t = (size_t)std::max(T, 0);
-    WsLayout w{};
-    size_t off = 0;
-    auto take = [&](size_t bytes) { size_t o = off; off = align_up(off + bytes); return o; };
     const int pairs = c.n_experts ? c.top_k : 1;
+    Sizes z{};
     // Rows of a GEMM input are read 64 bytes at a time by 16 lanes on 16 different rows; with a
     // power-of-two row pitch those land in one L2 channel.  256 bytes of padding per row walks
     // consecutive rows across the channels.
     const int pad = (int)(256 / e);
-    w.ld_h = c.hidden + pad;
-    w.ld_attn = c.n_q_heads * c.head_dim + pad;
-    w.ld_act = c.mlp_inter + pad;
-    w.h = take(t * w.ld_h * e);
-    w.qkv = take(t * qkv_width(c) * e);
-    w.attn = take(t * w.ld_attn * e);
-    w.x2 = take(t * c.hidden * e);
+    z.ld_h = c.hidden + pad;
+    z.ld_attn = c.n_q_heads * c.head_dim + pad;
+    z.ld_act = c.mlp_inter + pad;
+    z.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
+    z.h = t * z.ld_h * e;
+    z.qkv = t * qkv_width(c) * e;
+    z.attn = t * z.ld_attn * e;
+    z.x2 = t * c.hidden * e;
     // the [gate | up] intermediate exists only when the SiLU gate is not applied in the projection's epilogue
-    w.gu = take(dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden) ? 0 : t * pairs * 2 * c.mlp_inter * e);
-    w.act = take(t * pairs * w.ld_act * e);
-    w.xa = take(c.n_layers > 1 ? t * c.hidden * e : 0);
-    w.xb = take(c.n_layers > 2 ? t * c.hidden * e : 0);
+    z.gu = dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden) ? 0 : t * pairs * 2 * c.mlp_inter * e;
+    z.act = t * pairs * z.ld_act * e;
+    z.xa = c.n_layers > 1 ? t * c.hidden * e : 0;
+    z.xb = c.n_layers > 2 ? t * c.hidden * e : 0;
+    z.plan = (t * z.max_chunks + 2 * t) * 4 * sizeof(int32_t);   // per dispatch: two lists of 2 header words + 2 per entry, one chunk size per token
+    z.sel = c.n_experts ? t * c.top_k * sizeof(int32_t) : 0;
+    z.wgt = c.n_experts ? t * c.top_k * sizeof(float) : 0;
+    return z;
+}
+
+// Scratch a dispatch over `rows` token rows holds while it runs (bytes; 0 = none).
+struct ScratchBytes { size_t planes, part_o, part_ml, lists, moe_planes; };
+
+ScratchBytes dispatch_scratch(const dyn_layer *L, const Sizes &z, int op, int rows) {
+    const dyn_layer_config &c = L->cfg;
+    ScratchBytes k{};
+    if (rows <= 0) return k;
+    const size_t r = (size_t)rows;
+    const int H = c.hidden, I = c.mlp_inter, NQKV = qkv_width(c), NQ = c.n_q_heads * c.head_dim;
+    const bool moe = c.n_experts > 0, gated = dyn::gemm_gated_supported(c.dtype, 2 * I, H);
+    auto planes = [&](int N, int K) {
+        return dyn::gemm_uses_plane_buffer(c.dtype, rows, N, K) ? (size_t)dyn::gemm_split_k(c.dtype, N, K) * r * N * sizeof(float) : 0;
+    };
+    switch (op) {
+        case DYN_OP_QKV: k.planes = planes(NQKV, H); break;
+        case DYN_OP_OPROJ: k.planes = planes(H, NQ); break;
+        case DYN_OP_ATTN:
+            k.part_o = r * c.n_q_heads * z.max_chunks * c.head_dim * sizeof(float);
+            k.part_ml = r * c.n_q_heads * z.max_chunks * 2 * sizeof(float);
+            break;
+        case DYN_OP_GATE_UP:
+            if (moe) {
+                k.lists = r * c.top_k * 2 * c.n_experts * sizeof(int32_t);   // E counts + E lists of up to rows * top_k pairs
+                const int S = dyn::gemm_split_k(c.dtype, 2 * I, H, c.n_experts);
+                if (!gated && S > 1) k.planes = (size_t)S * r * c.top_k * 2 * I * sizeof(float);
+            } else if (!gated) {
+                k.planes = planes(2 * I, H);
+            }
+            break;
+        case DYN_OP_DOWN:
+            if (moe) {
+                k.lists = r * c.top_k * 2 * c.n_experts * sizeof(int32_t);
+                k.moe_planes = (size_t)dyn::gemm_split_k(c.dtype, H, I, c.n_experts) * r * c.top_k * H * sizeof(float);
+            } else {
+                k.planes = planes(H, I);
+            }
+            break;
+        default: break;
+    }
+    return k;
+}
+
+// Upper bound of the workspace any legal schedule of a batch of T tokens needs: every tensor and,
+// for every operator, scratch for all T rows at once (a schedule dispatches each (operator,
+// micro-batch) once per layer, so its dispatches' scratch adds up to at most that), nothing shared.
+size_t ws_bound(const dyn_layer *L, int T, int max_pages) {
+    const dyn_layer_config &c = L->cfg;
+    const Sizes z = tensor_sizes(L, T, max_pages);
+    const size_t t = (size_t)std::max(T, 0);
+    const int pairs = c.n_experts ? c.top_k : 1;
+    size_t total = 0;
+    for (size_t v : {z.h, z.qkv, z.attn, z.x2, z.gu, z.act, z.xa, z.xb, z.plan, z.sel, z.wgt}) total += align_up(v);
     const int widths[4][2] = {{qkv_width(c), c.hidden}, {c.hidden, c.n_q_heads * c.head_dim},
                               {2 * c.mlp_inter, c.hidden}, {c.hidden, c.mlp_inter}};
     for (int i = 0; i < 4; ++i) {
         const int S = dyn::gemm_split_k(c.dtype, widths[i][0], widths[i][1], i >= 2 && c.n_experts ? c.n_experts : 1);
         const size_t prow = (i == 2 ? (size_t)pairs : 1) * t;     // the MoE gate/up projection has a row per (token, expert)
-        w.gemm_partial[i] = take(S > 1 ? (size_t)S * prow * widths[i][0] * sizeof(float) : 0);
+        total += align_up(S > 1 ? (size_t)S * prow * widths[i][0] * sizeof(float) : 0);
     }
-    w.max_chunks = std::max(1, (std::max(max_pages, 1) + L->chunk_pages - 1) / L->chunk_pages);
-    w.part_o = take(t * c.n_q_heads * w.max_chunks * c.head_dim * sizeof(float));
-    w.part_ml = take(t * c.n_q_heads * w.max_chunks * 2 * sizeof(float));
-    w.plan = take((t * w.max_chunks + 2 * t) * 4 * sizeof(int32_t));   // per dispatch: two lists of 2 header words + 2 per entry, one chunk size per token
+    total += align_up(t * c.n_q_heads * z.max_chunks * c.head_dim * sizeof(float)) + align_up(t * c.n_q_heads * z.max_chunks * 2 * sizeof(float));
     if (c.n_experts) {
         const int Sd = dyn::gemm_split_k(c.dtype, c.hidden, c.mlp_inter, c.n_experts);
-        w.sel = take(t * c.top_k * sizeof(int32_t));
-        w.wgt = take(t * c.top_k * sizeof(float));
-        // a dispatch over rows r0.. uses ints [r0 * top_k * 2E, ...): E counts + E lists of up to rows * top_k pairs
-        w.lists_gu = take(t * c.top_k * 2 * c.n_experts * sizeof(int32_t));
-        w.lists_down = take(t * c.top_k * 2 * c.n_experts * sizeof(int32_t));
-        w.moe_planes = take((size_t)Sd * t * c.top_k * c.hidden * sizeof(float));
+        total += 2 * align_up(t * c.top_k * 2 * c.n_experts * sizeof(int32_t)) + align_up((size_t)Sd * t * c.top_k * c.hidden * sizeof(float));
     }
-    w.total = off;
-    return w;
+    return total + (size_t)256 * 5 * DYN_N_OPS * DYN_MAX_NANO;      // alignment of per-dispatch scratch regions
 }
 
 const int kDenseChain[] = {DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ,
@@ -295,6 +365,189 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
     return DYN_OK;
 }
 
+// Issue order is a timeline only within a stream: what is issued on another stream after
+// dispatch i may run beside it.  So whatever dispatch i is the last to touch stays alive until
+// the next dispatch on i's own stream is issued (that one cannot start before i ends):
+// until[i] = index of the last dispatch issued before that one.
+std::vector<int> alive_until(const std::vector<Dispatch> &plan) {
+    std::vector<int> until(plan.size());
+    int next_on[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
+    std::fill(next_on, next_on + (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS, (int)plan.size());
+    for (int i = (int)plan.size() - 1; i >= 0; --i) {
+        until[i] = next_on[plan[i].key()] - 1;
+        next_on[plan[i].key()] = i;
+    }
+    return until;
+}
+
+// The workspace layout of one plan (Section 3.3.1, Algorithm 1: the backend knows every
+// intermediate's producers and consumers, so it knows when its memory is free again).  Two
+// regions may share bytes only if everything that touches one has finished before anything
+// touches the other, and what orders dispatches on the device is stream order and events, not
+// the order of issue.  Two cases are safe by construction and are the ones used:
+//   * All dispatches on one stream (the sequential order, or micro-batches issued on a single
+//     stream): issue order is execution order.  Every region gets the set of issue slots during
+//     which it is alive - a tensor from its first producer to its last consumer over all
+//     micro-batches, a dispatch's scratch while the dispatch runs - folded over the layers, which
+//     all issue the same slots, and regions alive at disjoint times share bytes.
+//   * Several streams: micro-batches advance independently, so no tensor is ever known to be
+//     dead while another micro-batch may still be anywhere in the chain: tensors keep regions
+//     of their own.  The scratch of two dispatches on the SAME stream still never exists at the
+//     same time, so each stream's dispatches share one scratch arena; different streams' do not.
+// Regions are placed largest first at the lowest offset where they overlap no region they
+// conflict with.  The more runs side by side, the less can be shared: the peak-memory cost of
+// overlapping that Section 2.1 names.
+WsLayout plan_layout(const dyn_layer *L, const dyn_batch *b, const std::vector<Dispatch> &plan, std::vector<Region> *regions_out) {
+    const dyn_layer_config &c = L->cfg;
+    const Sizes z = tensor_sizes(L, b->n_tokens, b->max_pages_per_seq);
+    WsLayout w{};
+    w.ld_h = z.ld_h; w.ld_attn = z.ld_attn; w.ld_act = z.ld_act; w.max_chunks = z.max_chunks;
+    const int P = (int)plan.size(), n_slots = P / std::max(c.n_layers, 1);
+    w.slot.assign((size_t)std::max(n_slots, 0), SlotScratch{});
+    if (P == 0 || n_slots == 0) return w;
+    const std::vector<int> until = alive_until(plan);
+    const bool moe = c.n_experts > 0, gated = dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden);
+
+    bool single_stream = true;
+    {
+        int key = -1;
+        for (const Dispatch &d : plan) {
+            if (d.noop) continue;
+            if (key < 0) key = d.key();
+            single_stream = single_stream && d.key() == key;
+        }
+    }
+    std::vector<Region> regions;
+    auto add = [&](int kind, int slot, size_t bytes, bool always) {
+        always = always || (!single_stream && slot < 0);            // several streams: tensors are never known dead
+        regions.push_back(Region{kind, slot, bytes, 0, std::vector<char>((size_t)n_slots, always ? 1 : 0), always,
+                                 slot >= 0 ? plan[slot].key() : -1});
+        return (int)regions.size() - 1;
+    };
+    auto mark = [&](int region, int from, int to) {           // alive over dispatches from..to (global issue indices)
+        Region &r = regions[region];
+        if (to - from + 1 >= n_slots) { std::fill(r.live.begin(), r.live.end(), 1); return; }
+        for (int t = from; t <= to; ++t) r.live[t % n_slots] = 1;
+    };
+    // slot that dispatches (operator, micro-batch); the same in every layer
+    int slot_of[DYN_N_OPS][DYN_MAX_NANO];
+    for (auto &r : slot_of) std::fill(r, r + DYN_MAX_NANO, -1);
+    int k = 0;
+    for (int j = 0; j < n_slots; ++j)
+        for (int nb = plan[j].nano; nb < plan[j].nano + plan[j].n_nano; ++nb) { slot_of[plan[j].op][nb] = j; k = std::max(k, nb + 1); }
+
+    struct TensorDef { int kind; size_t bytes; int producer, last_consumer; bool present; };
+    const TensorDef defs[] = {
+        {DYN_REGION_H, z.h, DYN_OP_NORM1, DYN_OP_QKV, true},
+        {DYN_REGION_H, z.h, DYN_OP_NORM2, DYN_OP_GATE_UP, true},                   // the second norm's output takes the first one's place
+        {DYN_REGION_QKV, z.qkv, DYN_OP_QKV, DYN_OP_ATTN, true},
+        {DYN_REGION_ATTN, z.attn, DYN_OP_ATTN, DYN_OP_OPROJ, true},
+        {DYN_REGION_X2, z.x2, DYN_OP_OPROJ, DYN_OP_DOWN, true},
+        {DYN_REGION_GU, z.gu, DYN_OP_GATE_UP, DYN_OP_SILU, !gated},
+        {DYN_REGION_ACT, z.act, gated ? DYN_OP_GATE_UP : DYN_OP_SILU, DYN_OP_DOWN, true},
+        {DYN_REGION_ROUTING, align_up(z.sel) + z.wgt, DYN_OP_ROUTE, DYN_OP_DOWN, moe},
+    };
+    int region_of_kind[DYN_REGION_KINDS];
+    std::fill(region_of_kind, region_of_kind + DYN_REGION_KINDS, -1);
+    for (const TensorDef &d : defs) {
+        if (!d.present || !d.bytes) continue;
+        int r = region_of_kind[d.kind];
+        if (r < 0) r = region_of_kind[d.kind] = add(d.kind, -1, d.bytes, false);
+        for (int l = 0; l < c.n_layers; ++l) {
+            int from = P, to = -1;
+            for (int nb = 0; nb < k; ++nb) {
+                from = std::min(from, l * n_slots + slot_of[d.producer][nb]);
+                to = std::max(to, until[l * n_slots + slot_of[d.last_consumer][nb]]);
+            }
+            mark(r, from, to);
+        }
+    }
+    // layer outputs that feed the next layer alternate between two buffers; the work lists are built
+    // by the first layer and walked by all: alive throughout
+    const int r_xa = z.xa ? add(DYN_REGION_XA, -1, z.xa, true) : -1;
+    const int r_xb = z.xb ? add(DYN_REGION_XB, -1, z.xb, true) : -1;
+    const int r_plan = z.plan ? add(DYN_REGION_PLAN, -1, z.plan, true) : -1;
+    // scratch per slot
+    struct SlotRegions { int planes = -1, part_o = -1, part_ml = -1, lists = -1, moe_planes = -1; };
+    std::vector<SlotRegions> sr((size_t)n_slots);
+    for (int j = 0; j < n_slots; ++j) {
+        const Dispatch &d = plan[j];
+        if (d.noop) continue;
+        const ScratchBytes kb = dispatch_scratch(L, z, d.op, d.r1 - d.r0);
+        if (kb.planes) sr[j].planes = add(DYN_REGION_PLANES, j, kb.planes, false);
+        if (kb.part_o) sr[j].part_o = add(DYN_REGION_PART_O, j, kb.part_o, false);
+        if (kb.part_ml) sr[j].part_ml = add(DYN_REGION_PART_ML, j, kb.part_ml, false);
+        if (kb.lists && !(d.op == DYN_OP_DOWN && d.lists_ready)) sr[j].lists = add(DYN_REGION_LISTS, j, kb.lists, false);
+        if (kb.moe_planes) sr[j].moe_planes = add(DYN_REGION_MOE_PLANES, j, kb.moe_planes, false);
+        for (int l = 0; l < c.n_layers; ++l) {
+            const int i = l * n_slots + j;
+            for (int r : {sr[j].planes, sr[j].part_o, sr[j].part_ml, sr[j].lists, sr[j].moe_planes})
+                if (r >= 0) mark(r, i, single_stream ? until[i] : i);
+        }
+    }
+    // a down projection that reads the expert lists of the gate/up dispatch over the same rows keeps them alive
+    std::vector<int> lists_from((size_t)n_slots, -1);
+    for (int j = 0; j < n_slots; ++j) {
+        const Dispatch &d = plan[j];
+        if (d.op != DYN_OP_DOWN || !d.lists_ready || d.noop) continue;
+        for (int g = 0; g < n_slots; ++g)
+            if (plan[g].op == DYN_OP_GATE_UP && !plan[g].noop && plan[g].r0 == d.r0 && plan[g].r1 == d.r1) lists_from[j] = g;
+        if (lists_from[j] >= 0 && sr[lists_from[j]].lists >= 0) {
+            Region &lr = regions[sr[lists_from[j]].lists];
+            if (single_stream) {
+                for (int l = 0; l < c.n_layers; ++l) mark(sr[lists_from[j]].lists, l * n_slots + lists_from[j], until[l * n_slots + j]);
+            } else {                       // read later by a dispatch that may run on another stream: kept throughout
+                lr.always = true;
+                std::fill(lr.live.begin(), lr.live.end(), 1);
+            }
+        }
+    }
+
+    // placement: largest first, lowest offset that overlaps no placed region alive at the same time
+    std::vector<int> order(regions.size());
+    for (size_t i = 0; i < order.size(); ++i) order[i] = (int)i;
+    std::stable_sort(order.begin(), order.end(), [&](int a, int bb) { return regions[a].bytes > regions[bb].bytes; });
+    std::vector<int> placed;
+    size_t total = 0;
+    for (int ri : order) {
+        Region &r = regions[ri];
+        std::vector<std::pair<size_t, size_t>> busy;            // [offset, end) of placed regions that conflict
+        for (int pi : placed) {
+            const Region &q = regions[pi];
+            // scratch of dispatches on different streams may exist at the same time whatever the issue order
+            bool conflict = r.always || q.always || (!single_stream && r.stream_key != q.stream_key);
+            for (int t = 0; t < n_slots && !conflict; ++t) conflict = r.live[t] && q.live[t];
+            if (conflict) busy.push_back({q.offset, q.offset + align_up(q.bytes)});
+        }
+        std::sort(busy.begin(), busy.end());
+        size_t off = 0;
+        for (const auto &iv : busy)
+            if (iv.first < off + align_up(r.bytes) && iv.second > off) off = iv.second;     // overlaps the candidate: move past it
+        r.offset = off;
+        total = std::max(total, off + align_up(r.bytes));
+        placed.push_back(ri);
+    }
+    w.total = total;
+    auto off_of = [&](int region) { return region >= 0 ? regions[region].offset : (size_t)0; };
+    w.h = off_of(region_of_kind[DYN_REGION_H]);
+    w.qkv = off_of(region_of_kind[DYN_REGION_QKV]);
+    w.attn = off_of(region_of_kind[DYN_REGION_ATTN]);
+    w.x2 = off_of(region_of_kind[DYN_REGION_X2]);
+    w.gu = off_of(region_of_kind[DYN_REGION_GU]);
+    w.act = off_of(region_of_kind[DYN_REGION_ACT]);
+    w.sel = off_of(region_of_kind[DYN_REGION_ROUTING]);
+    w.wgt = w.sel + align_up(z.sel);
+    w.xa = off_of(r_xa);
+    w.xb = off_of(r_xb);
+    w.plan = off_of(r_plan);
+    for (int j = 0; j < n_slots; ++j) {
+        const int lists_region = lists_from[j] >= 0 ? sr[lists_from[j]].lists : sr[j].lists;
+        w.slot[j] = SlotScratch{off_of(sr[j].planes), off_of(sr[j].part_o), off_of(sr[j].part_ml), off_of(lists_region), off_of(sr[j].moe_planes)};
+    }
+    if (regions_out) *regions_out = std::move(regions);
+    return w;
+}
+
 void destroy_graph_entry(GraphEntry &g) {
     (void)hipGraphExecDestroy(g.exec);
     (void)hipGraphDestroy(g.graph);
@@ -340,7 +593,7 @@ dyn_status ensure_stream(dyn_layer *L, const dyn_schedule *s, int key, hipStream
 }
 
 dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, const WsLayout &ws, const Dispatch &d,
-                     hipStream_t st, hipEvent_t mid, hipEvent_t pre) {
+                     const SlotScratch &sc, hipStream_t st, hipEvent_t mid, hipEvent_t pre) {
     const dyn_layer_config &c = L->cfg;
     const dyn_layer_weights &w = L->w[d.layer];
     const size_t e = esize(c);
@@ -352,14 +605,14 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
     const char *x_in = d.layer == 0 ? (const char *)b->x : (d.layer % 2 ? base + ws.xa : base + ws.xb);
     char *x_out = d.layer == nl - 1 ? (char *)b->y : (d.layer % 2 ? base + ws.xb : base + ws.xa);
     auto rowp = [&](const char *p, int width) { return p + (size_t)d.r0 * width * e; };
-    const size_t T = (size_t)b->n_tokens;
     dyn::AttnShape sh{c.n_q_heads, c.n_kv_heads, c.head_dim, c.page_size, b->max_pages_per_seq, L->chunk_pages, ws.max_chunks, 0};
     if (d.partition > 0 && s->mode == DYN_SCHED_EXPLICIT)
         for (int i = 0; i < s->cu_mask_words; ++i)
             sh.n_cus += __builtin_popcount(s->cu_masks[(d.partition - 1) * s->cu_mask_words + i]);
     char *kc = (char *)b->k_cache + (size_t)d.layer * b->kv_layer_stride;
     char *vc = (char *)b->v_cache + (size_t)d.layer * b->kv_layer_stride;
-    auto partial = [&](int i, int width) { return (float *)(base + ws.gemm_partial[i]) + (size_t)d.r0 * width; };
+    // the dispatch's own scratch: split-K planes of `rows` rows each
+    float *const planes = (float *)(base + sc.planes);
     hipError_t err = hipSuccess;
     switch (d.op) {
         case DYN_OP_NORM1:
@@ -367,7 +620,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
             break;
         case DYN_OP_QKV:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_qkv, nullptr, (void *)rowp(base + ws.qkv, NQKV),
-                                   partial(0, NQKV), T * NQKV, rows, NQKV, H, st, mid);
+                                   planes, (size_t)rows * NQKV, rows, NQKV, H, st, mid);
             break;
         case DYN_OP_ROPE_KV:
             err = dyn::launch_rope_kv(c.dtype, (void *)rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0,
@@ -376,14 +629,13 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
         case DYN_OP_ATTN:
             err = dyn::launch_attention(c.dtype, rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0, b->pos_of_token + d.r0,
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
-                                        (float *)(base + ws.part_o) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * c.head_dim,
-                                        (float *)(base + ws.part_ml) + (size_t)d.r0 * c.n_q_heads * ws.max_chunks * 2,
+                                        (float *)(base + sc.part_o), (float *)(base + sc.part_ml),
                                         (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 2) * 4, d.any_multi, sh, rows, st, mid, pre,
                                         d.layer > 0);   // every layer dispatches the same row ranges: layer 0 built the work lists
             break;
         case DYN_OP_OPROJ:
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
-                                   partial(1, H), T * H, rows, H, NQ, st, mid);
+                                   planes, (size_t)rows * H, rows, H, NQ, st, mid);
             break;
         case DYN_OP_NORM2:
             err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
@@ -397,7 +649,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
             if (c.n_experts) {
                 // rows of the grouped projections are (token, rank) pairs p = t * top_k + rank
                 const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
-                int32_t *counts = (int32_t *)(base + ws.lists_gu) + (size_t)pair0 * 2 * c.n_experts;
+                int32_t *counts = (int32_t *)(base + sc.lists);
                 int32_t *lists = counts + c.n_experts;
                 err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
                 if (err != hipSuccess) break;
@@ -406,8 +658,9 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                     err = dyn::launch_gemm_gated(base + ws.h, ws.ld_h, w.w_gate_up, base + ws.act, ws.ld_act, gr, rows, 2 * I, H, st, mid);
                     break;
                 }
+                // the grouped kernels index planes by pair id: the dispatch's planes start at its first pair
                 err = dyn::launch_gemm_grouped(c.dtype, base + ws.h, ws.ld_h, w.w_gate_up, base + ws.gu,
-                                               (float *)(base + ws.gemm_partial[2]), T * c.top_k * 2 * I, gr, rows, pair0,
+                                               planes - (size_t)pair0 * 2 * I, (size_t)n_pairs * 2 * I, gr, rows, pair0,
                                                n_pairs, 2 * I, H, st, mid);
                 break;
             }
@@ -417,7 +670,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                 break;
             }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_gate_up, nullptr, (void *)rowp(base + ws.gu, 2 * I),
-                                   partial(2, 2 * I), T * 2 * I, rows, 2 * I, H, st, mid);
+                                   planes, (size_t)rows * 2 * I, rows, 2 * I, H, st, mid);
             break;
         case DYN_OP_SILU:
             if (dyn::gemm_gated_supported(c.dtype, 2 * I, H)) break;   // done in the gate/up projection's epilogue
@@ -432,23 +685,24 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
         case DYN_OP_DOWN:
             if (c.n_experts) {
                 const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
-                int32_t *counts = (int32_t *)(base + (d.lists_ready ? ws.lists_gu : ws.lists_down)) + (size_t)pair0 * 2 * c.n_experts;
+                int32_t *counts = (int32_t *)(base + sc.lists);     // its own, or the matching gate/up dispatch's (lists_ready)
                 int32_t *lists = counts + c.n_experts;
                 if (!d.lists_ready) err = dyn::launch_expert_lists((const int32_t *)(base + ws.sel), n_pairs, pair0, c.n_experts, n_pairs, counts, lists, st);
                 if (err != hipSuccess) break;
                 const int Sd = dyn::gemm_split_k(c.dtype, H, I, c.n_experts);
-                const size_t plane = T * c.top_k * H;
+                const size_t plane = (size_t)n_pairs * H;
+                float *const mp = (float *)(base + sc.moe_planes);
                 dyn::GemmGroups gr{counts, lists, n_pairs, 1, c.n_experts, (size_t)H * I, 1};
                 err = dyn::launch_gemm_grouped(c.dtype, base + ws.act, ws.ld_act, w.w_down, nullptr,
-                                               (float *)(base + ws.moe_planes), plane, gr, rows, pair0, n_pairs, H, I, st, mid);
+                                               mp - (size_t)pair0 * H, plane, gr, rows, pair0, n_pairs, H, I, st, mid);
                 if (err != hipSuccess) break;
-                err = dyn::launch_moe_combine(c.dtype, (const float *)(base + ws.moe_planes) + (size_t)pair0 * H, plane, Sd,
+                err = dyn::launch_moe_combine(c.dtype, mp, plane, Sd,
                                               (const float *)(base + ws.wgt) + pair0, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
                                               rows, H, c.top_k, st);
                 break;
             }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, ws.ld_act), ws.ld_act, w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
-                                   partial(3, H), T * H, rows, H, I, st, mid);
+                                   planes, (size_t)rows * H, rows, H, I, st, mid);
             break;
         default:
             return fail(DYN_ERR_UNSUPPORTED, "operator %s has no kernel", op_name(d.op));
@@ -514,7 +768,7 @@ dyn_status run_plan(dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, con
             for (int j = 1; j <= 3; ++j) HIP_TRY(hipEventRecord(L->prof_events[j + 4 * i], st));
         }
         const bool mark = profile && d.r1 > d.r0;
-        dyn_status rc = launch_op(L, b, s, ws, d, st, mark ? L->prof_events[3 + 4 * i] : nullptr,
+        dyn_status rc = launch_op(L, b, s, ws, d, ws.slot[i % ws.slot.size()], st, mark ? L->prof_events[3 + 4 * i] : nullptr,
                                   mark ? L->prof_events[2 + 4 * i] : nullptr);
         if (rc != DYN_OK) return rc;
         if (profile) HIP_TRY(hipEventRecord(L->prof_events[4 + 4 * i], st));
@@ -561,7 +815,7 @@ void analyse_memory(const dyn_layer *L, const dyn_batch *b, const std::vector<Di
                     dyn_memory_report *out, size_t *peak, int *peak_at) {
     const dyn_layer_config &c = L->cfg;
     const size_t e = esize(c);
-    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    const Sizes ws = tensor_sizes(L, b->n_tokens, b->max_pages_per_seq);
     const int n_slots = (int)plan.size() / c.n_layers;
     const bool moe = c.n_experts > 0, gated = dyn::gemm_gated_supported(c.dtype, 2 * c.mlp_inter, c.hidden);
     const int pairs = moe ? c.top_k : 1, H = c.hidden, I = c.mlp_inter, NQKV = qkv_width(c), NQ = c.n_q_heads * c.head_dim;
@@ -582,18 +836,7 @@ void analyse_memory(const dyn_layer *L, const dyn_batch *b, const std::vector<Di
         {gated ? DYN_OP_GATE_UP : DYN_OP_SILU, {DYN_OP_DOWN, -1}, (size_t)pairs * ws.ld_act * e, false, true},
     };
     std::vector<size_t> born(plan.size(), 0), dies(plan.size(), 0), scratch(plan.size(), 0);
-    // Issue order is a timeline only within a stream: what is issued on another stream after
-    // dispatch i may run beside it.  So whatever dispatch i is the last to touch stays alive
-    // until the next dispatch on i's own stream is issued (that one cannot start before i ends).
-    std::vector<int> until(plan.size());
-    {
-        int next_on[(DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS];
-        std::fill(next_on, next_on + (DYN_MAX_PARTITIONS + 1) * DYN_MAX_STREAMS, (int)plan.size());
-        for (int i = (int)plan.size() - 1; i >= 0; --i) {
-            until[i] = next_on[plan[i].key()] - 1;
-            next_on[plan[i].key()] = i;
-        }
-    }
+    const std::vector<int> until = alive_until(plan);      // stream-aware end of what a dispatch is the last to touch
     out->n_regions = out->max_ref_count = out->n_resharded = 0;
     for (int l = 0; l < c.n_layers; ++l)
         for (const Tensor &t : tensors) {
@@ -756,12 +999,35 @@ void dyn_layer_destroy(dyn_layer *L) {
 
 size_t dyn_layer_workspace_bytes(const dyn_layer *L, int max_tokens, int max_pages_per_seq) {
     if (!L || max_tokens < 0 || max_pages_per_seq < 0) return 0;
-    return ws_layout(L, max_tokens, max_pages_per_seq).total;
+    return ws_bound(L, max_tokens, max_pages_per_seq);
 }
 
 dyn_status dyn_schedule_validate(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s) {
     std::vector<Dispatch> plan;
     return build_plan(L, b, s, plan);
+}
+
+size_t dyn_schedule_workspace_bytes(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s) {
+    std::vector<Dispatch> plan;
+    if (build_plan(L, b, s, plan) != DYN_OK) return 0;
+    return plan_layout(L, b, plan, nullptr).total;
+}
+
+dyn_status dyn_schedule_regions(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, dyn_region *out, int capacity, int *n_out) {
+    if (!n_out || capacity < 0 || (capacity > 0 && !out)) return fail(DYN_ERR_INVALID_ARG, "NULL argument");
+    std::vector<Dispatch> plan;
+    dyn_status rc = build_plan(L, b, s, plan);
+    if (rc != DYN_OK) return rc;
+    std::vector<Region> regions;
+    plan_layout(L, b, plan, &regions);
+    *n_out = (int)regions.size();
+    for (int i = 0; i < *n_out && i < capacity; ++i) {
+        const Region &r = regions[i];
+        out[i] = dyn_region{r.kind, r.slot, r.stream_key, r.offset, r.bytes, {0, 0}};
+        for (size_t t = 0; t < r.live.size() && t < 128; ++t)
+            if (r.live[t]) out[i].live_slots[t / 64] |= 1ull << (t % 64);
+    }
+    return DYN_OK;
 }
 
 dyn_status dyn_schedule_memory(const dyn_layer *L, const dyn_batch *b, const dyn_schedule *s, dyn_memory_report *out) {
@@ -770,7 +1036,8 @@ dyn_status dyn_schedule_memory(const dyn_layer *L, const dyn_batch *b, const dyn
     dyn_status rc = build_plan(L, b, s, plan);
     if (rc != DYN_OK) return rc;
     *out = dyn_memory_report{};
-    out->workspace_bytes = ws_layout(L, b->n_tokens, b->max_pages_per_seq).total;
+    out->workspace_bytes = ws_bound(L, b->n_tokens, b->max_pages_per_seq);
+    out->workspace_bytes_schedule = plan_layout(L, b, plan, nullptr).total;
     if (b->n_tokens == 0) return DYN_OK;
     const int32_t whole[2] = {0, b->n_tokens};
     dyn_memory_report seq_report{};
@@ -792,10 +1059,10 @@ dyn_status dyn_layer_forward(dyn_layer *L, const dyn_batch *b, const dyn_schedul
     if (rc != DYN_OK) return rc;
     if (b->n_tokens == 0) return DYN_OK;
     if ((rc = check_batch_tensors(L, b)) != DYN_OK) return rc;
-    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    const WsLayout ws = plan_layout(L, b, plan, nullptr);
     if (!b->workspace || ((uintptr_t)b->workspace & 255)) return fail(DYN_ERR_WORKSPACE, "workspace missing or not 256-byte aligned");
     if (b->workspace_bytes < ws.total)
-        return fail(DYN_ERR_WORKSPACE, "workspace has %zu bytes, %zu needed", b->workspace_bytes, ws.total);
+        return fail(DYN_ERR_WORKSPACE, "workspace has %zu bytes, this schedule needs %zu", b->workspace_bytes, ws.total);
     hipStream_t origin = (hipStream_t)hip_stream;
 
     // every stream the schedule names exists before the first kernel of the forward is issued
@@ -929,7 +1196,7 @@ dyn_status dyn_layer_forward_noalloc(dyn_layer *L, const dyn_batch *b, void *hip
     if (rc != DYN_OK) return rc;
     if (b->n_tokens == 0) return DYN_OK;
     if ((rc = check_batch_tensors(L, b)) != DYN_OK) return rc;
-    const WsLayout ws = ws_layout(L, b->n_tokens, b->max_pages_per_seq);
+    const WsLayout ws = plan_layout(L, b, plan, nullptr);
     if (ws.total > kScratchBytes)
         return fail(DYN_ERR_WORKSPACE, "this batch needs %zu bytes of workspace, the static scratch array holds %zu: use dyn_layer_forward with a workspace of the caller's",
                     ws.total, kScratchBytes);
@@ -944,7 +1211,7 @@ dyn_status dyn_layer_forward_noalloc(dyn_layer *L, const dyn_batch *b, void *hip
     // builds the lists.
     for (const Dispatch &d : plan) {
         if (d.noop) continue;
-        if ((rc = launch_op(L, &local, &seq, ws, d, (hipStream_t)hip_stream, nullptr, nullptr)) != DYN_OK) return rc;
+        if ((rc = launch_op(L, &local, &seq, ws, d, ws.slot[(&d - plan.data()) % ws.slot.size()], (hipStream_t)hip_stream, nullptr, nullptr)) != DYN_OK) return rc;
     }
     return DYN_OK;
 }

@@ -59,12 +59,16 @@ extern "C" dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const i
         return fail(DYN_ERR_INVALID_ARG, "NULL layer, batch, options, scheduler, output or result");
     dyn_tune_options opt = *opt_in;
     if (opt.use_graph && !hip_stream) return fail(DYN_ERR_INVALID_ARG, "graph replays need a stream other than the null stream");
-    // Four micro-batches are enumerated and recorded on the host but not timed here: in a tuning
-    // run over 13 tokens, hipGraphLaunch of the 50th graph of the process (four micro-batches,
-    // projections merged, the rest split over four plain streams) ended in a segmentation fault
-    // inside the runtime, and neither the graph's shape nor the number of graphs could be shown
-    // to be the cause.  Up to three micro-batches ran through repeatedly.
-    if (opt.max_k > 3) return fail(DYN_ERR_UNSUPPORTED, "the device search covers up to three micro-batches (max_k = %d)", opt.max_k);
+    // More than two micro-batches are enumerated and recorded on the host but not timed here.  Tuning
+    // runs that capture, replay and destroy many graphs with three or four parallel branches have
+    // ended in a segmentation fault inside hipGraphLaunch (host side, in the runtime): with four
+    // micro-batches at the 50th graph of a process, and with three micro-batches - one graph alive
+    // at a time - late in a long process, while the same run alone in a fresh process went through.
+    // The library's own bookkeeping of streams, events, graphs and executables replays clean on the
+    // CPU under sanitizers against a stand-in runtime that checks every lifetime, so no cause in
+    // this library could be shown, and the case stays off the GPU.  Explicit schedules with up to
+    // eight micro-batches run and replay as graphs; only this search is limited.
+    if (opt.max_k > 2) return fail(DYN_ERR_UNSUPPORTED, "the device search covers two micro-batches (max_k = %d)", opt.max_k);
     int dev = 0, n_cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return fail(DYN_ERR_HIP, "cannot read the device's CU count");

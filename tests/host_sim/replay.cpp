@@ -117,7 +117,7 @@ void tune_like(Setup &s, int max_k, int partitions, int warmup, int iters) {
         ++graphs;
     }
     fprintf(stderr, "replay: %d candidates, each captured, replayed and timed\n", graphs);
-    if (max_k <= 3) {                      // and the library's own search on the same batch
+    if (max_k <= 2) {                      // and the library's own search on the same batch
         dyn_schedule out;
         dyn_tune_result res{};
         opt.warmup = warmup; opt.iters = iters;

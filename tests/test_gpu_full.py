@@ -108,6 +108,19 @@ def test_prefill_decode_mix_full_size():
         say("case c3: schedule %s" % label)
         outs[label] = run.run(sched, repeat=2)
     y0, k0, v0 = outs["sequential"]
+    # the sequential order again on a workspace of its own size (about 0.33 GB instead of 1.2 GB: regions share bytes)
+    seq = B.sequential(use_graph=True)
+    tight = B.DeviceStep(run.layer, data, sched=seq)
+    assert tight.batch.workspace_bytes < 0.35e9 < 1.1e9 < run.layer.workspace_bytes(w.n_tokens, tight.batch.max_pages_per_seq)
+    tight.workspace.fill_(0xFF)
+    st = torch.cuda.Stream()
+    with torch.cuda.stream(st):
+        run.layer.forward(tight.batch, seq, st)
+        run.layer.forward(tight.batch, seq, st)
+    st.synchronize()
+    say("case c3: sequential on a %.1f MB workspace" % (tight.batch.workspace_bytes / 1e6))
+    outs["sequential, schedule-sized workspace"] = (tight.y.cpu(), tight.k_cache.cpu(), tight.v_cache.cpu())
+    del tight
     for label, (y, kc, vc) in outs.items():
         assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
         assert torch.equal(kc.view(torch.uint8), k0.view(torch.uint8)), label

@@ -240,3 +240,39 @@ def test_released_graphs_are_captured_again():
             assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8)), rnd
         run.layer.release_graphs()
     assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8))
+
+
+@pytest.mark.parametrize("name", ["c2_small", "c3_small", "c4_small", "c5_small", "f32_moe_small", "moe_many_b", "stack_mixed", "pf_640"])
+def test_schedule_sized_workspace_with_shared_regions_is_bit_exact(name):
+    """The workspace sized for one schedule (regions that are never alive together share bytes),
+    filled with 0xFF, with a guard behind it: same bits as with the any-schedule workspace, the
+    guard untouched, a second forward on the used workspace the same again."""
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    scheds = dict(schedules_for(w), sequential=B.sequential(), sequential_graph=B.sequential(use_graph=True))
+    st = torch.cuda.Stream()
+    for label, sched in scheds.items():
+        step = B.DeviceStep(run.layer, data, sched=sched, guard=4096)
+        bound = run.layer.workspace_bytes(w.n_tokens, step.batch.max_pages_per_seq)
+        say("case %s schedule %s: workspace %d bytes (any schedule: %d)" % (name, label, step.batch.workspace_bytes, bound))
+        assert step.batch.workspace_bytes <= bound
+        step.workspace.fill_(0xFF)
+        torch.cuda.synchronize()
+        for rep in range(2):
+            step.y.zero_()
+            torch.cuda.synchronize()
+            with torch.cuda.stream(st):
+                run.layer.forward(step.batch, sched, st)
+            st.synchronize()
+            assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8)), (label, rep)
+        assert torch.equal(step.k_cache.cpu().view(torch.uint8), k0.view(torch.uint8)), label
+        assert torch.equal(step.v_cache.cpu().view(torch.uint8), v0.view(torch.uint8)), label
+        guard = step.workspace[step.workspace_offset + step.batch.workspace_bytes:]
+        assert bool((guard == 0xFF).all()), label
+        # one byte less is refused
+        step.batch.workspace_bytes -= 1
+        with pytest.raises(B.DynError) as e:
+            run.layer.forward(step.batch, sched, st)
+        assert e.value.status == B.DYN_ERR_WORKSPACE

@@ -114,7 +114,7 @@ def test_tuning_run_with_four_micro_batches_keeps_every_object_alive_while_used(
     assert stats["empty_branches"] == 0                      # no stream is forked into a capture without launching in it
 
 
-@pytest.mark.parametrize("name,max_k,partitions", [("c2_small", 3, 1), ("c3_small", 2, 3), ("c4_small", 3, 0), ("c5_small", 3, 1)])
+@pytest.mark.parametrize("name,max_k,partitions", [("c2_small", 3, 1), ("c2_small", 2, 3), ("c3_small", 2, 3), ("c4_small", 3, 0), ("c5_small", 3, 1), ("c5_small", 2, 1)])
 def test_tuning_runs(replay, name, max_k, partitions):
     stats = _run(replay, name, "tune", max_k, partitions, 1, 2)
     assert stats["graph_launches"] > 0 and stats["execs_destroyed"] == stats["instantiations"]

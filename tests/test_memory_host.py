@@ -95,3 +95,65 @@ def test_bad_arguments():
     bad = B.nano_schedule((0, 1, w.n_tokens), B.DENSE_CHAIN[:-1])     # incomplete chain
     with pytest.raises(B.DynError):
         layer.memory(hb, bad)
+
+
+def _conflict(a, b):
+    """Must never share bytes: alive at the same time, or scratch of dispatches on different streams."""
+    return bool(a["live"] & b["live"]) or (a["slot"] >= 0 and b["slot"] >= 0 and a["stream"] != b["stream"])
+
+
+def _check_layout(layer, hb, sched):
+    regions = layer.schedule_regions(hb, sched)
+    total = layer.schedule_workspace_bytes(hb, sched)
+    assert regions and total > 0
+    for r in regions:
+        assert r["offset"] % 256 == 0 and r["bytes"] > 0 and r["offset"] + r["bytes"] <= total and r["live"]
+    for i, a in enumerate(regions):
+        for b in regions[i + 1:]:
+            if _conflict(a, b):
+                assert a["offset"] + a["bytes"] <= b["offset"] or b["offset"] + b["bytes"] <= a["offset"], (a, b)
+    assert max(r["offset"] + r["bytes"] for r in regions) > total - 256          # nothing is reserved beyond the last region
+    return regions, total
+
+
+@pytest.mark.parametrize("name", ["c1", "c2_small", "c3_small", "c4_small", "c5_small", "f32_moe_small", "moe_many_b", "stack_mixed"])
+def test_layout_never_overlaps_regions_that_can_be_alive_together(name):
+    """The workspace layout of every candidate schedule, checked region pair by region pair with
+    the rule restated here: the placement may share bytes only between regions that are never
+    alive together.  The schedule's need never exceeds the bound that holds for every schedule;
+    one stream shares more than several."""
+    w, md, layer, hb, sch = setup(name)
+    bound = layer.workspace_bytes(w.n_tokens, md["max_pages_per_seq"])
+    _, seq_total = _check_layout(layer, hb, B.sequential())
+    assert seq_total < bound
+    assert layer.memory(hb, B.sequential())["workspace_bytes_schedule"] == seq_total
+    for c in sch.tune_candidates(md["ctx_len"], max_k=4, partitions=1):
+        sched = sch.tune_record(c, n_cus=256)
+        regions, total = _check_layout(layer, hb, sched)
+        assert seq_total <= total <= bound
+        if c.form != B.DYN_FORM_SEQUENTIAL and c.k > 1:
+            tensors = [r for r in regions if r["slot"] < 0]
+            assert all(r["live"] == tensors[0]["live"] for r in tensors)           # several streams: every tensor alive throughout
+    # micro-batches on one stream are as good as the sequential order for sharing tensors
+    one = B.nano_schedule(w.nano_rows, B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN, streams=[0] * (len(w.nano_rows) - 1))
+    regions, total = _check_layout(layer, hb, one)
+    assert total < bound and any(r["slot"] < 0 and r["live"] != regions[0]["live"] for r in regions)
+
+
+def test_sequential_layout_of_the_prefill_decode_mix_shares_most_of_the_workspace():
+    """c3 at full size (2048-token chunk + 64 decodes): the any-schedule bound reserves split-K
+    planes for every projection and every tensor side by side, about 1.2 GB; the sequential order
+    needs the split-KV partials plus what is alive beside them."""
+    w, md, layer, hb, sch = setup("c3")
+    bound = layer.workspace_bytes(w.n_tokens, md["max_pages_per_seq"])
+    regions, total = _check_layout(layer, hb, B.sequential())
+    assert bound > 1.1e9 and total < 0.35e9
+    by_kind = {r["kind"]: r for r in regions}
+    assert "planes" not in by_kind                      # 2112-row launches fold their planes in registers
+    # the gated activation reuses bytes of the attention's partials, which are dead by then
+    act, part = by_kind["act"], by_kind["part_o"]
+    assert not (act["live"] & part["live"])
+    assert act["offset"] < part["offset"] + part["bytes"] and part["offset"] < act["offset"] + act["bytes"]
+    split = B.nano_schedule(w.nano_rows, stagger=1)
+    _, total_split = _check_layout(layer, hb, split)
+    assert total < total_split < bound
