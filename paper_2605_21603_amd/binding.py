@@ -11,7 +11,7 @@ import numpy as np
 import torch  # must be imported before the library so both share one HIP runtime
 
 _HERE = os.path.dirname(os.path.abspath(__file__))
-LIB_PATH = os.path.join(_HERE, "libdynlayer.so")
+LIB_PATH = os.environ.get("DYNLAYER_LIB") or os.path.join(_HERE, "libdynlayer.so")   # the in-tree build unless another build is named
 
 DYN_OK, DYN_ERR_INVALID_ARG, DYN_ERR_UNSUPPORTED, DYN_ERR_SCHEDULE, DYN_ERR_WORKSPACE, DYN_ERR_HIP = range(6)
 DYN_F32, DYN_BF16 = 0, 1

@@ -233,6 +233,15 @@ const char *op_name(int op) {
     return op >= 0 && op < DYN_N_OPS ? n[op] : "?";
 }
 
+// The projections' dispatches also run the operator that follows them on the same rows - where
+// split-K planes are reduced, inside the reduce kernel (one pass over the planes instead of a
+// kernel per operator): qkv -> rotary + cache append, o -> second norm, down -> the next layer's
+// first norm.  The slots of those operators stay in the chain (schedules name them, the
+// ready-operator rule covers them) and launch nothing.
+bool fused_into_producer(int op, int layer) {
+    return op == DYN_OP_ROPE_KV || op == DYN_OP_NORM2 || (op == DYN_OP_NORM1 && layer > 0);
+}
+
 // Checks of an explicit schedule that need no batch: counts in range, arrays present, masks not empty.
 dyn_status check_schedule_fields(const dyn_schedule *s) {
     if (s->k < 1 || s->k > DYN_MAX_NANO) return fail(DYN_ERR_SCHEDULE, "k = %d outside 1..%d", s->k, DYN_MAX_NANO);
@@ -335,7 +344,12 @@ dyn_status build_plan(const dyn_layer *L, const dyn_batch *b, const dyn_schedule
         for (int i = 0; i < n_slots; ++i) {
             const dyn_slot &sl = slots[i];
             Dispatch d{l, sl.op, sl.nano, sl.n_nano, rows[sl.nano], rows[sl.nano + sl.n_nano], sl.stream, sl.partition, false, false, {}};
-            d.noop = d.r1 <= d.r0 || (sl.op == DYN_OP_SILU && dyn::gemm_gated_supported(L->cfg.dtype, 2 * L->cfg.mlp_inter, L->cfg.hidden));
+            // Operators that launch nothing of their own: the SiLU gate where the gate/up projection's epilogue
+            // applies it; rotary + cache append, which the qkv projection's dispatch applies to the rows it
+            // wrote; the second norm, applied by the o projection's dispatch; and from the second layer on
+            // the first norm, applied by the previous layer's down projection (fused_into_producer).
+            d.noop = d.r1 <= d.r0 || (sl.op == DYN_OP_SILU && dyn::gemm_gated_supported(L->cfg.dtype, 2 * L->cfg.mlp_inter, L->cfg.hidden)) ||
+                     fused_into_producer(sl.op, l);
             {   // sequences inside [r0, r1): cut points are sequence boundaries
                 const int32_t *q = b->q_start_host;
                 const int s0 = (int)(std::lower_bound(q, q + b->n_seqs + 1, d.r0) - q);
@@ -436,16 +450,20 @@ WsLayout plan_layout(const dyn_layer *L, const dyn_batch *b, const std::vector<D
     for (int j = 0; j < n_slots; ++j)
         for (int nb = plan[j].nano; nb < plan[j].nano + plan[j].n_nano; ++nb) { slot_of[plan[j].op][nb] = j; k = std::max(k, nb + 1); }
 
-    struct TensorDef { int kind; size_t bytes; int producer, last_consumer; bool present; };
+    // h holds three generations per layer: the first norm's output (written by the first layer's
+    // own norm, from then on by the previous layer's down projection), read by qkv; and the second
+    // norm's, written by the o projection's dispatch, read by the router and gate/up
+    struct TensorDef { int kind; size_t bytes; int producer, last_consumer; bool present; int producer_layer_offset; };
     const TensorDef defs[] = {
-        {DYN_REGION_H, z.h, DYN_OP_NORM1, DYN_OP_QKV, true},
-        {DYN_REGION_H, z.h, DYN_OP_NORM2, DYN_OP_GATE_UP, true},                   // the second norm's output takes the first one's place
-        {DYN_REGION_QKV, z.qkv, DYN_OP_QKV, DYN_OP_ATTN, true},
-        {DYN_REGION_ATTN, z.attn, DYN_OP_ATTN, DYN_OP_OPROJ, true},
-        {DYN_REGION_X2, z.x2, DYN_OP_OPROJ, DYN_OP_DOWN, true},
-        {DYN_REGION_GU, z.gu, DYN_OP_GATE_UP, DYN_OP_SILU, !gated},
-        {DYN_REGION_ACT, z.act, gated ? DYN_OP_GATE_UP : DYN_OP_SILU, DYN_OP_DOWN, true},
-        {DYN_REGION_ROUTING, align_up(z.sel) + z.wgt, DYN_OP_ROUTE, DYN_OP_DOWN, moe},
+        {DYN_REGION_H, z.h, DYN_OP_NORM1, DYN_OP_QKV, true, 0},
+        {DYN_REGION_H, z.h, DYN_OP_DOWN, DYN_OP_QKV, c.n_layers > 1, -1},
+        {DYN_REGION_H, z.h, DYN_OP_OPROJ, DYN_OP_GATE_UP, true, 0},
+        {DYN_REGION_QKV, z.qkv, DYN_OP_QKV, DYN_OP_ATTN, true, 0},
+        {DYN_REGION_ATTN, z.attn, DYN_OP_ATTN, DYN_OP_OPROJ, true, 0},
+        {DYN_REGION_X2, z.x2, DYN_OP_OPROJ, DYN_OP_DOWN, true, 0},
+        {DYN_REGION_GU, z.gu, DYN_OP_GATE_UP, DYN_OP_SILU, !gated, 0},
+        {DYN_REGION_ACT, z.act, gated ? DYN_OP_GATE_UP : DYN_OP_SILU, DYN_OP_DOWN, true, 0},
+        {DYN_REGION_ROUTING, align_up(z.sel) + z.wgt, DYN_OP_ROUTE, DYN_OP_DOWN, moe, 0},
     };
     int region_of_kind[DYN_REGION_KINDS];
     std::fill(region_of_kind, region_of_kind + DYN_REGION_KINDS, -1);
@@ -454,9 +472,11 @@ WsLayout plan_layout(const dyn_layer *L, const dyn_batch *b, const std::vector<D
         int r = region_of_kind[d.kind];
         if (r < 0) r = region_of_kind[d.kind] = add(d.kind, -1, d.bytes, false);
         for (int l = 0; l < c.n_layers; ++l) {
+            const int pl = l + d.producer_layer_offset;           // layer of the producing dispatch
+            if (pl < 0) continue;
             int from = P, to = -1;
             for (int nb = 0; nb < k; ++nb) {
-                from = std::min(from, l * n_slots + slot_of[d.producer][nb]);
+                from = std::min(from, pl * n_slots + slot_of[d.producer][nb]);
                 to = std::max(to, until[l * n_slots + slot_of[d.last_consumer][nb]]);
             }
             mark(r, from, to);
@@ -616,16 +636,25 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
     hipError_t err = hipSuccess;
     switch (d.op) {
         case DYN_OP_NORM1:
+            if (fused_into_producer(d.op, d.layer)) break;       // the previous layer's down projection wrote h
             err = dyn::launch_rmsnorm(c.dtype, rowp(x_in, H), w.g_norm1, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
             break;
-        case DYN_OP_QKV:
+        case DYN_OP_QKV: {
+            dyn::GemmEpilogue ep;                                 // rotary + cache append on the rows just projected
+            ep.kind = dyn::GemmEpilogue::ROPE;
+            ep.seq_of_token = b->seq_of_token + d.r0;
+            ep.pos_of_token = b->pos_of_token + d.r0;
+            ep.block_table = b->block_table;
+            ep.k_cache = kc;
+            ep.v_cache = vc;
+            ep.rope = &L->rope;
+            ep.shape = &sh;
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_qkv, nullptr, (void *)rowp(base + ws.qkv, NQKV),
-                                   planes, (size_t)rows * NQKV, rows, NQKV, H, st, mid);
+                                   planes, (size_t)rows * NQKV, rows, NQKV, H, st, mid, &ep);
             break;
+        }
         case DYN_OP_ROPE_KV:
-            err = dyn::launch_rope_kv(c.dtype, (void *)rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0,
-                                      b->pos_of_token + d.r0, b->block_table, kc, vc, L->rope, sh, rows, st);
-            break;
+            break;                                                // applied by the qkv projection's dispatch
         case DYN_OP_ATTN:
             err = dyn::launch_attention(c.dtype, rowp(base + ws.qkv, NQKV), b->seq_of_token + d.r0, b->pos_of_token + d.r0,
                                         b->block_table, kc, vc, (void *)rowp(base + ws.attn, ws.ld_attn), ws.ld_attn,
@@ -633,13 +662,19 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                                         (int32_t *)(base + ws.plan) + (size_t)d.r0 * (ws.max_chunks + 2) * 4, d.any_multi, sh, rows, st, mid, pre,
                                         d.layer > 0);   // every layer dispatches the same row ranges: layer 0 built the work lists
             break;
-        case DYN_OP_OPROJ:
+        case DYN_OP_OPROJ: {
+            dyn::GemmEpilogue ep;                                 // the second norm of the rows just written
+            ep.kind = dyn::GemmEpilogue::NORM;
+            ep.g = w.g_norm2;
+            ep.h_out = (void *)rowp(base + ws.h, ws.ld_h);
+            ep.ld_h = ws.ld_h;
+            ep.eps = c.rms_eps;
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.attn, ws.ld_attn), ws.ld_attn, w.w_o, rowp(x_in, H), (void *)rowp(base + ws.x2, H),
-                                   planes, (size_t)rows * H, rows, H, NQ, st, mid);
+                                   planes, (size_t)rows * H, rows, H, NQ, st, mid, &ep);
             break;
+        }
         case DYN_OP_NORM2:
-            err = dyn::launch_rmsnorm(c.dtype, rowp(base + ws.x2, H), w.g_norm2, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h, rows, H, c.rms_eps, st);
-            break;
+            break;                                                // applied by the o projection's dispatch
         case DYN_OP_ROUTE:
             err = dyn::launch_route(c.dtype, rowp(base + ws.h, ws.ld_h), ws.ld_h, w.w_router,
                                     (int32_t *)(base + ws.sel) + (size_t)d.r0 * c.top_k,
@@ -682,7 +717,7 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
             }
             err = dyn::launch_silu_mul(c.dtype, rowp(base + ws.gu, 2 * I), (void *)rowp(base + ws.act, ws.ld_act), ws.ld_act, rows, I, st);
             break;
-        case DYN_OP_DOWN:
+        case DYN_OP_DOWN: {
             if (c.n_experts) {
                 const int n_pairs = rows * c.top_k, pair0 = d.r0 * c.top_k;
                 int32_t *counts = (int32_t *)(base + sc.lists);     // its own, or the matching gate/up dispatch's (lists_ready)
@@ -699,11 +734,23 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
                 err = dyn::launch_moe_combine(c.dtype, mp, plane, Sd,
                                               (const float *)(base + ws.wgt) + pair0, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
                                               rows, H, c.top_k, st);
+                if (err == hipSuccess && d.layer + 1 < nl)        // the next layer's first norm of the rows just written
+                    err = dyn::launch_rmsnorm(c.dtype, rowp(x_out, H), L->w[d.layer + 1].g_norm1, (void *)rowp(base + ws.h, ws.ld_h), ws.ld_h,
+                                              rows, H, c.rms_eps, st);
                 break;
             }
+            dyn::GemmEpilogue ep;                                 // the next layer's first norm of the rows just written
+            if (d.layer + 1 < nl) {
+                ep.kind = dyn::GemmEpilogue::NORM;
+                ep.g = L->w[d.layer + 1].g_norm1;
+                ep.h_out = (void *)rowp(base + ws.h, ws.ld_h);
+                ep.ld_h = ws.ld_h;
+                ep.eps = c.rms_eps;
+            }
             err = dyn::launch_gemm(c.dtype, rowp(base + ws.act, ws.ld_act), ws.ld_act, w.w_down, rowp(base + ws.x2, H), (void *)rowp(x_out, H),
-                                   planes, (size_t)rows * H, rows, H, I, st, mid);
+                                   planes, (size_t)rows * H, rows, H, I, st, mid, &ep);
             break;
+        }
         default:
             return fail(DYN_ERR_UNSUPPORTED, "operator %s has no kernel", op_name(d.op));
     }
@@ -823,24 +870,27 @@ void analyse_memory(const dyn_layer *L, const dyn_batch *b, const std::vector<Di
     for (auto &r : slot_of) std::fill(r, r + DYN_MAX_NANO, -1);
     for (int i = 0; i < n_slots; ++i)
         for (int nb = plan[i].nano; nb < plan[i].nano + plan[i].n_nano; ++nb) slot_of[plan[i].op][nb] = i;
-    struct Tensor { int producer; int consumers[2]; size_t row_bytes; bool from_previous_layer; bool present; };
+    // Who writes and who reads what (the projections' dispatches also run the operator that follows
+    // them: qkv rotates and appends, o and down write the next norm's output).
+    struct Tensor { int producer; int consumers[2]; size_t row_bytes; bool from_previous_layer; bool present; bool first_layer_only; };
     const Tensor tensors[] = {
-        {DYN_OP_DOWN, {DYN_OP_NORM1, DYN_OP_OPROJ}, H * e, true, true},                       // layer input (not the caller's x)
-        {DYN_OP_NORM1, {DYN_OP_QKV, -1}, ws.ld_h * e, false, true},
-        {DYN_OP_QKV, {DYN_OP_ROPE_KV, DYN_OP_ATTN}, NQKV * e, false, true},                   // q and k rotated in place
-        {DYN_OP_ATTN, {DYN_OP_OPROJ, -1}, ws.ld_attn * e, false, true},
-        {DYN_OP_OPROJ, {DYN_OP_NORM2, DYN_OP_DOWN}, H * e, false, true},                      // x2: normed, and the residual of the MLP
-        {DYN_OP_NORM2, {moe ? DYN_OP_ROUTE : DYN_OP_GATE_UP, moe ? DYN_OP_GATE_UP : -1}, ws.ld_h * e, false, true},
-        {DYN_OP_ROUTE, {DYN_OP_GATE_UP, DYN_OP_DOWN}, (size_t)c.top_k * 8, false, moe},       // selected experts and their weights
-        {DYN_OP_GATE_UP, {DYN_OP_SILU, -1}, (size_t)pairs * 2 * I * e, false, !gated},
-        {gated ? DYN_OP_GATE_UP : DYN_OP_SILU, {DYN_OP_DOWN, -1}, (size_t)pairs * ws.ld_act * e, false, true},
+        {DYN_OP_DOWN, {DYN_OP_OPROJ, -1}, H * e, true, true, false},                          // layer input (not the caller's x): the residual
+        {DYN_OP_NORM1, {DYN_OP_QKV, -1}, ws.ld_h * e, false, true, true},                     // first norm, first layer
+        {DYN_OP_DOWN, {DYN_OP_QKV, -1}, ws.ld_h * e, true, true, false},                      // first norm, later layers
+        {DYN_OP_QKV, {DYN_OP_ATTN, -1}, NQKV * e, false, true, false},                        // q rotated by the projection's dispatch
+        {DYN_OP_ATTN, {DYN_OP_OPROJ, -1}, ws.ld_attn * e, false, true, false},
+        {DYN_OP_OPROJ, {DYN_OP_DOWN, -1}, H * e, false, true, false},                         // x2: the residual of the MLP
+        {DYN_OP_OPROJ, {moe ? DYN_OP_ROUTE : DYN_OP_GATE_UP, moe ? DYN_OP_GATE_UP : -1}, ws.ld_h * e, false, true, false},   // second norm
+        {DYN_OP_ROUTE, {DYN_OP_GATE_UP, DYN_OP_DOWN}, (size_t)c.top_k * 8, false, moe, false},   // selected experts and their weights
+        {DYN_OP_GATE_UP, {DYN_OP_SILU, -1}, (size_t)pairs * 2 * I * e, false, !gated, false},
+        {gated ? DYN_OP_GATE_UP : DYN_OP_SILU, {DYN_OP_DOWN, -1}, (size_t)pairs * ws.ld_act * e, false, true, false},
     };
     std::vector<size_t> born(plan.size(), 0), dies(plan.size(), 0), scratch(plan.size(), 0);
     const std::vector<int> until = alive_until(plan);      // stream-aware end of what a dispatch is the last to touch
     out->n_regions = out->max_ref_count = out->n_resharded = 0;
     for (int l = 0; l < c.n_layers; ++l)
         for (const Tensor &t : tensors) {
-            if (!t.present || (t.from_previous_layer && l == 0)) continue;
+            if (!t.present || (t.from_previous_layer && l == 0) || (t.first_layer_only && l > 0)) continue;
             for (int nb = 0; nb < k; ++nb) {
                 const size_t n_rows = (size_t)(rows[nb + 1] - rows[nb]);
                 if (!n_rows) continue;

@@ -60,11 +60,32 @@ bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K);
 hipError_t launch_rmsnorm(int dtype, const void *x, const void *g, void *out, int ld_out, int rows, int H, float eps,
                           hipStream_t s);
 
+// What follows a projection on the same token rows and is applied by the same launch sequence,
+// so that its input never makes a round trip through a kernel of its own: the RMSNorm of the
+// output rows (after the o and down projections) or rotary + cache append (after the qkv
+// projection).  Where the projection's split-K planes are summed by a reduce kernel, that kernel
+// applies it (one pass over the planes); otherwise the operator's own kernel runs on the rows the
+// projection wrote.  Either way every element sees the same arithmetic in the same order.
+struct GemmEpilogue {
+    enum { NONE = 0, NORM = 1, ROPE = 2 } kind = NONE;
+    // NORM: h_out[row] = RMSNorm(Y[row]) * g, row pitch ld_h
+    const void *g = nullptr;
+    void *h_out = nullptr;
+    int ld_h = 0;
+    float eps = 0.f;
+    // ROPE: rotary on the q and k heads of the Y rows (q in place), k' and v appended to the cache
+    const int32_t *seq_of_token = nullptr, *pos_of_token = nullptr, *block_table = nullptr;
+    void *k_cache = nullptr, *v_cache = nullptr;
+    const RopeTable *rope = nullptr;
+    const AttnShape *shape = nullptr;
+};
+
 // Y[rows,N] = X[rows,K] W[N,K]^T (+ R[rows,N]); ldx = elements between rows of X (>= K).  partial: fp32 scratch for split-K planes,
 // plane p at partial + p * plane_stride (elements); unused when the split factor is 1.
 // If mid is not NULL it is recorded after the contraction kernel, before the split-K reduce.
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
-                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid = nullptr);
+                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid = nullptr,
+                       const GemmEpilogue *ep = nullptr);
 
 hipError_t launch_gemm_grouped(int dtype, const void *X, int ldx, const void *W, void *Y, float *partial,
                                size_t plane_stride, const GemmGroups &gr, int max_rows, int row0, int n_rows, int N, int K,
@@ -109,6 +130,14 @@ hipError_t launch_attention(int dtype, const void *qkv, const int32_t *seq_of_to
 
 // out[rows, I] = silu(gu[:, :I]) * gu[:, I:]
 hipError_t launch_silu_mul(int dtype, const void *gu, void *out, int ld_out, int rows, int I, hipStream_t s);
+
+// The split-K reduce of a projection fused with what follows it (bf16; used by launch_gemm).
+hipError_t launch_reduce_norm(const float *P, size_t plane_stride, int S, const void *R, void *Y, const void *g, void *out,
+                              int ld_out, int rows, int H, float eps, hipStream_t s);
+bool reduce_rope_supported(int dtype, const AttnShape &sh);
+hipError_t launch_reduce_rope(const float *P, size_t plane_stride, int S, void *qkv, const int32_t *seq_of_token,
+                              const int32_t *pos_of_token, const int32_t *block_table, void *k_cache, void *v_cache,
+                              const RopeTable &tab, const AttnShape &sh, int rows, hipStream_t s);
 
 // Measurement aid: reads `bytes` (a multiple of 16, 16-byte aligned) of buf once; sink receives 8192 words.
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t s);

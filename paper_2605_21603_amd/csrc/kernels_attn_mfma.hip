@@ -45,6 +45,14 @@ constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of th
 // chunks of prefill_chunk_positions() positions (1024 unless the block reaches past 8192 keys).
 // One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
 // (first token row, chunk | tokens << 20) at list[2 + 2 i].
+// List 0 is ordered by work, largest first: its entries are bucketed by the number of tile pairs
+// (four pages each) the chunk is walked in - kPlanBuckets of them, a chunk has at most 16 pages -
+// and inside a bucket they stay in token order, so the eight kv heads of a chunk and the chunks
+// of a sequence remain neighbours.  The persistent decode kernel deals the list out by wave index
+// in a snake (attn_mfma_kernel): with equal-sized items first and the small ones at the end, the
+// waves' totals differ by about one percent instead of six on contexts spread over 1024..8192.
+constexpr int kPlanBuckets = 4;
+
 __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restrict__ seq_of_token,
                                                          const int32_t *__restrict__ pos_of_token, int rows, int ct,
                                                          int tg1, int32_t *__restrict__ plan0,
@@ -52,63 +60,136 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
     // One workgroup of 16 waves walks the rows 1024 at a time.  A sequence's tokens are adjacent
     // rows with consecutive positions, so a token leads its group iff it starts its sequence or
     // its aligned block, and the group's size comes from a bisection over the look-ahead rows.
-    // Entry offsets come from a wave scan plus one LDS step per list.
-    __shared__ int wave_tot[2][16];
+    // Entry offsets come from a wave scan plus one LDS step per list (per bucket of list 0).
+    constexpr int NL = kPlanBuckets + 1;                    // scanned counters: list 0's buckets, then list 1
+    __shared__ int wave_tot[NL][16];
+    __shared__ int bucket_total[kPlanBuckets];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    int base0 = 0, base1 = 0;
+    const int chunk_pages = ct / PS, pair_pages = 2 * TILE_PAGES;
+
+    // What token row t contributes: which list, how many entries, and for list 0 the buckets of
+    // its chunks (all but the last have the sequence's balanced chunk size, the last the rest).
+    struct Row { int which, nc, n_tok, b_full, b_last; };
+    auto classify = [&](int t) {
+        Row r{0, 0, 0, 0, 0};
+        const int s = seq_of_token[t], p = pos_of_token[t];
+        const bool prev_same = t > 0 && seq_of_token[t - 1] == s, next_same = t + 1 < rows && seq_of_token[t + 1] == s;
+        r.which = prev_same || next_same;
+        const int tg = r.which ? tg1 : 1;
+        if (!prev_same || p % tg == 0) {                     // group leader
+            const int cand = tg - p % tg;                    // positions left in the aligned block
+            // rows t .. t + n_tok - 1 belong to the sequence: the matches form a prefix of the
+            // candidates, found by bisection (a few dependent cache hits instead of tg loads)
+            int lo = 1, hi = min(cand, rows - t);            // n_tok lies in [lo, hi]
+            while (lo < hi) {
+                const int mid = (lo + hi + 1) >> 1;
+                if (seq_of_token[t + mid - 1] == s) lo = mid;
+                else hi = mid - 1;
+            }
+            r.n_tok = lo;
+            const int ctw = r.which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;
+            r.nc = (p + r.n_tok - 1 + ctw) / ctw;            // chunks the group's last token reaches
+            if (!r.which) {                                  // the decode kernel's own chunking of this sequence
+                const int seq_pages = (p + PS) / PS;         // ceil((p + 1) / PS)
+                const int cp = (seq_pages + r.nc - 1) / r.nc, last = seq_pages - (r.nc - 1) * cp;
+                r.b_full = max(0, kPlanBuckets - (cp + pair_pages - 1) / pair_pages);
+                r.b_last = max(0, kPlanBuckets - (last + pair_pages - 1) / pair_pages);
+            }
+        }
+        return r;
+    };
+
+    // pass 1: sizes of list 0's buckets
+    if (threadIdx.x < kPlanBuckets) bucket_total[threadIdx.x] = 0;
+    __syncthreads();
+    Row first_batch{0, 0, 0, 0, 0};                          // the first 1024 rows are classified once (most batches have no more)
+    for (int t = threadIdx.x; t < rows; t += 1024) {
+        const Row r = classify(t);
+        if (t < 1024) first_batch = r;
+        if (!r.which && r.nc > 0) {
+            if (r.nc > 1) atomicAdd(&bucket_total[r.b_full], r.nc - 1);
+            atomicAdd(&bucket_total[r.b_last], 1);
+        }
+    }
+    __syncthreads();
+    int base[NL];                                             // next free entry of each bucket / of list 1
+    base[0] = 0;
+#pragma unroll
+    for (int k = 1; k < kPlanBuckets; ++k) base[k] = base[k - 1] + bucket_total[k - 1];
+    const int total0 = base[kPlanBuckets - 1] + bucket_total[kPlanBuckets - 1];
+    base[kPlanBuckets] = 0;
+    (void)chunk_pages;
+
+    // pass 2: entries, in token order inside each bucket
     for (int t0 = 0; t0 < rows; t0 += 1024) {
         const int t = t0 + threadIdx.x;
-        int nc = 0, n_tok = 0, which = 0;
+        Row r{0, 0, 0, 0, 0};
         if (t < rows) {
-            const int s = seq_of_token[t], p = pos_of_token[t];
-            const bool prev_same = t > 0 && seq_of_token[t - 1] == s, next_same = t + 1 < rows && seq_of_token[t + 1] == s;
-            which = prev_same || next_same;
-            const int tg = which ? tg1 : 1;
-            if (!prev_same || p % tg == 0) {                 // group leader
-                const int cand = tg - p % tg;                // positions left in the aligned block
-                // rows t .. t + n_tok - 1 belong to the sequence: the matches form a prefix of the
-                // candidates, found by bisection (a few dependent cache hits instead of tg loads)
-                int lo = 1, hi = min(cand, rows - t);        // n_tok lies in [lo, hi]
-                while (lo < hi) {
-                    const int mid = (lo + hi + 1) >> 1;
-                    if (seq_of_token[t + mid - 1] == s) lo = mid;
-                    else hi = mid - 1;
-                }
-                n_tok = lo;
-                const int ctw = which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;
-                nc = (p + n_tok - 1 + ctw) / ctw;            // chunks the group's last token reaches
+            r = t0 == 0 ? first_batch : classify(t);
+            const int p = pos_of_token[t];
+            ct_of_token[t] = r.which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;   // the chunk size this token's partials are indexed by
+        }
+        int v[NL];                                            // this thread's entries per counter
+#pragma unroll
+        for (int k = 0; k < NL; ++k) v[k] = 0;
+        if (r.which) {
+            v[kPlanBuckets] = r.nc;
+        } else if (r.nc > 0) {
+#pragma unroll
+            for (int k = 0; k < kPlanBuckets; ++k) v[k] = (k == r.b_full ? r.nc - 1 : 0) + (k == r.b_last ? 1 : 0);
+        }
+        int incl[NL];                                         // inclusive wave scans
+#pragma unroll
+        for (int k = 0; k < NL; ++k) {
+            int x = v[k];
+#pragma unroll
+            for (int off = 1; off < 64; off <<= 1) {
+                const int u = __shfl_up(x, off, 64);
+                if (lane >= off) x += u;
             }
-            ct_of_token[t] = which ? prefill_chunk_positions((p / tg1 + 1) * tg1) : ct;   // the chunk size this token's partials are indexed by
+            incl[k] = x;
+            if (lane == 63) wave_tot[k][wave] = x;
         }
-        int v0 = which ? 0 : nc, v1 = which ? nc : 0;        // inclusive wave scans of both lists
-#pragma unroll
-        for (int off = 1; off < 64; off <<= 1) {
-            const int u0 = __shfl_up(v0, off, 64), u1 = __shfl_up(v1, off, 64);
-            if (lane >= off) { v0 += u0; v1 += u1; }
-        }
-        if (lane == 63) { wave_tot[0][wave] = v0; wave_tot[1][wave] = v1; }
         __syncthreads();
-        int pre0 = 0, pre1 = 0, tot0 = 0, tot1 = 0;
+        int start[NL];
 #pragma unroll
-        for (int w = 0; w < 16; ++w) {
-            if (w < wave) { pre0 += wave_tot[0][w]; pre1 += wave_tot[1][w]; }
-            tot0 += wave_tot[0][w];
-            tot1 += wave_tot[1][w];
+        for (int k = 0; k < NL; ++k) {
+            int pre = 0, tot = 0;
+#pragma unroll
+            for (int w = 0; w < 16; ++w) {
+                if (w < wave) pre += wave_tot[k][w];
+                tot += wave_tot[k][w];
+            }
+            start[k] = base[k] + pre + incl[k] - v[k];
+            base[k] += tot;
         }
-        int32_t *plan = which ? plan1 : plan0;
-        const int start = which ? base1 + pre1 + v1 - nc : base0 + pre0 + v0 - nc;
-        for (int c = 0; c < nc; ++c) {
-            plan[2 + 2 * (start + c)] = t;
-            plan[3 + 2 * (start + c)] = c | (n_tok << 20);
+        if (r.which) {
+            for (int c = 0; c < r.nc; ++c) {
+                plan1[2 + 2 * (start[kPlanBuckets] + c)] = t;
+                plan1[3 + 2 * (start[kPlanBuckets] + c)] = c | (r.n_tok << 20);
+            }
+        } else if (r.nc > 0) {
+            int at_full = 0, at_last = 0;
+#pragma unroll
+            for (int k = 0; k < kPlanBuckets; ++k) {          // select without indexing the register arrays dynamically
+                if (k == r.b_full) at_full = start[k];
+                if (k == r.b_last) at_last = start[k] + (r.b_last == r.b_full ? r.nc - 1 : 0);
+            }
+            for (int c = 0; c + 1 < r.nc; ++c) {
+                plan0[2 + 2 * (at_full + c)] = t;
+                plan0[3 + 2 * (at_full + c)] = c | (1 << 20);
+            }
+            plan0[2 + 2 * at_last] = t;
+            plan0[3 + 2 * at_last] = (r.nc - 1) | (1 << 20);
         }
-        base0 += tot0;
-        base1 += tot1;
         __syncthreads();                                      // wave_tot is reused by the next batch
     }
-    if (threadIdx.x == 0) { plan0[0] = base0; plan1[0] = base1; plan1[1] = 0; }   // list sizes; list 1's work counter
+    if (threadIdx.x == 0) { plan0[0] = total0; plan1[0] = base[kPlanBuckets]; plan1[1] = 0; }   // list sizes; list 1's work counter
 }
 
-// Persistent waves: wave w of the launch takes (entry, kv head) pairs w, w + n_waves, ...
+// Persistent waves: in round k wave w of the launch takes (entry, kv head) pair k * n_waves + w,
+// in odd rounds k * n_waves + (n_waves - 1 - w): a snake over a list that is ordered largest first
+// (attn_plan_kernel), so a wave that drew the largest item of one round draws the smallest of the next.
 // A pair is walked two tiles (four pages) at a time through two register buffers, and when a
 // pair runs out of tiles the free buffer is refilled with the first tile of the wave's next
 // pair - whose indices were fetched while this pair was being multiplied - so the stream of
@@ -141,7 +222,10 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
     const int col_tok = lr / G, col_head = lr % G;   // MFMA column lr of set q = (token q * TG + col_tok, q head col_head)
     const float sscale = 1.4426950408889634f / sqrtf((float)HD);   // log2(e) / sqrt(d)
 
-    int item = blockIdx.x * 4 + wave;
+    const int gw = blockIdx.x * 4 + wave;
+    int round = 0;
+    auto item_at = [&](int k) { return k * n_waves + ((k & 1) ? n_waves - 1 - gw : gw); };
+    int item = item_at(0);
     if (item >= n_items) return;
 
     auto fetch_item = [&](int it, int &g_out) {
@@ -252,7 +336,7 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
     DYN_ATTN_LOAD_Q(qb, nk_cur, cur, g_cur)
     DYN_ATTN_LOAD(0, cur, g_cur, 0)
     while (true) {
-        const int next_item = item + n_waves;
+        const int next_item = item_at(round + 1);
         const bool more = next_item < n_items;
         // the wave's last pair "prefetches" itself again: harmless loads instead of a conditional branch
         AttnItem nxt = fetch_item(more ? next_item : item, g_nxt);
@@ -304,6 +388,7 @@ __global__ __launch_bounds__(256, NQG == 1 ? 2 : 1) void attn_mfma_kernel(const 
         }
         if (!more) break;
         item = next_item;
+        ++round;
         cur = nxt;
         g_cur = g_nxt;
 #pragma unroll

@@ -90,11 +90,7 @@ __global__ __launch_bounds__(256) void gemm_f32_kernel(const float *__restrict__
 // the fp32 plane traffic would cost more than the weights.
 constexpr int BK = 64, ROWB = BK * 2;
 constexpr int kRotGroup = 32, kRotStep = 9;   // stage-order rotation of the bf16 kernel
-#ifndef DYN_BIG_BN             // tile and ring depth of the many-row (matrix-core-bound) regime
-#define DYN_BIG_BN 128
-#define DYN_BIG_MT 128
-#define DYN_BIG_NS 2
-#endif
+constexpr int kBigBN = 128, kBigMT = 128, kBigNS = 2;   // tile and ring depth of the many-row (matrix-core-bound) regime
 
 __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(n) only; n folds to a literal <= 63
     // simm16: vmcnt[3:0] | expcnt[6:4] | lgkmcnt[11:8] | vmcnt[5:4] << 14; expcnt 7 and lgkmcnt 15 = no wait
@@ -362,7 +358,7 @@ int gemm_split_k(int dtype, int N, int K, int groups) {
 
 namespace {
 bool gemm_many_rows(int rows, int N) {      // enough 128 x 128 tiles for the many-row regime
-    return N % DYN_BIG_BN == 0 && (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) >= 256;
+    return N % kBigBN == 0 && (N / kBigBN) * ((rows + kBigMT - 1) / kBigMT) >= 256;
 }
 
 // 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
@@ -392,7 +388,7 @@ int gemm_tall_rows(int rows, int S, int N, int K) {
     // traffic is small next to the contraction (S / K small: the down projection; 1024 rows: 212 ->
     // 148 us, while qkv and o stay with the folded path: 79 and 66 us against 99 and 81).
     const bool folded_ok = gemm_many_rows(rows, N);
-    const bool half_filled = (N / DYN_BIG_BN) * ((rows + DYN_BIG_MT - 1) / DYN_BIG_MT) < 512;
+    const bool half_filled = (N / kBigBN) * ((rows + kBigMT - 1) / kBigMT) < 512;
     if (folded_ok && !(half_filled && K >= 1400 * S)) return 0;
     if (rows > 1024) return folded_ok ? 512 : 0;
     return (rows + 383) / 384 <= (rows + 511) / 512 ? 384 : 512;
@@ -460,23 +456,46 @@ bool gemm_uses_plane_buffer(int dtype, int rows, int N, int K) {
     return p.split > 1 && !p.folded;
 }
 
+namespace {
+// The operator that follows the projection, as a kernel of its own on the rows the projection wrote.
+hipError_t run_epilogue(int dtype, const GemmEpilogue &ep, void *Y, int rows, int N, hipStream_t s) {
+    if (ep.kind == GemmEpilogue::NORM) return launch_rmsnorm(dtype, Y, ep.g, ep.h_out, ep.ld_h, rows, N, ep.eps, s);
+    if (ep.kind == GemmEpilogue::ROPE)
+        return launch_rope_kv(dtype, Y, ep.seq_of_token, ep.pos_of_token, ep.block_table, ep.k_cache, ep.v_cache, *ep.rope, *ep.shape, rows, s);
+    return hipSuccess;
+}
+
+GemmEpilogue epilogue_at(const GemmEpilogue &ep, int dtype, int row, int N) {      // the same epilogue for rows starting `row` rows in
+    GemmEpilogue e = ep;
+    const size_t es = dtype == 0 ? 4 : 2;
+    if (e.kind == GemmEpilogue::NORM) e.h_out = (char *)e.h_out + (size_t)row * e.ld_h * es;
+    if (e.kind == GemmEpilogue::ROPE) { e.seq_of_token += row; e.pos_of_token += row; }
+    (void)N;
+    return e;
+}
+}  // namespace
+
 hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const void *R, void *Y, float *partial,
-                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid) {
+                       size_t plane_stride, int rows, int N, int K, hipStream_t s, hipEvent_t mid, const GemmEpilogue *ep) {
     if (rows <= 0) return hipSuccess;
     const GemmGroups none{};
+    const bool has_ep = ep && ep->kind != GemmEpilogue::NONE;
     if (dtype == 0) {
         hipLaunchKernelGGL(gemm_f32_kernel, dim3((N + 63) / 64, (rows + 63) / 64), dim3(256), 0, s, (const float *)X, ldx,
                            (const float *)W, (const float *)R, (float *)Y, rows, N, K, none);
         hipError_t e0 = hipGetLastError();
         if (e0 == hipSuccess && mid) e0 = hipEventRecord(mid, s);
+        if (e0 == hipSuccess && has_ep) e0 = run_epilogue(dtype, *ep, Y, rows, N, s);
         return e0;
     }
     const GemmPath p = gemm_path(dtype, rows, N, K);
     if (p.tail_rows) {         // the last rows in a launch of their own (own tiles, own planes and reduce)
         const int head = rows - p.tail_rows;
+        GemmEpilogue tail_ep;
+        if (has_ep) tail_ep = epilogue_at(*ep, dtype, head, N);
         hipError_t et = launch_gemm(dtype, (const bf16_t *)X + (size_t)head * ldx, ldx, W, R ? (const bf16_t *)R + (size_t)head * N : nullptr,
                                     (bf16_t *)Y + (size_t)head * N, partial ? partial + (size_t)head * N : nullptr, plane_stride,
-                                    p.tail_rows, N, K, s, nullptr);
+                                    p.tail_rows, N, K, s, nullptr, has_ep ? &tail_ep : nullptr);
         if (et != hipSuccess) return et;
         rows = head;
     }
@@ -488,17 +507,26 @@ hipError_t launch_gemm(int dtype, const void *X, int ldx, const void *W, const v
     hipError_t e;
     if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GEMM(128, 256, false, 3, 8) : p.mt == 384 ? DYN_GEMM(128, 384, false, 2, 8) : DYN_GEMM(128, 512, false, 2, 8);
     else if (p.kind == GEMM_WIDE) e = DYN_GEMM(256, 256, false, 2, 8);
-    else if (p.kind == GEMM_MANY && p.mt == 160) e = p.folded ? DYN_GEMM(DYN_BIG_BN, 160, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, 160, false, DYN_BIG_NS, 4);
-    else if (p.kind == GEMM_MANY) e = p.folded ? DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, true, DYN_BIG_NS, 4) : DYN_GEMM(DYN_BIG_BN, DYN_BIG_MT, false, DYN_BIG_NS, 4);
+    else if (p.kind == GEMM_MANY && p.mt == 160) e = p.folded ? DYN_GEMM(kBigBN, 160, true, kBigNS, 4) : DYN_GEMM(kBigBN, 160, false, kBigNS, 4);
+    else if (p.kind == GEMM_MANY) e = p.folded ? DYN_GEMM(kBigBN, kBigMT, true, kBigNS, 4) : DYN_GEMM(kBigBN, kBigMT, false, kBigNS, 4);
     else e = p.mt == 64 ? DYN_GEMM(128, 64, false, 4, 8) : DYN_GEMM(128, 128, false, 4, 8);
 #undef DYN_GEMM
     if (e == hipSuccess && mid) e = hipEventRecord(mid, s);
-    if (e != hipSuccess || S == 1 || p.folded) return e;
+    if (e != hipSuccess) return e;
+    if (S == 1 || p.folded) return has_ep ? run_epilogue(dtype, *ep, Y, rows, N, s) : hipSuccess;
+    // the planes are summed in plane order, with the residual; where an operator follows on the same rows, by its fused form
+    if (has_ep && ep->kind == GemmEpilogue::NORM && N % 8 == 0)
+        return launch_reduce_norm(partial, plane_stride, S, R, Y, ep->g, ep->h_out, ep->ld_h, rows, N, ep->eps, s);
+    if (has_ep && ep->kind == GemmEpilogue::ROPE && !R && reduce_rope_supported(dtype, *ep->shape))
+        return launch_reduce_rope(partial, plane_stride, S, Y, ep->seq_of_token, ep->pos_of_token, ep->block_table, ep->k_cache,
+                                  ep->v_cache, *ep->rope, *ep->shape, rows, s);
     const size_t n_vec = (size_t)rows * N / 4;
     const int blocks = (int)((n_vec + 255) / 256 < 2048 ? (n_vec + 255) / 256 : 2048);
     hipLaunchKernelGGL(gemm_reduce_kernel, dim3(blocks), dim3(256), 0, s, partial, plane_stride, (const bf16_t *)R,
                        (bf16_t *)Y, n_vec, S);
-    return hipGetLastError();
+    e = hipGetLastError();
+    if (e == hipSuccess && has_ep) e = run_epilogue(dtype, *ep, Y, rows, N, s);
+    return e;
 }
 
 namespace {
@@ -541,11 +569,11 @@ hipError_t launch_gemm_gated(const void *X, int ldx, const void *W, void *Y, int
             if (e != hipSuccess) return e;
             max_rows = head;
         }
-        const int mt = p.kind == GEMM_MANY ? DYN_BIG_MT : p.mt;    // the gated many-row kernel has 128-row tiles only
+        const int mt = p.kind == GEMM_MANY ? kBigMT : p.mt;    // the gated many-row kernel has 128-row tiles only
         const int grid = ((N2 / p.bn + 7) / 8) * 8 * ((max_rows + mt - 1) / mt);
         if (p.kind == GEMM_TALL) e = p.mt == 256 ? DYN_GATED(128, 256, 3, 8) : DYN_GATED(128, 384, 2, 8);
         else if (p.kind == GEMM_WIDE) e = DYN_GATED(256, 256, 2, 8);
-        else if (p.kind == GEMM_MANY) e = DYN_GATED(DYN_BIG_BN, DYN_BIG_MT, DYN_BIG_NS, 4);
+        else if (p.kind == GEMM_MANY) e = DYN_GATED(kBigBN, kBigMT, kBigNS, 4);
         else e = p.mt == 64 ? DYN_GATED(128, 64, 4, 8) : DYN_GATED(128, 128, 4, 8);
     }
 #undef DYN_GATED

@@ -21,7 +21,7 @@ def test_sequential_peak_of_the_fp32_layer_by_hand():
     Row bytes (GEMM inputs carry 256 bytes of padding): h 1280, qkv 3072, attention out 1280,
     x2 1024, gate|up 8192, act 4352.  Attention scratch: 4 tokens x 4 heads x 1 chunk x
     (64 + 2) floats + (4 + 8) x 4 ints = 4416.  Alive while each operator runs:
-      norm1 h | qkv h+qkv | rope qkv | attn qkv+out+scratch | oproj out+x2 | norm2 x2+h |
+      norm1 h | qkv (+ rotary, cache append) h+qkv | attn qkv+out+scratch | oproj (+ second norm) out+x2+h |
       gate_up x2+h+gu | silu x2+gu+act | down x2+act
     The gate (fp32: not fused into the projection) is the peak: 4 x (1024 + 8192 + 4352)."""
     w, md, layer, hb, sch = setup("c1")
@@ -29,7 +29,7 @@ def test_sequential_peak_of_the_fp32_layer_by_hand():
     assert r["peak_live_bytes"] == 4 * (1024 + 8192 + 4352) == 54272
     assert r["peak_at_dispatch"] == 7
     assert r["peak_live_bytes_sequential"] == r["peak_live_bytes"]
-    assert r["n_regions"] == 7 and r["max_ref_count"] == 2 and r["n_resharded"] == 0
+    assert r["n_regions"] == 7 and r["max_ref_count"] == 1 and r["n_resharded"] == 0
     assert r["workspace_bytes"] == layer.workspace_bytes(w.n_tokens, md["max_pages_per_seq"])
     assert r["peak_live_bytes"] < r["workspace_bytes"]
 
@@ -48,7 +48,7 @@ def test_every_candidate_schedule_accounts_consistently(name):
         assert 0 < r["peak_live_bytes"] <= r["workspace_bytes"]
         assert r["peak_live_bytes_sequential"] == seq["peak_live_bytes"]
         assert r["n_regions"] == c.k * (tensors * L - 1)
-        assert r["max_ref_count"] == 2
+        assert r["max_ref_count"] == (2 if w.shape.n_experts else 1)     # only the routing result has two readers (gate/up, down)
         if c.form in (B.DYN_FORM_SEQUENTIAL, B.DYN_FORM_SPLIT):
             assert r["n_resharded"] == 0          # producer and consumers always at the same number of micro-batches
         else:

@@ -118,6 +118,9 @@ def config(name: str) -> Workload:
         ctx = _uniform_ctx(0, 256, 1024, 8192)
         sh = dataclasses.replace(LLAMA3_8B, n_layers=32)
         return Workload("c5", sh, tuple((1, c) for c in ctx), 0, (0, 128, 256))
+    if name == "c5_layer":      # one layer of c5 (same sequences): quick operator-level measurements of the 256-row decode regime
+        ctx = _uniform_ctx(0, 256, 1024, 8192)
+        return Workload("c5_layer", LLAMA3_8B, tuple((1, c) for c in ctx), 0, (0, 128, 256))
     if name == "d300":          # full layer shape at 300 rows: the 384-row projection tile next to 256-row tiles when split
         ctx = _uniform_ctx(20, 300, 1, 300)
         return Workload("d300", LLAMA3_8B, tuple((1, c) for c in ctx), 20, (0, 150, 300))
