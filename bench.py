@@ -180,6 +180,35 @@ def cpu_baseline(w, data, n_sample=128):
                       % (len(picks), w.n_seqs, dt_s)}
 
 
+def prefill_decode_mix(B, gen, stream, steps, warmup, prefill=512, decodes=64, ctx=2048):
+    """Where the method's premise holds on this GPU: a chunked-prefill step - one prefill chunk of a few hundred tokens
+    beside decode sequences (Section 2.1 "Splitting", Section 5.3.1) - under the sequential order and under the
+    library's own policy (which records a two-micro-batch split at the prefill / decode boundary when its cost model
+    predicts a gain), one Llama-3-8B-shaped layer, HIP-graph replays, medians of per-step event times."""
+    import torch
+    w = gen.mixed(prefill, decodes, ctx)
+    data = gen.generate(w, device="cuda:0")
+    layer = B.DynLayer(B.make_config(w.shape), data["weights"])
+    step = B.DeviceStep(layer, data)
+    md = gen.metadata(w)
+    sched, choice = B.Scheduler(B.make_config(w.shape), md["q_start"]).auto(md["ctx_len"], use_graph=True)
+    t_seq = time_schedule(layer, step, B.sequential(use_graph=True), stream, steps, warmup)
+    out = {"workload": "%s: %d-token prefill chunk + %d decodes at context %d, 1 layer" % (w.name, prefill, decodes, ctx),
+           "tokens": w.n_tokens, "sequential_ms": t_seq["median_ms"], "policy_choice": "split" if choice["split"] else "sequential",
+           "policy_est_sequential_us": choice["est_sequential_us"], "policy_est_split_us": choice["est_split_us"]}
+    if choice["split"]:
+        t_pol = time_schedule(layer, step, sched, stream, steps, warmup)
+        y_split = step.y.clone()
+        layer.forward(step.batch, B.sequential(use_graph=True), stream)
+        torch.cuda.synchronize()
+        out.update({"policy_ms": t_pol["median_ms"], "policy_stats_ms": t_pol, "speedup_over_sequential": t_seq["median_ms"] / t_pol["median_ms"],
+                    "tokens_per_s_sequential": w.n_tokens / (t_seq["median_ms"] * 1e-3), "tokens_per_s_policy": w.n_tokens / (t_pol["median_ms"] * 1e-3),
+                    "bit_identical_to_sequential": bool(torch.equal(y_split.view(torch.uint8), step.y.view(torch.uint8)))})
+    del step, layer, data
+    torch.cuda.empty_cache()
+    return out
+
+
 def policy_sweep(args):
     """Where splitting starts to pay: a prefill chunk of P tokens beside D decode sequences at
     context C, Llama-3-8B layer.  For every point: measured sequential and split (two
@@ -281,6 +310,7 @@ def main():
     ap.add_argument("--tune", action="store_true",
                     help="also run the library's measured search over micro-batch sizes, forms and CU shares and time its choice")
     ap.add_argument("--no-event-profile", action="store_true", help="skip the per-operator HIP-event pass")
+    ap.add_argument("--no-mix", action="store_true", help="skip the chunked-prefill + decode step timed beside the main workload")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
     ap.add_argument("--copy-probe", action="store_true",
@@ -443,6 +473,9 @@ def main():
         "roofline": dict(roofline, traffic=traffic["bytes"] if traffic and roofline["kernel"] == "attn_mfma_kernel" else None,
                          traffic_source=traffic["source"] if traffic and roofline["kernel"] == "attn_mfma_kernel" else None),
     }
+    if not args.no_mix:
+        out["prefill_decode_mix"] = prefill_decode_mix(B, gen, stream, min(args.steps, 100), args.warmup)
+        log("prefill + decode mix: %s" % out["prefill_decode_mix"])
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample ...")
         out["cpu_baseline"] = cpu_baseline(w, data, 128 if w.shape.n_layers == 1 else 16)

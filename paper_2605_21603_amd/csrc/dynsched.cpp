@@ -162,12 +162,19 @@ OpCost estimate(const dyn_scheduler *s, const int32_t *ctx_len, int r0, int r1) 
 }
 
 // Two streams that run side by side share the CUs' memory pipelines: while a decode-attention
-// kernel streams K/V, a co-resident projection kernel advances at about a fifth of its own
-// speed (its L2 reads queue behind the attention's HBM reads), so the makespan of a prefill
-// micro-batch beside a decode micro-batch is the longer stream plus almost all of the shorter
-// one.  Measured over prefill chunks of 256..4096 tokens beside 64..256 decodes at contexts
-// 2048..8192: split / (sum of the two streams' own estimates) = 0.93..1.0.
-constexpr double kUnhiddenShare = 0.95;
+// kernel streams K/V, a co-resident projection kernel advances at a fraction of its own speed
+// (its L2 reads queue behind the attention's HBM reads), so the makespan of a prefill
+// micro-batch beside a decode micro-batch is the longer stream plus most of the shorter one.
+// How much of the shorter one stays unhidden grows with the prefill chunk: small chunks leave
+// CUs and launch gaps for the other stream, 2048 tokens and more fill the chip round after
+// round.  Fitted to prefill chunks of 256..4096 tokens beside 64..256 decodes at contexts
+// 2048..8192 (measured split time = longer + share x shorter, estimates scaled to the measured
+// sequential time): 0.58-0.76 at 256 tokens, 0.77-0.81 at 512, 0.71-0.88 at 1024, 0.90-0.99 at 2048.
+double unhidden_share(int prefill_tokens) {
+    if (prefill_tokens <= 384) return 0.62;
+    if (prefill_tokens <= 1536) return 0.80;
+    return 0.93;
+}
 
 }  // namespace
 
@@ -325,12 +332,13 @@ dyn_status dyn_policy_auto(dyn_scheduler *s, const int32_t *ctx_len_host, int us
     double t_split = 0;
     if (cut > 0) {
         const double a = estimate(s, ctx_len_host, 0, cut).total(), b = estimate(s, ctx_len_host, cut, T).total();
-        t_split = std::max(a, b) + kUnhiddenShare * std::min(a, b);
+        const int multi_rows = s->q_start[1] - s->q_start[0] > 1 ? cut : T - cut;     // tokens of the multi-token side of the cut
+        t_split = std::max(a, b) + unhidden_share(multi_rows) * std::min(a, b);
     }
     // The model is good to about 5-8 % on mixes of 256..4096 prefill tokens and 64..256 decodes,
-    // but its errors on the two orders go the same way: on those mixes every predicted gain of
-    // 1.5 % or more was a measured gain.  Below that the extra streams are not worth recording.
-    const bool split = cut > 0 && t_split < 0.985 * t_seq;
+    // but its errors on the two orders go the same way.  A predicted gain below 1 % is not worth
+    // the extra streams.
+    const bool split = cut > 0 && t_split < 0.99 * t_seq;
     if (choice) {
         choice->split = split;
         choice->cut_row = split ? cut : 0;
