@@ -11,6 +11,7 @@
 #include <cstdlib>
 
 #include <algorithm>
+#include <utility>
 #include "common.h"
 #include "kernels.h"
 
@@ -102,6 +103,34 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
 #undef DYN_W
 }
 
+// One 16-byte LDS read per lane, as inline assembly so that its wait is placed by hand (wait_lgkmcnt).
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds_read offset field");
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {                   // s_waitcnt lgkmcnt(N) only (vmcnt 63, expcnt 7 = no wait)
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));
+}
+
+// The MFMA as inline assembly, so that the many-row loop's instruction order is the one written down.
+// The compiler neither sees the instruction's latency nor orders anything around it: the caller keeps
+// dependent uses of an accumulator far apart and waits before reading it as an ordinary register.
+__device__ __forceinline__ void mfma_acc(f32x4 &c, const bf16x8 &a, const bf16x8 &b) {
+    asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
+}
+template <int I0, int I1, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>());
+        static_for<I0 + 1, I1>(f);
+    }
+}
+
 template <int BN, int MT, bool INREG, int NS, bool GATED, int NW>
 __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 1024) ? 2 : 1) void gemm_bf16_kernel(
     const bf16_t *__restrict__ X, int ldx, const bf16_t *__restrict__ W, const bf16_t *__restrict__ R,
@@ -114,6 +143,7 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     static_assert(ROWS % (NW * 8) == 0, "the stage's rows must divide among the waves' direct loads");
     constexpr int STAGE = ROWS * ROWB;              // bytes; NS of them form the ring
     constexpr int NA = RW / 16, NB = MT / (16 * WMW);       // 16-row operand tiles per wave
+    constexpr bool PIPE = MT >= 256;                // the hand-laid-out loop: it pays from 256-row tiles on (128-row tiles: 1-2 % slower with it)
     extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
     const int m_tiles = (M + MT - 1) / MT;
     // Workgroup ids are dealt round-robin to the 8 XCDs.  Tiles that share W rows (the
@@ -180,17 +210,24 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
     const int rot_group = (GATED ? n_tile * (BN / 2) / 64 : n0 / 128) / kRotGroup;   // by output column, the same for every tile shape
     const int rot = (int)(((unsigned)rot_group * kRotStep) % (unsigned)plane_stages);
     int iss_w = 0, iss_base = 0;                       // next stage to issue: index inside its plane, plane's first stage
-    auto issue = [&](int st) {                         // all direct loads of stage st into ring buffer st % NS; st ascends by one per call
-        unsigned char *buf = lds + (st % NS) * STAGE;
-        int kst = iss_w + rot;
-        if (kst >= plane_stages) kst -= plane_stages;
-        kst += iss_base;
+    unsigned char *iss_buf = lds;                      // the pending stage's ring buffer and k offset (issue_begin / issue_one)
+    int iss_kst = 0;
+    auto issue_begin = [&](int st) {                   // stage st goes into ring buffer st % NS; st ascends by one per call
+        iss_buf = lds + (st % NS) * STAGE;
+        iss_kst = iss_w + rot;
+        if (iss_kst >= plane_stages) iss_kst -= plane_stages;
+        iss_kst += iss_base;
         if (++iss_w == plane_stages) { iss_w = 0; iss_base += plane_stages; }
+    };
+    auto issue_one = [&](int j) {                      // direct load j of the stage begun last
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)iss_kst * BK),
+                                         (__attribute__((address_space(3))) void *)(iss_buf + (j * NW + wave) * 8 * ROWB),
+                                         16, 0, 0);
+    };
+    auto issue = [&](int st) {                         // all direct loads of stage st
+        issue_begin(st);
 #pragma unroll
-        for (int j = 0; j < LPS; ++j)
-            __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(src[j] + (size_t)kst * BK),
-                                             (__attribute__((address_space(3))) void *)(buf + (j * NW + wave) * 8 * ROWB),
-                                             16, 0, 0);
+        for (int j = 0; j < LPS; ++j) issue_one(j);
     };
 
     f32x4 acc[NA][NB], total[INREG ? NA : 1][INREG ? NB : 1];
@@ -215,17 +252,134 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
         b_off[b] = row * ROWB + ((lq ^ ((row >> 1) & 7)) << 4);
     }
 
+    auto fold_plane = [&](int st) {                    // a plane ends: fold its sum into the total, start from zero
+        if (INREG && (st + 1) % plane_stages == 0) {
 #pragma unroll
-    for (int d = 0; d < NS - 1; ++d)
-        if (d < n_stage) issue(d);
-    for (int st = 0; st < n_stage; ++st) {
-        // stage st has landed when at most the loads of the stages issued after it are outstanding
+            for (int a = 0; a < NA; ++a)
+#pragma unroll
+                for (int b = 0; b < NB; ++b) {
+                    total[a][b] += acc[a][b];
+                    acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
+                }
+        }
+    };
+    auto wait_stage = [&](int st) {                    // stage st has landed when at most the loads of the stages issued after it are outstanding
         const int ahead = min(NS - 2, n_stage - 1 - st);
         if (ahead >= 4) wait_vmcnt(4 * LPS);
         else if (ahead == 3) wait_vmcnt(3 * LPS);
         else if (ahead == 2) wait_vmcnt(2 * LPS);
         else if (ahead == 1) wait_vmcnt(LPS);
         else wait_vmcnt(0);
+    };
+
+    if constexpr (PIPE) {
+        // Many rows: the matrix cores are the bound, and what keeps them waiting is everything that comes
+        // in bursts - a block of operand reads before a block of MFMAs, all of a stage's direct loads
+        // right after the barrier.  So the loop is laid out by hand, as inline assembly that the
+        // compiler neither reorders nor waits for.  A stage is four steps, (k half 0 | 1) x (first |
+        // second half of the wave's X tiles).  While the MFMAs of a step issue, the operands of the
+        // next step are read from LDS, one read every few MFMAs, across the stage boundary too; the
+        // direct loads of the stage that refills this stage's buffer are spread over the last step in
+        // the same way.  When a step begins, all that is outstanding is what the previous step read,
+        // so lgkmcnt(0) opens it (LDS reads return in order; nothing newer is in flight).  An
+        // accumulator is used once per step, so dependent MFMAs are never close.  Every accumulator
+        // still receives its k halves and stages in ascending order: the same bits as the plain loop.
+        constexpr int H0 = (NB + 1) / 2, H1 = NB - H0, TILE = 16 * ROWB;   // X tiles of the first and of the second half
+        bf16x8 a_cur[NA], a_nxt[NA], b_lo[H0], b_hi[H1];
+        // Operand tile i of a kind sits 16 rows = TILE bytes after tile 0 (the swizzle depends on the
+        // row's low four bits only), so one address per (kind, k half) and an immediate offset do.
+        const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+        const unsigned a_adr[2] = {lds0 + (unsigned)a_off[0], lds0 + (unsigned)(a_off[0] ^ 64)};
+        const unsigned b_adr[2] = {lds0 + (unsigned)b_off[0], lds0 + (unsigned)(b_off[0] ^ 64)};
+        // The MFMAs of av x bv into accumulator columns b0 .. b0 + hb, with item(0) .. item(n_items - 1)
+        // spread evenly between them.
+        auto step = [&](const bf16x8 (&av)[NA], const auto &bv, auto b0, auto hb, auto n_items, auto &&item) {
+            constexpr int B0 = decltype(b0)::value, M = NA * decltype(hb)::value, T = decltype(n_items)::value;
+            static_for<0, M>([&](auto i) {
+                constexpr int I = decltype(i)::value;
+                mfma_acc(acc[I % NA][B0 + I / NA], av[I % NA], bv[I / NA]);
+                static_for<0, T>([&](auto k) {
+                    if constexpr (decltype(k)::value * M / T == I) item(k);
+                });
+            });
+        };
+        const std::integral_constant<int, 0> c0;
+        const std::integral_constant<int, H0> ch0;
+        const std::integral_constant<int, H1> ch1;
+        // All NS ring buffers are filled before the loop; stage st + NS is issued into the buffer of
+        // stage st once every wave has taken its last operands out of it.
+#pragma unroll
+        for (int d = 0; d < NS; ++d)
+            if (d < n_stage) issue(d);
+        {
+            const int ahead = min(NS - 1, n_stage - 1);
+            if (ahead >= 3) wait_vmcnt(3 * LPS);
+            else if (ahead == 2) wait_vmcnt(2 * LPS);
+            else if (ahead == 1) wait_vmcnt(LPS);
+            else wait_vmcnt(0);
+        }
+        __builtin_amdgcn_s_barrier();
+        static_for<0, NA>([&](auto k) { a_cur[decltype(k)::value] = lds_read16<decltype(k)::value * TILE>(a_adr[0]); });
+        static_for<0, H0>([&](auto k) { b_lo[decltype(k)::value] = lds_read16<decltype(k)::value * TILE>(b_adr[0]); });
+        for (int st = 0; st < n_stage; ++st) {
+            const unsigned so = (unsigned)(st % NS) * STAGE;
+            const unsigned a1 = a_adr[1] + so, b0 = b_adr[0] + so, b1 = b_adr[1] + so;
+            wait_lgkmcnt<0>();
+            step(a_cur, b_lo, c0, ch0, ch1, [&](auto k) {
+                constexpr int K = decltype(k)::value;
+                b_hi[K] = lds_read16<(H0 + K) * TILE>(b0);
+            });
+            wait_lgkmcnt<0>();
+            step(a_cur, b_hi, ch0, ch1, std::integral_constant<int, NA + H0>(), [&](auto k) {
+                constexpr int K = decltype(k)::value;
+                if constexpr (K < NA) a_nxt[K] = lds_read16<K * TILE>(a1);
+                else b_lo[K - NA] = lds_read16<(K - NA) * TILE>(b1);
+            });
+            wait_lgkmcnt<0>();
+            step(a_nxt, b_lo, c0, ch0, ch1, [&](auto k) {
+                constexpr int K = decltype(k)::value;
+                b_hi[K] = lds_read16<(H0 + K) * TILE>(b1);
+            });
+            wait_lgkmcnt<0>();                     // this wave has taken its last operands out of stage st's buffer
+            // One path for every stage, the last included (a second copy of the step's assembly would
+            // give each accumulator two definitions to merge at the loop's head): after the last stage
+            // the reads fetch operands nobody uses from the other ring buffer, and nothing is issued.
+            wait_stage(st + 1);
+            __builtin_amdgcn_s_barrier();          // every wave is done with the buffer and sees stage st + 1
+            const unsigned no = (unsigned)((st + 1) % NS) * STAGE;
+            const unsigned na = a_adr[0] + no, nb = b_adr[0] + no;
+            const bool refill = st + NS < n_stage;
+            if (refill) issue_begin(st + NS);
+            // reads and direct loads alternate while both last, then the rest of the longer list
+            constexpr int R = NA + H0, PAIRS = R < LPS ? R : LPS;
+            step(a_nxt, b_hi, ch0, ch1, std::integral_constant<int, R + LPS>(), [&](auto k) {
+                constexpr int K = decltype(k)::value;
+                constexpr bool is_read = K < 2 * PAIRS ? K % 2 == 0 : R > LPS;
+                constexpr int idx = K < 2 * PAIRS ? K / 2 : K - PAIRS;
+                if constexpr (is_read) {
+                    if constexpr (idx < NA) a_cur[idx] = lds_read16<idx * TILE>(na);
+                    else b_lo[idx - NA] = lds_read16<(idx - NA) * TILE>(nb);
+                } else {
+                    if (refill) issue_one(idx);
+                }
+            });
+            if (INREG && (st + 1) % plane_stages == 0) {
+                // the compiler does not know that the assembly's results arrive late: the last MFMAs
+                // must have left the pipeline before the accumulators are read as ordinary registers,
+                // and the cleared accumulators must be written before the next MFMA reads them
+                asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+                fold_plane(st);
+                asm volatile("s_nop 7" ::: "memory");
+            }
+        }
+        wait_lgkmcnt<0>();
+        asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    } else {
+#pragma unroll
+    for (int d = 0; d < NS - 1; ++d)
+        if (d < n_stage) issue(d);
+    for (int st = 0; st < n_stage; ++st) {
+        wait_stage(st);
         // Bare barrier: __syncthreads() would add a fence that drains every outstanding load, which
         // is exactly the prefetch.  The loads of stage st are complete (waited above) and, being
         // direct-to-LDS, visible once complete; the reads of stage st-1 were consumed by MFMAs.
@@ -245,15 +399,8 @@ __global__ __launch_bounds__(NW * 64, (NW == 4 && (BN + MT) * ROWB * NS <= 72 * 
                 for (int b = 0; b < NB; ++b)
                     acc[a][b] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(av[a], bv[b], acc[a][b], 0, 0, 0);
         }
-        if (INREG && (st + 1) % plane_stages == 0) {   // a plane ends: fold its sum into the total, start from zero
-#pragma unroll
-            for (int a = 0; a < NA; ++a)
-#pragma unroll
-                for (int b = 0; b < NB; ++b) {
-                    total[a][b] += acc[a][b];
-                    acc[a][b] = f32x4{0.f, 0.f, 0.f, 0.f};
-                }
-        }
+        fold_plane(st);
+    }
     }
 
     if (GATED) {
@@ -362,7 +509,7 @@ bool gemm_many_rows(int rows, int N) {      // enough 128 x 128 tiles for the ma
 }
 
 // 256 x 256 tiles, eight waves of 64 x 128 each: half the operand bytes moved into LDS per FLOP
-// of the 128 x 128 tile, which is what bounds the many-row kernel.  They pay once there are at
+// of the 128 x 128 tile.  They pay once there are at
 // least two m tiles and enough tiles to fill the chip (2112 x 28672 x 4096: 519 -> 432 us; 512
 // rows: 164 -> 121 us; 400 rows: 128 us with a 512-row tall tile, 120 us here).  Not for planes
 // folded in registers: the second accumulator set does not fit.
