@@ -117,6 +117,31 @@ def measure_stream_read(B, buf, stream, reps=7):
             "kernel": "stream_read_kernel (16-byte loads, read only, 2048 x 256 threads, grid-strided)"}
 
 
+def measure_mfma_loop(B, device, stream, n_stages=4096, reps=3):
+    """TFLOP/s of the library's matrix-core probe (the wide projection tile's main loop on L2-resident operands) with
+    random bf16 operands N(0, 1) - what the projections work on - and with zeros."""
+    import torch
+    sink = torch.empty(256 * 512, dtype=torch.float32, device=device)
+    gen_ = torch.Generator(device=device)
+    gen_.manual_seed(1234)
+    out = {}
+    for name, buf in (("random_operands", torch.randn(8 << 20, dtype=torch.float32, device=device, generator=gen_).to(torch.bfloat16)),
+                      ("zero_operands", torch.zeros(8 << 20, dtype=torch.bfloat16, device=device))):
+        evs = [torch.cuda.Event(enable_timing=True) for _ in range(reps + 1)]
+        with torch.cuda.stream(stream):
+            flops = B.probe_mfma_loop(buf, n_stages, sink, stream)
+            evs[0].record(stream)
+            for i in range(reps):
+                B.probe_mfma_loop(buf, n_stages, sink, stream)
+                evs[i + 1].record(stream)
+        torch.cuda.synchronize()
+        ms = statistics.median(evs[i].elapsed_time(evs[i + 1]) for i in range(reps))
+        out[name] = {"TFLOP/s": flops / 1e12 / (ms * 1e-3), "median_ms": ms}
+    out["kernel"] = ("mfma_loop_probe_kernel (256 workgroups x 8 waves, %d stages of 64 MFMA 16x16x32 bf16 per wave with LDS operand "
+                     "reads, a barrier and 64 KB of direct loads per stage)" % n_stages)
+    return out
+
+
 def attention_bytes(w):
     """Algorithmic HBM bytes of one attention launch: every cached position of every kv head
     read once, K and V (4096 B per position for the Llama-3-8B shape), plus q in and o out."""
@@ -371,6 +396,10 @@ def main():
     results = {k: r["median_ms"] for k, r in stats.items()}
     stream_read = measure_stream_read(B, step.k_cache, stream)
     log("streaming read of resident cache: %.0f GB/s" % stream_read["GB/s"])
+    mfma_loop = measure_mfma_loop(B, step.k_cache.device, stream) if w.shape.dtype == "bf16" else None
+    if mfma_loop:
+        log("matrix-core loop probe: %.0f TFLOP/s on random operands, %.0f on zeros"
+            % (mfma_loop["random_operands"]["TFLOP/s"], mfma_loop["zero_operands"]["TFLOP/s"]))
     # the library's measured tuner: unequal micro-batch sizes, forms, staggers, CU shares
     md = gen.metadata(w)
     tuned = None
@@ -463,6 +492,7 @@ def main():
         "schedules_ms": results,
         "schedules_stats_ms": stats,
         "hbm": {"peak_GB/s": HBM_PEAK_GBS, "measured_stream_read": stream_read},
+        "mfma": {"peak_TFLOP/s": MFMA_BF16_PEAK_TFLOPS, "measured_loop": mfma_loop},
         "tuned": tuned,
         "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",
                    "est_sequential_ms_per_layer": policy["est_sequential_us"] * 1e-3,
@@ -473,6 +503,11 @@ def main():
         "roofline": dict(roofline, traffic=traffic["bytes"] if traffic and roofline["kernel"] == "attn_mfma_kernel" else None,
                          traffic_source=traffic["source"] if traffic and roofline["kernel"] == "attn_mfma_kernel" else None),
     }
+    # the same kernel against what this machine's memory system / matrix cores gave the library's probes in this run
+    if out["roofline"]["bound"] == "hbm":
+        out["roofline"]["frac_of_measured_stream_read"] = out["roofline"]["achieved"] / stream_read["GB/s"]
+    elif mfma_loop:
+        out["roofline"]["frac_of_measured_loop_random_operands"] = out["roofline"]["achieved"] / mfma_loop["random_operands"]["TFLOP/s"]
     if not args.no_mix:
         out["prefill_decode_mix"] = prefill_decode_mix(B, gen, stream, min(args.steps, 100), args.warmup)
         log("prefill + decode mix: %s" % out["prefill_decode_mix"])

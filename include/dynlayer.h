@@ -439,6 +439,19 @@ dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const int32_t *ctx
  * caller times it with events.  Allocates nothing. */
 dyn_status dyn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *hip_stream);
 
+/* The same for the compute-bound operator class (Section 2): the many-row projections are priced
+ * against the matrix cores' datasheet peak, and that figure assumes a clock the chip does not hold
+ * under load.  This launches the main loop of the library's 256 x 256-tile projection kernel stripped
+ * of its indexing - 256 workgroups of eight waves, per stage and wave 64 MFMA 16x16x32 bf16 with
+ * their LDS operand reads, one barrier and the direct loads that refill the other stage buffer -
+ * for n_stages stages (1 .. 2^20) on operands read from buf: DEVICE, 16-byte aligned, at least
+ * 16 MiB (more is ignored), bf16 bit patterns of the caller's choosing - the rate depends on
+ * them, zeros run about a third faster than random values.  sink: DEVICE, sink_bytes >= 524288,
+ * overwritten.  *flops (HOST, may be NULL) receives the floating-point operations of the launch.
+ * Asynchronous on hip_stream; the caller times it with events.  Allocates nothing. */
+dyn_status dyn_probe_mfma_loop(const void *buf, size_t bytes, int n_stages, void *sink, size_t sink_bytes,
+                               void *hip_stream, double *flops);
+
 /* Thread-local description of the last error returned on this thread ("" if none). */
 const char *dyn_last_error(void);
 

@@ -109,7 +109,7 @@ EXPORTS = ["dyn_layer_create", "dyn_layer_destroy", "dyn_layer_workspace_bytes",
            "dyn_scheduler_create", "dyn_scheduler_destroy", "dyn_scheduler_split", "dyn_scheduler_set_partitions",
            "dyn_scheduler_get_ready_ops", "dyn_scheduler_execute", "dyn_scheduler_finish", "dyn_policy_auto",
            "dyn_tune_candidates", "dyn_tune_record", "dyn_tune", "dyn_schedule_memory", "dyn_schedule_workspace_bytes",
-           "dyn_schedule_regions", "dyn_probe_hbm_read"]
+           "dyn_schedule_regions", "dyn_probe_hbm_read", "dyn_probe_mfma_loop"]
 
 _lib = None
 
@@ -133,6 +133,7 @@ def lib() -> C.CDLL:
         l.dyn_layer_release_graphs.argtypes = [C.c_void_p]
         l.dyn_layer_forward_noalloc.argtypes = [C.c_void_p, C.c_void_p, C.c_void_p]
         l.dyn_probe_hbm_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+        l.dyn_probe_mfma_loop.argtypes = [C.c_void_p, C.c_size_t, C.c_int, C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
         l.dyn_layer_set_profiling.argtypes = [C.c_void_p, C.c_int]
         l.dyn_layer_get_slot_times.argtypes = [C.c_void_p, C.c_void_p, C.c_int, C.c_void_p]
         l.dyn_scheduler_create.argtypes = [C.c_void_p, C.c_int, C.c_int, C.c_void_p, C.c_void_p]
@@ -447,6 +448,14 @@ def probe_hbm_read(buf: torch.Tensor, nbytes: int, sink: torch.Tensor, stream: t
     """One launch of the library's read-only streaming kernel over the first nbytes of buf."""
     assert sink.numel() * sink.element_size() >= 32768
     _check(lib().dyn_probe_hbm_read(_ptr(buf), nbytes, _ptr(sink), C.c_void_p(stream.cuda_stream)))
+
+
+def probe_mfma_loop(buf: torch.Tensor, n_stages: int, sink: torch.Tensor, stream: torch.cuda.Stream) -> float:
+    """One launch of the library's matrix-core probe on the operands in buf (>= 16 MiB); returns its FLOP count."""
+    flops = C.c_double(0.0)
+    _check(lib().dyn_probe_mfma_loop(_ptr(buf), buf.numel() * buf.element_size(), n_stages, _ptr(sink),
+                                     sink.numel() * sink.element_size(), C.c_void_p(stream.cuda_stream), C.byref(flops)))
+    return flops.value
 
 
 def make_config(sh) -> dyn_layer_config:

@@ -1274,6 +1274,17 @@ dyn_status dyn_probe_hbm_read(const void *buf, size_t bytes, void *sink, void *h
     return DYN_OK;
 }
 
+dyn_status dyn_probe_mfma_loop(const void *buf, size_t bytes, int n_stages, void *sink, size_t sink_bytes, void *hip_stream, double *flops) {
+    if (!buf || !sink || ((uintptr_t)buf & 15) || ((uintptr_t)sink & 3) || n_stages < 1 || n_stages > (1 << 20))
+        return fail(DYN_ERR_INVALID_ARG, "probe needs a 16-byte aligned buffer, a sink and 1 .. 2^20 stages");
+    if (bytes < dyn::mfma_probe_bytes() || sink_bytes < (size_t)256 * 512 * sizeof(float))
+        return fail(DYN_ERR_INVALID_ARG, "probe needs %zu bytes of operands and %zu bytes of sink", dyn::mfma_probe_bytes(), (size_t)256 * 512 * sizeof(float));
+    hipError_t e = dyn::launch_mfma_probe(buf, n_stages, (float *)sink, (hipStream_t)hip_stream);
+    if (e != hipSuccess) return fail(DYN_ERR_HIP, "launch of the matrix-core probe failed: %s", hipGetErrorString(e));
+    if (flops) *flops = dyn::mfma_probe_flops(n_stages);
+    return DYN_OK;
+}
+
 dyn_status dyn_layer_set_profiling(dyn_layer *L, int on) {
     if (!L) return fail(DYN_ERR_INVALID_ARG, "NULL layer");
     L->profiling = on != 0;

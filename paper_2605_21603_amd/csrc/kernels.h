@@ -141,5 +141,10 @@ hipError_t launch_reduce_rope(const float *P, size_t plane_stride, int S, void *
 
 // Measurement aid: reads `bytes` (a multiple of 16, 16-byte aligned) of buf once; sink receives 8192 words.
 hipError_t launch_stream_read(const void *buf, size_t bytes, uint32_t *sink, hipStream_t s);
+// Matrix-core probe (kernels_gemm.hip): n_stages stages of the wide projection tile's main loop on 256 workgroups,
+// operands from the first mfma_probe_bytes() of buf; sink takes 256 x 512 floats.
+size_t mfma_probe_bytes();
+double mfma_probe_flops(int n_stages);
+hipError_t launch_mfma_probe(const void *buf, int n_stages, float *sink, hipStream_t s);
 
 }  // namespace dyn

@@ -489,6 +489,82 @@ __global__ __launch_bounds__(256) void gemm_reduce_kernel(const float *__restric
     }
 }
 
+// Matrix-core probe: the main loop of the 256 x 256-tile kernel above without its indexing - eight
+// waves, one workgroup per CU, and per stage and wave 64 MFMAs with 24 operand reads from LDS spread
+// between them, one barrier, and eight direct loads (64 KB per workgroup) that refill the other
+// stage buffer - on operands that are whatever the caller's buffer holds.  Every workgroup walks a
+// 256 KB window of the first 16 MiB of the buffer again and again, so the loads hit L2.  What it
+// reaches is what the chip gives a loop of this shape with a schedule that has nothing left to
+// improve; it depends on the operands (the chip lowers its clock with the activity of its matrix
+// pipes: zeros run a third faster than random values), which is why the caller supplies them.
+constexpr size_t kMfmaProbeBytes = (size_t)16 << 20;
+__global__ __launch_bounds__(512) void mfma_loop_probe_kernel(const unsigned char *__restrict__ src, int n_stages, float *__restrict__ sink) {
+    constexpr int STAGE = 65536;
+    extern __shared__ __attribute__((aligned(1024))) unsigned char lds[];
+    const int tid = threadIdx.x, lane = tid & 63, wave = __builtin_amdgcn_readfirstlane(tid >> 6);
+    const int row = (lane & 15) + (wave & 3) * 64;
+    const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+    const unsigned addr = lds0 + row * 128 + (((lane >> 4) ^ ((row >> 1) & 7)) << 4);       // conflict-free 16-byte reads, as the projections' operand reads
+    const unsigned addr1 = addr ^ 64;                  // k half 1: the other half of the 128-byte row
+    const unsigned char *gsrc = src + (size_t)(blockIdx.x % 64) * 262144 + wave * 1024 + lane * 16;
+    auto load = [&](int st, int j) {        // 1 KB per wave: part j of stage st's 64 KB; offsets stay below 16 MiB and inside the two stage buffers
+        __builtin_amdgcn_global_load_lds((const __attribute__((address_space(1))) void *)(gsrc + ((st * 8 + j) & 31) * 8192),
+                                         (__attribute__((address_space(3))) void *)(lds + (st & 1) * STAGE + (j * 8 + wave) * 1024), 16, 0, 0);
+    };
+    f32x4 acc[32];
+    bf16x8 fa[2][4], fb[2][8];
+#pragma unroll
+    for (int i = 0; i < 32; ++i) acc[i] = f32x4{0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+    for (int j = 0; j < 8; ++j) load(0, j);
+    wait_vmcnt(0);
+    __builtin_amdgcn_s_barrier();
+    static_for<0, 4>([&](auto i) { fa[0][decltype(i)::value] = lds_read16<decltype(i)::value * 2048>(addr); });
+    static_for<0, 8>([&](auto i) { fb[0][decltype(i)::value] = lds_read16<16384 + decltype(i)::value * 2048>(addr); });
+    for (int st = 0; st < n_stages; ++st) {
+        const unsigned so1 = addr1 + (st & 1) * STAGE, sn = addr + ((st + 1) & 1) * STAGE;
+        // k half 0: its MFMAs, with the reads of k half 1 and the direct loads of the next stage between them
+        wait_lgkmcnt<0>();
+        static_for<0, 32>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            mfma_acc(acc[I], fa[0][I & 3], fb[0][I >> 2]);
+            if constexpr (I % 8 == 1 && I / 8 < 4) fa[1][I / 8] = lds_read16<(I / 8) * 2048>(so1);
+            if constexpr (I % 4 == 3) fb[1][I / 4] = lds_read16<16384 + (I / 4) * 2048>(so1);
+            if constexpr (I % 4 == 2) load(st + 1, I / 4);
+        });
+        // k half 1; the next stage's buffer is complete once every wave has waited for its loads and passed the barrier
+        wait_lgkmcnt<0>();
+        wait_vmcnt(0);
+        __builtin_amdgcn_s_barrier();
+        static_for<0, 32>([&](auto i) {
+            constexpr int I = decltype(i)::value;
+            mfma_acc(acc[I], fa[1][I & 3], fb[1][I >> 2]);
+            if constexpr (I % 8 == 1 && I / 8 < 4) fa[0][I / 8] = lds_read16<(I / 8) * 2048>(sn);
+            if constexpr (I % 4 == 3) fb[0][I / 4] = lds_read16<16384 + (I / 4) * 2048>(sn);
+        });
+    }
+    wait_lgkmcnt<0>();
+    asm volatile("s_nop 15\n\ts_nop 15" ::: "memory");
+    float v = 0.f;
+#pragma unroll
+    for (int i = 0; i < 32; ++i) v += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+    sink[(size_t)blockIdx.x * 512 + tid] = v;        // keeps the products alive
+}
+
+size_t mfma_probe_bytes() { return kMfmaProbeBytes; }
+double mfma_probe_flops(int n_stages) { return 256.0 * 8 * n_stages * 64 * (16.0 * 16 * 32 * 2); }
+
+hipError_t launch_mfma_probe(const void *buf, int n_stages, float *sink, hipStream_t s) {
+    static bool attr_set = false;
+    if (!attr_set) {
+        hipError_t e = hipFuncSetAttribute((const void *)mfma_loop_probe_kernel, hipFuncAttributeMaxDynamicSharedMemorySize, 2 * 65536);
+        if (e != hipSuccess) return e;
+        attr_set = true;
+    }
+    hipLaunchKernelGGL(mfma_loop_probe_kernel, dim3(256), dim3(512), 2 * 65536, s, (const unsigned char *)buf, n_stages, sink);
+    return hipGetLastError();
+}
+
 bool gemm_supported(int dtype, int N, int K) {
     if (dtype == 0) return N > 0 && K > 0;
     return N > 0 && K > 0 && N % 128 == 0 && K % BK == 0;

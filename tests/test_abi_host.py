@@ -149,3 +149,17 @@ def test_workspace_grows_with_tokens_and_context_not_with_k():
     assert layer.workspace_bytes(32, 8) > a
     assert layer.workspace_bytes(16, 64) > a
     assert layer.workspace_bytes(0, 0) >= 0
+
+
+def test_measurement_probes_reject_bad_arguments_before_touching_the_gpu():
+    l = B.lib()
+    assert l.dyn_probe_hbm_read(None, 1 << 20, None, None) == B.DYN_ERR_INVALID_ARG
+    flops = C.c_double(-1.0)
+    buf = C.create_string_buffer(64)                    # a host address: never dereferenced, the sizes are refused first
+    p = C.c_void_p((C.addressof(buf) + 15) & ~15)
+    assert l.dyn_probe_mfma_loop(None, 16 << 20, 8, p, 1 << 20, None, C.byref(flops)) == B.DYN_ERR_INVALID_ARG
+    assert l.dyn_probe_mfma_loop(p, (16 << 20) - 16, 8, p, 1 << 20, None, C.byref(flops)) == B.DYN_ERR_INVALID_ARG     # operands short of 16 MiB
+    assert l.dyn_probe_mfma_loop(p, 16 << 20, 8, p, 524288 - 4, None, C.byref(flops)) == B.DYN_ERR_INVALID_ARG         # sink too small
+    assert l.dyn_probe_mfma_loop(p, 16 << 20, 0, p, 1 << 20, None, C.byref(flops)) == B.DYN_ERR_INVALID_ARG            # no stages
+    assert flops.value == -1.0
+    assert b"16777216" in l.dyn_last_error() or b"stages" in l.dyn_last_error()

@@ -276,3 +276,27 @@ def test_schedule_sized_workspace_with_shared_regions_is_bit_exact(name):
         with pytest.raises(B.DynError) as e:
             run.layer.forward(step.batch, sched, st)
         assert e.value.status == B.DYN_ERR_WORKSPACE
+
+
+def test_matrix_core_probe_multiplies_what_it_says():
+    """The measurement aid behind bench.py's `mfma.measured_loop`: with every operand 1.0 each of a lane's 128
+    accumulator elements gains 32 per MFMA and sees two MFMAs per stage, so its sum is 8192 x stages exactly - the
+    probe issues the 64 MFMAs per wave and stage its FLOP count claims - and with zeros it is zero."""
+    dev = torch.device("cuda:0")
+    stream = torch.cuda.Stream()
+    sink = torch.full((256 * 512,), -1.0, dtype=torch.float32, device=dev)
+    ones = torch.ones(8 << 20, dtype=torch.bfloat16, device=dev)
+    zeros = torch.zeros(8 << 20, dtype=torch.bfloat16, device=dev)
+    torch.cuda.synchronize()
+    for stages in (1, 8, 13):
+        say("matrix-core probe, ones, %d stages" % stages)
+        flops = B.probe_mfma_loop(ones, stages, sink, stream)
+        torch.cuda.synchronize()
+        assert flops == 256 * 8 * stages * 64 * 16 * 16 * 32 * 2
+        assert torch.equal(sink, torch.full_like(sink, 8192.0 * stages))
+    say("matrix-core probe, zeros")
+    B.probe_mfma_loop(zeros, 5, sink, stream)
+    torch.cuda.synchronize()
+    assert torch.count_nonzero(sink).item() == 0
+    with pytest.raises(B.DynError):
+        B.probe_mfma_loop(ones[: (8 << 20) - 8], 4, sink, stream)
