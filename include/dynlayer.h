@@ -386,12 +386,13 @@ typedef struct {
 } dyn_tune_candidate;
 
 typedef struct {
-    int max_k;          /* largest number of micro-batches enumerated, 2..4 (0 = 2); dyn_tune itself times two */
+    int max_k;          /* largest number of micro-batches enumerated, 2..4 (0 = 2) */
     int partitions;     /* CU-partition sizes tried: 0 none, 1 half | half, 2 adds 3/4 | 1/4, 3 adds 1/4 | 3/4 */
     int n_cus;          /* CUs of the device (0 = 256); dyn_tune overwrites it with the device's count */
     int warmup, iters;  /* per candidate: untimed forwards, then three timed runs of iters forwards issued
                            back to back, median of the three means (0 = 2 and 7) */
-    int use_graph;      /* run candidates as HIP graph replays */
+    int use_graph;      /* the use_graph field of the schedule dyn_tune records; candidates are timed with
+                           eager launches either way (see dyn_tune) */
     float min_gain;     /* an overlapped candidate is chosen only if it beats the sequential order by this
                            fraction (negative = 0.02) */
 } dyn_tune_options;
@@ -417,14 +418,16 @@ int dyn_tune_candidates(const dyn_scheduler *s, const int32_t *ctx_len_host, con
  * partitions) and ends the recording into *out, as dyn_scheduler_finish does. */
 dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_cus, int use_graph, dyn_schedule *out);
 
-/* Times every candidate on the batch (replay loops on hip_stream, each followed by a wait
- * for its end event: this call blocks, allocates no device memory, and leaves y and the caches
- * as one forward leaves them) and records the winner into s / *out.  s must have been
- * created for this batch's structure.  table (may be NULL) receives the candidates with
- * their times, at most capacity of them.  DYN_ERR_HIP if even the sequential order fails;
- * DYN_ERR_UNSUPPORTED for opt->max_k > 2 (three and four micro-batches can be enumerated and
- * recorded with the two calls above and run as explicit schedules, but are not part of the
- * device search). */
+/* Times every candidate on the batch (loops of eager forwards on hip_stream, each followed by
+ * a wait for its end event: this call blocks, allocates no device memory, and leaves y and the
+ * caches as one forward leaves them) and records the winner into s / *out with opt->use_graph.
+ * s must have been created for this batch's structure.  table (may be NULL) receives the
+ * candidates with their times, at most capacity of them.  The search captures no HIP graph:
+ * one graph per candidate, destroyed after its replays, is a pattern under which long-lived
+ * processes have died inside the HIP runtime here; eager timing includes the host's launch
+ * cost, which weighs on candidates with more streams, so the search errs towards the
+ * sequential order.  DYN_ERR_HIP if even the sequential order fails; DYN_ERR_INVALID_ARG for
+ * opt->max_k outside 0..4. */
 dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const int32_t *ctx_len_host, const dyn_tune_options *opt,
                     void *hip_stream, dyn_scheduler *s, dyn_schedule *out, dyn_tune_result *result,
                     dyn_tune_candidate *table, int capacity);

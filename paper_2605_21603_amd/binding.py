@@ -340,8 +340,9 @@ class Scheduler:
 
     def tune(self, layer: "DynLayer", batch, stream, ctx_len: Optional[Sequence[int]] = None, max_k: int = 2,
              partitions: int = 0, warmup: int = 0, iters: int = 0, use_graph: bool = True, min_gain: float = -1.0):
-        """Times every candidate on the device and records the fastest: returns (schedule,
-        result dict, table of candidate dicts).  batch is a dyn_batch; stream a torch stream."""
+        """Times every candidate on the device (eager launches; use_graph marks the recorded schedule only) and
+        records the fastest: returns (schedule, result dict, table of candidate dicts).  batch is a dyn_batch;
+        stream a torch stream."""
         ctx = np.ascontiguousarray(ctx_len, dtype=np.int32) if ctx_len is not None else None
         opt = self._tune_options(max_k, partitions, 0, warmup, iters, use_graph, min_gain)
         cap = 256

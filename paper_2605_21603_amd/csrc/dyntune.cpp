@@ -58,17 +58,20 @@ extern "C" dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const i
     if (!layer || !batch || !opt_in || !s || !out || !result || capacity < 0 || (capacity > 0 && !table))
         return fail(DYN_ERR_INVALID_ARG, "NULL layer, batch, options, scheduler, output or result");
     dyn_tune_options opt = *opt_in;
-    if (opt.use_graph && !hip_stream) return fail(DYN_ERR_INVALID_ARG, "graph replays need a stream other than the null stream");
-    // More than two micro-batches are enumerated and recorded on the host but not timed here.  Tuning
-    // runs that capture, replay and destroy many graphs with three or four parallel branches have
-    // ended in a segmentation fault inside hipGraphLaunch (host side, in the runtime): with four
-    // micro-batches at the 50th graph of a process, and with three micro-batches - one graph alive
-    // at a time - late in a long process, while the same run alone in a fresh process went through.
-    // The library's own bookkeeping of streams, events, graphs and executables replays clean on the
-    // CPU under sanitizers against a stand-in runtime that checks every lifetime, so no cause in
-    // this library could be shown, and the case stays off the GPU.  Explicit schedules with up to
-    // eight micro-batches run and replay as graphs; only this search is limited.
-    if (opt.max_k > 2) return fail(DYN_ERR_UNSUPPORTED, "the device search covers two micro-batches (max_k = %d)", opt.max_k);
+    // Candidates are timed with eager launches, whatever opt.use_graph says; the flag only marks the
+    // schedule that is recorded at the end.  Timing them as graphs meant capturing, replaying and
+    // destroying one graph per candidate, dozens per search, in a process that goes on launching
+    // graphs - and searches of that kind have ended in a segmentation fault on the host, inside the
+    // runtime (in hipGraphLaunch where a stack could be read): with four micro-batches at the 50th
+    // graph of a process; with three micro-batches and one graph alive at a time, late in a long
+    // process; at last with two micro-batches, late in a long process, after the same run had
+    // passed many times.  The library's own bookkeeping of streams, events, graphs and executables
+    // replays clean on the CPU under sanitizers against a stand-in runtime that checks every
+    // lifetime, so no cause in this library could be shown; what the faults share is a graph
+    // destroyed soon after its last replay while others follow, and the search no longer does that.
+    // Eager timing carries the host's launch cost, which weighs on the candidates with more streams:
+    // the search errs towards the sequential order, never away from it.
+    if (opt.max_k < 0 || opt.max_k > 4) return fail(DYN_ERR_INVALID_ARG, "the search covers two to four micro-batches (max_k = %d)", opt.max_k);
     int dev = 0, n_cus = 0;
     if (hipGetDevice(&dev) != hipSuccess || hipDeviceGetAttribute(&n_cus, hipDeviceAttributeMultiprocessorCount, dev) != hipSuccess)
         return fail(DYN_ERR_HIP, "cannot read the device's CU count");
@@ -91,16 +94,13 @@ extern "C" dyn_status dyn_tune(dyn_layer *layer, const dyn_batch *batch, const i
     // CU-masked stream synchronises the device, which must not land inside a timed replay loop
     for (int i = 0; i < n; ++i) {
         dyn_schedule sched;
-        if (dyn_tune_record(s, &cand[i], n_cus, opt.use_graph, &sched) == DYN_OK) (void)dyn_layer_prepare(layer, &sched);
+        if (dyn_tune_record(s, &cand[i], n_cus, 0, &sched) == DYN_OK) (void)dyn_layer_prepare(layer, &sched);
     }
     int best = 0;
     for (int i = 0; i < n; ++i) {
         dyn_schedule sched;
-        dyn_status rc = dyn_tune_record(s, &cand[i], n_cus, opt.use_graph, &sched);
+        dyn_status rc = dyn_tune_record(s, &cand[i], n_cus, 0, &sched);
         if (rc == DYN_OK) cand[i].us = time_candidate(layer, batch, &sched, stream, ev, warmup, iters, &rc);
-        // a candidate is used once: its graph goes before the next one is captured, so at most one
-        // multi-stream executable is alive at any time during the search
-        if (opt.use_graph) (void)dyn_layer_release_graphs(layer);
         if (rc != DYN_OK) {
             if (i == 0) return rc;       // the sequential order must run; the error text is the forward's
             cand[i].us = -1.f;

@@ -83,9 +83,10 @@ bool load(const char *path, Setup &s) {
     return true;
 }
 
-// The device search of dyn_tune, step for step (prepare every candidate's streams, then per
-// candidate: warm-up forwards, three timed runs between two events, a stream synchronisation),
-// without its limit on the number of micro-batches.
+// The device search as it once was, step for step, with every candidate a HIP graph (prepare every
+// candidate's streams, then per candidate: warm-up forwards, three timed runs between two events, a
+// stream synchronisation) - the sequence that died inside the runtime on the GPU - and then dyn_tune
+// itself, which times the same candidates with eager launches.
 void tune_like(Setup &s, int max_k, int partitions, int warmup, int iters) {
     dyn_scheduler *sch = nullptr;
     EXPECT_OK(dyn_scheduler_create(&s.cfg, s.n_tokens, s.n_seqs, s.q_start.data(), &sch));
@@ -117,7 +118,7 @@ void tune_like(Setup &s, int max_k, int partitions, int warmup, int iters) {
         ++graphs;
     }
     fprintf(stderr, "replay: %d candidates, each captured, replayed and timed\n", graphs);
-    if (max_k <= 2) {                      // and the library's own search on the same batch
+    {                                      // and the library's own search on the same batch (eager launches, no graph)
         dyn_schedule out;
         dyn_tune_result res{};
         opt.warmup = warmup; opt.iters = iters;

@@ -19,25 +19,21 @@ def say(msg):
     print(msg, file=sys.stderr, flush=True)
 
 
-@pytest.mark.skip(reason="hipGraphLaunch of the 50th graph of a tuning run with four micro-batches (projections merged, "
-                         "the rest split over four plain streams, 13 tokens) ended in a segmentation fault inside the "
-                         "runtime; cause not shown (the library's host side replays clean under sanitizers on the CPU: "
-                         "tests/test_host_sanitizer.py), so the device search is limited to two micro-batches and this "
-                         "case stays off the GPU")
+# The searches below once timed every candidate as a HIP graph (capture, replay, destroy, dozens per search) and ended
+# in a segmentation fault inside the runtime three times - with four micro-batches at the 50th graph of a process, with
+# three late in the full suite, at last with two - without a cause that could be shown in this library (its host side
+# replays clean under sanitizers on the CPU: tests/test_host_sanitizer.py).  That code path is gone: dyn_tune times its
+# candidates with eager launches and captures nothing, so these cases run what every other eager test runs.
 def test_tuning_with_four_micro_batches():
     _tune_and_check("c2_small", 4, 1)
 
 
-@pytest.mark.skip(reason="a tuning run with three micro-batches on 13 tokens went through alone in a fresh process and "
-                         "ended in a segmentation fault inside the runtime (host side, during dyn_tune) when it ran late "
-                         "in the full suite, with one graph alive at a time; cause not shown, the device search refuses "
-                         "more than two micro-batches and these cases stay off the GPU")
 @pytest.mark.parametrize("name,max_k,partitions", [("c2_small", 3, 0), ("c5_small", 3, 1)])
 def test_tuning_with_three_micro_batches(name, max_k, partitions):
     _tune_and_check(name, max_k, partitions)
 
 
-def test_device_search_refuses_more_than_two_micro_batches():
+def test_device_search_rejects_more_than_four_micro_batches():
     w = gen.config("c2_small")
     data = gen.generate(w)
     run = GpuRun(w, data)
@@ -45,8 +41,8 @@ def test_device_search_refuses_more_than_two_micro_batches():
     step = B.DeviceStep(run.layer, data, run.device)
     sch = B.Scheduler(B.make_config(w.shape), md["q_start"])
     with pytest.raises(B.DynError) as e:
-        sch.tune(run.layer, step.batch, torch.cuda.Stream(), ctx_len=md["ctx_len"], max_k=3)
-    assert e.value.status == B.DYN_ERR_UNSUPPORTED
+        sch.tune(run.layer, step.batch, torch.cuda.Stream(), ctx_len=md["ctx_len"], max_k=5)
+    assert e.value.status == B.DYN_ERR_INVALID_ARG
 
 
 @pytest.mark.parametrize("name,max_k,partitions", [("c2_small", 2, 1), ("c3_small", 2, 1), ("c4_small", 2, 0),
