@@ -146,6 +146,9 @@ __global__ __launch_bounds__(256) void attn_combine_segments_kernel(float *__res
     if (sub == 0) { ml[0] = M; ml[1] = L; }
 }
 
+// Chunks whose partial outputs a half-wave has in flight at once in the final merge (the adds stay in chunk order).
+constexpr int kMergeLoads = 8;
+
 template <typename T, bool BASE2>
 __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restrict__ part_o,
                                                            const float *__restrict__ part_ml,
@@ -186,10 +189,10 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
         for (int off = 16; off >= 1; off >>= 1) wl += __shfl_xor(wl, off, 32);
         L += wl;
         const int nb = min(32, n_chunks - cb);
-        for (int j0 = 0; j0 < nb; j0 += 4) {
-            f32x4 v[4][2];
+        for (int j0 = 0; j0 < nb; j0 += kMergeLoads) {
+            f32x4 v[kMergeLoads][2];
 #pragma unroll
-            for (int j = 0; j < 4; ++j)
+            for (int j = 0; j < kMergeLoads; ++j)
 #pragma unroll
                 for (int q = 0; q < 2; ++q) {
                     const int i = sub * 4 + q * 128;
@@ -197,7 +200,7 @@ __global__ __launch_bounds__(256) void attn_combine_kernel(const float *__restri
                                                       : f32x4{0.f, 0.f, 0.f, 0.f};
                 }
 #pragma unroll
-            for (int j = 0; j < 4; ++j) {
+            for (int j = 0; j < kMergeLoads; ++j) {
                 const float wj = __shfl(wgt, j0 + j, 32);      // 0 beyond the last chunk
 #pragma unroll
                 for (int q = 0; q < 2; ++q) acc[q] += v[j][q] * wj;
