@@ -12,7 +12,8 @@ from gpu_util import GpuRun, check_against_oracle, say
 pytestmark = pytest.mark.gpu
 
 SMALL = ["c1", "f32_small", "c2_small", "c3_small", "c5_small", "c4_small", "f32_moe_small", "c3_mid", "pf_long", "pf_g8",
-         "pf_mha", "pf_480", "pf_640", "bf16_hd64", "bf16_ps32", "bf16_max", "stack_mixed", "pf_g16", "pf_g2", "pf_deep", "dec_deep", "moe_mid", "moe_many_a", "moe_many_b"]
+         "pf_mha", "pf_480", "pf_640", "bf16_hd64", "bf16_ps32", "bf16_max", "stack_mixed", "pf_g16", "pf_g2", "pf_deep", "dec_deep", "moe_mid", "moe_many_a", "moe_many_b",
+         "shallow_a", "shallow_b", "shallow_wide"]
 
 
 def schedules_for(w):

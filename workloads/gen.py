@@ -212,6 +212,16 @@ def config(name: str) -> Workload:
     if name == "moe_many_b":    # the other way round: gate/up with planes (not gated), 256 x 256 tiles for down
         sh = LayerShape("bf16", 1024, 8, 2, 128, 512, n_experts=4, top_k=2)
         return Workload("moe_many_b", sh, tuple((1, c) for c in _uniform_ctx(26, 700, 1, 40)), 26, (0, 300, 700))
+    if name == "shallow_a":     # contractions of one and two 64-deep stages (hidden 128, MLP width 64) under the 256-row tall tile
+        sh = LayerShape("bf16", 128, 1, 1, 128, 64)
+        return Workload("shallow_a", sh, tuple((1, c) for c in _uniform_ctx(28, 200, 1, 40)), 28, (0, 130, 200))
+    if name == "shallow_b":     # the same depths under the 384-row tall tile, a prefill chunk among the rows
+        sh = LayerShape("bf16", 128, 1, 1, 128, 64)
+        seqs = ((150, 150),) + tuple((1, c) for c in _uniform_ctx(29, 190, 1, 40))
+        return Workload("shallow_b", sh, seqs, 29, (0, 150, 340))
+    if name == "shallow_wide":  # two stages deep under the 256 x 256 tile (gate/up 1536 x 8192 x 128), 64 stages for down
+        sh = LayerShape("bf16", 128, 1, 1, 128, 4096)
+        return Workload("shallow_wide", sh, tuple((1, c) for c in _uniform_ctx(30, 1536, 1, 8)), 30, (0, 768, 1536))
     if name == "f32_small":
         sh = LayerShape("f32", 128, 4, 2, 32, 320, n_layers=2)
         seqs = ((9, 9), (1, 40), (1, 17), (5, 21), (1, 1))
