@@ -244,8 +244,11 @@ def policy_sweep(args):
     from workloads import gen
     rows, weights, layer = [], None, None
     stream = torch.cuda.Stream()
-    for P in (256, 512, 1024, 2048, 4096):
-        for D, Cx in ((64, 2048), (64, 8192), (256, 2048), (256, 8192)):
+    # "fit": the grid the policy's three overlap constants were fitted on; "holdout": points between and beside them
+    grid = {"fit": ((256, 512, 1024, 2048, 4096), ((64, 2048), (64, 8192), (256, 2048), (256, 8192))),
+            "holdout": ((384, 768, 1536, 3072), ((32, 4096), (128, 1024), (128, 4096), (192, 8192)))}[args.sweep_grid]
+    for P in grid[0]:
+        for D, Cx in grid[1]:
             w = gen.mixed(P, D, Cx)
             data = gen.generate(w, device="cuda:0")
             if layer is None:                       # the same layer weights serve every point
@@ -276,7 +279,7 @@ def policy_sweep(args):
             torch.cuda.empty_cache()
     agree = sum(r["policy_split"] == r["split_is_faster"] for r in rows)
     regret = [min(r["sequential_us"], r["split_us"]) / (r["split_us"] if r["policy_split"] else r["sequential_us"]) for r in rows]
-    print(json.dumps({"policy_sweep": rows, "policy_agrees_with_measurement": "%d of %d" % (agree, len(rows)),
+    print(json.dumps({"grid": args.sweep_grid, "policy_sweep": rows, "policy_agrees_with_measurement": "%d of %d" % (agree, len(rows)),
                       "worst_policy_efficiency": min(regret)}), flush=True)
 
 
@@ -338,6 +341,8 @@ def main():
     ap.add_argument("--no-mix", action="store_true", help="skip the chunked-prefill + decode step timed beside the main workload")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
+    ap.add_argument("--sweep-grid", default="fit", choices=["fit", "holdout"],
+                    help="--policy-sweep: the grid the policy's constants were fitted on, or a held-out one")
     ap.add_argument("--copy-probe", action="store_true",
                     help="only copy 1 GiB device-to-device five times (calibrates rocprofv3 FETCH_SIZE / WRITE_SIZE)")
     ap.add_argument("--trace-overlap", metavar="DB",
