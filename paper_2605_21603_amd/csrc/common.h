@@ -4,6 +4,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <type_traits>
+#include <utility>
+
 namespace dyn {
 
 typedef uint16_t bf16_t;   // raw bfloat16 storage word
@@ -43,6 +46,44 @@ __device__ __forceinline__ float wave_max(float v) {
 #pragma unroll
     for (int off = 32; off >= 1; off >>= 1) v = fmaxf(v, __shfl_xor(v, off, 64));
     return v;
+}
+
+// LDS operand reads as inline assembly, with their waits placed by hand (wait_lgkmcnt).  The compiler's own
+// wait insertion waits for every outstanding LDS read before each block of MFMAs, which serialises
+// reads and matrix products; reads it does not see it does not wait for.  The price: the compiler
+// believes a result is in its registers as soon as the read has been issued, so nothing but
+// instructions placed after the matching wait (and a scheduling barrier, where the consumer is not
+// assembly itself) may touch them.  LDS operations return in issue order, so "at most N outstanding"
+// means everything but the N most recent has arrived; LDS operations the compiler issues in between
+// can only make such a wait stricter, never laxer.
+template <int OFFSET>
+__device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {        // 16 bytes per lane at LDS byte address addr + OFFSET
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds_read offset field");
+    bf16x8 v;
+    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+    return v;
+}
+template <int OFFSET>
+__device__ __forceinline__ u32x2 lds_read8(unsigned addr) {          // 8 bytes per lane
+    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds_read offset field");
+    u32x2 v;
+    asm volatile("ds_read_b64 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
+    return v;
+}
+template <int N>
+__device__ __forceinline__ void wait_lgkmcnt() {                   // s_waitcnt lgkmcnt(N) only (vmcnt 63, expcnt 7 = no wait)
+    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
+    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));
+}
+
+// f(integral_constant<int, I0>), ..., f(integral_constant<int, I1 - 1>): a loop whose index is a compile-time
+// constant in the body (immediate offsets of the assembly above, register-array indices).
+template <int I0, int I1, class F>
+__device__ __forceinline__ void static_for(F &&f) {
+    if constexpr (I0 < I1) {
+        f(std::integral_constant<int, I0>());
+        static_for<I0 + 1, I1>(f);
+    }
 }
 
 // Split-KV chunk size (cached positions per work item) of a query block of a multi-token

@@ -149,6 +149,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
         // twice as many banks as the plain layout.
         const int v_off = lr * 32 + ((((lq >> 1) ^ (lr >> 2)) & 1) << 4) + ((lq & 1) << 3);
 
+        // Operand reads from the ring are assembly with hand-placed waits (common.h): a page's K operands are
+        // read while the previous page's score products issue, a V operand group while the previous group's
+        // value products issue.  The K operand of k
+        // step ks sits in 16-byte column (4 ks + lq) ^ (lr & 7) of row lr: two lane addresses (bit 2 of
+        // the column is ks & 1 flipped by bit 2 of the row) and an immediate of 0 or 128 bytes.
+        const unsigned lds0 = (unsigned)(uintptr_t)(__attribute__((address_space(3))) unsigned char *)lds;
+        const unsigned k_lane0 = lr * 256 + (((lq ^ (lr & 3)) + 4 * ((lr >> 2) & 1)) << 4);
+        const unsigned k_lane1 = lr * 256 + (((lq ^ (lr & 3)) + 4 * (((lr >> 2) & 1) ^ 1)) << 4);
+
         issue(0);
         issue(1);
         for (int ti = 0; ti < n_tile; ++ti) {
@@ -159,21 +168,36 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
             if (key0 >= wave_keys) continue;                              // wave-uniform: nothing of this tile is visible to the wave
             const unsigned char *kb = lds + (ti % kRing) * kTile, *vb = kb + kTP * 4096;
 
+            const unsigned tb = lds0 + (unsigned)(ti % kRing) * kTile;
+            const unsigned ka0 = tb + k_lane0, ka1 = tb + k_lane1, va = tb + kTP * 4096 + (unsigned)v_off;
+            auto read_k = [&](bf16x8 (&kf)[4], auto pi) {
+                constexpr int OFF = decltype(pi)::value * 4096;
+                kf[0] = lds_read16<OFF>(ka0);
+                kf[1] = lds_read16<OFF>(ka1);
+                kf[2] = lds_read16<OFF + 128>(ka0);
+                kf[3] = lds_read16<OFF + 128>(ka1);
+            };
             f32x4 sv[kSets][kTP];                                         // raw scores q . k
-#pragma unroll
-            for (int pi = 0; pi < kTP; ++pi) {
-                bf16x8 kf[4];
-#pragma unroll
-                for (int ks = 0; ks < 4; ++ks)
-                    kf[ks] = *reinterpret_cast<const bf16x8 *>(kb + pi * 4096 + lr * 256 + (((ks * 4 + lq) ^ (lr & 7)) << 4));
+            bf16x8 kf[2][4];
+            read_k(kf[0], std::integral_constant<int, 0>());
+            static_for<0, kTP>([&](auto pi_c) {
+                constexpr int pi = decltype(pi_c)::value;
+                if constexpr (pi + 1 < kTP) {
+                    read_k(kf[(pi + 1) & 1], std::integral_constant<int, pi + 1>());
+                    wait_lgkmcnt<4>();                                    // page pi's four operands have arrived
+                } else {
+                    wait_lgkmcnt<0>();
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int q = 0; q < kSets; ++q) {
                     f32x4 s = f32x4{0.f, 0.f, 0.f, 0.f};
 #pragma unroll
-                    for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[ks], qb[q][ks], s, 0, 0, 0);
+                    for (int ks = 0; ks < 4; ++ks) s = __builtin_amdgcn_mfma_f32_16x16x32_bf16(kf[pi & 1][ks], qb[q][ks], s, 0, 0, 0);
                     sv[q][pi] = s;
                 }
-            }
+                __builtin_amdgcn_sched_barrier(0);
+            });
             __builtin_amdgcn_sched_barrier(0);
             // Causal mask: only the last tiles of a block have positions that some live column of
             // the wave must not see (wave-uniform test).
@@ -229,6 +253,15 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
                     for (int dt = 0; dt < 8; ++dt) acc[q][dt] *= alpha[q];
                 }
             }
+            // V operands of output rows 16 dt .. 16 dt + 15, one 8-byte read per page; group 0 is in flight
+            // during the denominator's products and the mask arithmetic below
+            u32x2 vx[2][kTP];
+            auto read_v = [&](u32x2 (&x)[kTP], auto dt_c) {
+                static_for<0, kTP>([&](auto pi_c) {
+                    x[decltype(pi_c)::value] = lds_read8<decltype(pi_c)::value * 4096 + decltype(dt_c)::value * 512>(va);
+                });
+            };
+            read_v(vx[0], std::integral_constant<int, 0>());
             // the denominator sums the probabilities exactly as the value product sees them (rounded
             // to bf16): one more matrix product, against a block of ones
 #pragma unroll
@@ -245,20 +278,26 @@ __global__ __launch_bounds__(kWaves * 64, 1) void attn_prefill_kernel(const bf16
                 vm[pi][1] = (nv > 2 ? 0x0000ffffu : 0u) | (nv > 3 ? 0xffff0000u : 0u);
             }
             __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-            for (int dt = 0; dt < 8; ++dt) {
+            static_for<0, 8>([&](auto dt_c) {
+                constexpr int dt = decltype(dt_c)::value;
+                if constexpr (dt + 1 < 8) {
+                    read_v(vx[(dt + 1) & 1], std::integral_constant<int, dt + 1>());
+                    wait_lgkmcnt<kTP>();                                  // group dt has arrived
+                } else {
+                    wait_lgkmcnt<0>();
+                }
+                __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
                 for (int pp = 0; pp < kTP / 2; ++pp) {
-                    const u32x2 x0 = *reinterpret_cast<const u32x2 *>(vb + (2 * pp) * 4096 + dt * 512 + v_off);
-                    const u32x2 x1 = *reinterpret_cast<const u32x2 *>(vb + (2 * pp + 1) * 4096 + dt * 512 + v_off);
+                    const u32x2 x0 = vx[dt & 1][2 * pp], x1 = vx[dt & 1][2 * pp + 1];
                     const bf16x8 vf = __builtin_bit_cast(bf16x8, u32x4{x0[0] & vm[2 * pp][0], x0[1] & vm[2 * pp][1],
                                                                        x1[0] & vm[2 * pp + 1][0], x1[1] & vm[2 * pp + 1][1]});
 #pragma unroll
                     for (int q = 0; q < kSets; ++q)
                         acc[q][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(vf, pb[q][pp], acc[q][dt], 0, 0, 0);
                 }
-                if (dt & 1) __builtin_amdgcn_sched_barrier(0);
-            }
+                __builtin_amdgcn_sched_barrier(0);
+            });
         }
 
 #pragma unroll

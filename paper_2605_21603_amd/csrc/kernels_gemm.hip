@@ -103,32 +103,11 @@ __device__ __forceinline__ void wait_vmcnt(int n) {          // s_waitcnt vmcnt(
 #undef DYN_W
 }
 
-// One 16-byte LDS read per lane, as inline assembly so that its wait is placed by hand (wait_lgkmcnt).
-template <int OFFSET>
-__device__ __forceinline__ bf16x8 lds_read16(unsigned addr) {
-    static_assert(OFFSET >= 0 && OFFSET < 65536, "ds_read offset field");
-    bf16x8 v;
-    asm volatile("ds_read_b128 %0, %1 offset:%2" : "=v"(v) : "v"(addr), "n"(OFFSET) : "memory");
-    return v;
-}
-template <int N>
-__device__ __forceinline__ void wait_lgkmcnt() {                   // s_waitcnt lgkmcnt(N) only (vmcnt 63, expcnt 7 = no wait)
-    static_assert(N >= 0 && N <= 15, "lgkmcnt is a 4-bit counter");
-    __builtin_amdgcn_s_waitcnt(0xc07f | (N << 8));
-}
-
 // The MFMA as inline assembly, so that the many-row loop's instruction order is the one written down.
 // The compiler neither sees the instruction's latency nor orders anything around it: the caller keeps
 // dependent uses of an accumulator far apart and waits before reading it as an ordinary register.
 __device__ __forceinline__ void mfma_acc(f32x4 &c, const bf16x8 &a, const bf16x8 &b) {
     asm volatile("v_mfma_f32_16x16x32_bf16 %0, %1, %2, %0" : "+v"(c) : "v"(a), "v"(b));
-}
-template <int I0, int I1, class F>
-__device__ __forceinline__ void static_for(F &&f) {
-    if constexpr (I0 < I1) {
-        f(std::integral_constant<int, I0>());
-        static_for<I0 + 1, I1>(f);
-    }
 }
 
 template <int BN, int MT, bool INREG, int NS, bool GATED, int NW>
