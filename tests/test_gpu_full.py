@@ -247,3 +247,34 @@ def test_32_layer_decode_step_full_size():
     say("case c5: worst single layer %.3e (layer %d, bound %.0e); end to end through 32 layers %.3e (reported, not a gate)"
         % (worst, worst_layer, TOL[w.shape.dtype], end_to_end))
     assert end_to_end < 0.25          # a sanity bound only: an error of this size means a broken layer, not rounding drift
+
+
+def test_bench_line_keeps_its_contract_on_a_small_workload():
+    """bench.py end to end on a 13-token decode batch (seconds): one JSON line on stdout with the fields the driver
+    reads, the two measured ceilings, the roofline object, the oracle timed beside it and the prefill + decode mix."""
+    import json
+    import os
+    import subprocess
+    import sys
+    root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+    say("bench.py --workload c2_small")
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c2_small", "--steps", "20", "--warmup", "3"],
+                       stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=500)
+    assert p.returncode == 0, p.stderr[-3000:]
+    lines = [l for l in p.stdout.splitlines() if l.strip()]
+    assert len(lines) == 1
+    d = json.loads(lines[0])
+    for k in ("metric", "value", "unit", "n_gpus", "steps", "warmup", "ms_per_step", "higher_is_better", "scaling", "vs_baseline",
+              "dtype", "data", "config", "roofline", "cpu_baseline"):
+        assert k in d, k
+    assert d["n_gpus"] == 1 and d["steps"] == 20 and d["warmup"] == 3 and d["unit"] == "tokens/s" and d["data"] == "synthetic"
+    assert d["config"]["workload"].startswith("c2_small") and "model" not in d["config"]
+    assert d["value"] > 0 and abs(d["value"] - 13 / (d["ms_per_step"] * 1e-3)) < 1e-6 * d["value"]
+    r = d["roofline"]
+    assert r["bound"] in ("hbm", "mfma") and r["peak"] in (8000.0, 2500.0) and abs(r["frac"] - r["achieved"] / r["peak"]) < 1e-9
+    assert d["cpu_baseline"]["kind"] == "oracle" and d["cpu_baseline"]["value"] > 0 and d["cpu_baseline"]["cores"] >= 1
+    assert d["hbm"]["measured_stream_read"]["GB/s"] > 0
+    assert d["mfma"]["measured_loop"]["zero_operands"]["TFLOP/s"] >= d["mfma"]["measured_loop"]["random_operands"]["TFLOP/s"] > 100
+    mix = d["prefill_decode_mix"]
+    assert mix["bit_identical_to_sequential"] is True and mix["tokens"] == 576
+    assert set(d["schedules_stats_ms"]["sequential"]) >= {"median_ms", "min_ms", "max_ms", "slowest_step"}
