@@ -47,12 +47,15 @@ def sample_ids(w, n):
     return sorted(ids)
 
 
-@pytest.mark.parametrize("name", ["c2", "c4", "d300", "d600", "d1100"])
+@pytest.mark.parametrize("name", ["c2", "c4", "d300", "d600", "d1100", "c2@seed41", "c2@seed97"])
 def test_decode_configs_full_size(name):
     """Every sequence of the batch against the oracle (the oracle's loops are parallel over
-    rows), and every schedule against the sequential one bit for bit."""
+    rows), and every schedule against the sequential one bit for bit.  "c2@seedN": the same
+    sequences with weights, inputs, caches and page placement drawn from another seed."""
     say("case %s: generating" % name)
-    w = gen.config(name)
+    w = gen.config(name.split("@")[0])
+    if "@seed" in name:
+        w = dataclasses.replace(w, seed=int(name.split("@seed")[1]))
     data = gen.generate(w)
     run = GpuRun(w, data)
     outs = {}
