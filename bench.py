@@ -488,7 +488,9 @@ def main():
         "config": {"workload": "%s: %d-layer decoder forward, %d tokens / %d sequences, hidden %d, heads %d/%d x %d, "
                                "mlp %d, page %d" % (w.name, w.shape.n_layers, T, w.n_seqs, w.shape.hidden, w.shape.n_q,
                                                     w.shape.n_kv, w.shape.head_dim, w.shape.inter, w.shape.page_size),
-                   "schedule": best, "nano_rows": list(w.nano_rows), "hip_graph": use_graph},
+                   "schedule": best, "nano_rows": list(w.nano_rows),
+                   # schedules on CU partitions are always issued eagerly: a replayed graph drops the masks
+                   "hip_graph": use_graph and "cu_partitioned" not in best},
         "sequential_tokens_per_s": T / (results["sequential"] * 1e-3),
         "sequential_ms_per_step": results["sequential"],
         "best_overlapped_schedule": best_ovl,

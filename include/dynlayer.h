@@ -118,11 +118,16 @@ typedef struct {
                                    on sequence boundaries; unequal sizes allowed */
     int n_streams;              /* stream ids 0..n_streams-1 */
     int n_partitions;           /* masked partitions 1..n_partitions */
-    const uint32_t *cu_masks;   /* HOST [n_partitions, cu_mask_words] for hipExtStreamCreateWithCUMask */
+    const uint32_t *cu_masks;   /* HOST [n_partitions, cu_mask_words] for hipExtStreamCreateWithCUMask.  On MI355X
+                                   bit i of a mask (bit i % 32 of word i / 32) is compute unit i / 8 of XCD i % 8:
+                                   a run of 8 n consecutive bits takes n units of every XCD, which is what a
+                                   persistent launch sized for "two workgroups per unit of the partition" needs */
     int cu_mask_words;
     int n_slots;                /* issue order within one layer; the list repeats for every layer */
     const dyn_slot *slots;      /* HOST */
-    int use_graph;              /* 1: capture the whole step into a HIP graph once and replay it */
+    int use_graph;              /* 1: capture the whole step into a HIP graph once and replay it.  Ignored
+                                   (the step is issued eagerly) when a slot names a partition: a replayed graph
+                                   runs on streams of its own, which carry no CU mask */
 } dyn_schedule;
 
 typedef struct dyn_layer dyn_layer;
@@ -174,7 +179,8 @@ dyn_status dyn_layer_prepare(dyn_layer *layer, const dyn_schedule *sched);
  * more than 8 evictions whose replays are all still running makes the call wait for the oldest)
  * and replayed while the batch's pointers,
  * sizes, q_start_host contents, cut points and slots stay the same; the contents of device
- * arrays (positions, block table, activations, caches) may change between replays. */
+ * arrays (positions, block table, activations, caches) may change between replays.
+ * A schedule with a slot on a CU partition is never captured (see dyn_schedule.use_graph). */
 dyn_status dyn_layer_forward(dyn_layer *layer, const dyn_batch *batch, const dyn_schedule *sched, void *hip_stream);
 
 /* For callers that cannot allocate device memory or create GPU objects at the point of the

@@ -213,12 +213,16 @@ def sequential(use_graph: bool = False) -> Schedule:
 
 def nano_schedule(nano_rows: Sequence[int], chain: Sequence[int] = DENSE_CHAIN, merged_ops: Sequence[int] = (),
                   streams: Optional[Sequence[int]] = None, partitions: Optional[Sequence[int]] = None,
-                  cu_masks: Sequence[Sequence[int]] = (), use_graph: bool = False, stagger: int = 0) -> Schedule:
+                  cu_masks: Sequence[Sequence[int]] = (), use_graph: bool = False, stagger: int = 0,
+                  op_partitions: Optional[dict] = None) -> Schedule:
     """Split-and-overlap schedule in the style of the paper's batch-splitting strategies:
     micro-batch b runs its operators on stream streams[b]; operators in merged_ops are
     dispatched once for all micro-batches (merge form) on stream 0.  Issue order interleaves
     the micro-batches operator by operator, micro-batch b lagging `stagger` operators behind
-    micro-batch b-1, so that a memory-bound operator of one meets a GEMM of the other."""
+    micro-batch b-1, so that a memory-bound operator of one meets a GEMM of the other.
+    partitions gives each micro-batch a CU partition; op_partitions ({operator: partition})
+    overrides it per operator class, e.g. every micro-batch's attention on one partition and
+    the projections on another."""
     k = len(nano_rows) - 1
     streams = list(streams) if streams is not None else list(range(k))
     partitions = list(partitions) if partitions is not None else [0] * k
@@ -229,7 +233,7 @@ def nano_schedule(nano_rows: Sequence[int], chain: Sequence[int] = DENSE_CHAIN, 
                 continue
             op = chain[pos[b]]
             if op not in merged_ops:
-                slots.append((op, b, 1, streams[b], partitions[b]))
+                slots.append((op, b, 1, streams[b], (op_partitions or {}).get(op, partitions[b])))
                 pos[b] += 1
             elif all(p == pos[b] for p in pos):      # the last micro-batch has arrived: merge form
                 slots.append((op, 0, k, 0, 0))

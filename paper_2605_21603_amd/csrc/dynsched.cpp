@@ -496,7 +496,9 @@ dyn_status dyn_tune_record(dyn_scheduler *s, const dyn_tune_candidate *c, int n_
     if (c->rows[0] != 0) return fail(DYN_ERR_SCHEDULE, "the first micro-batch starts at row %d", c->rows[0]);
     if ((rc = dyn_scheduler_split(s, c->k, sizes)) != DYN_OK) return rc;
     if (c->cus_first) {
-        // the same share of every XCD: the mask has one 32-bit word per 32 CUs
+        // Partition 1 takes the low `low` bits of every 32-bit mask word, partition 2 the rest.  Bit i
+        // of a mask is compute unit i / 8 of XCD i % 8, so every XCD gives the same share whenever
+        // `low` is a multiple of 8 (the quarter shares of 256 units: 8, 16 and 24 bits per word).
         if (n_cus <= 0) n_cus = 256;
         const int words = (n_cus + 31) / 32, per_word = n_cus / words;
         const int low = c->cus_first / words;

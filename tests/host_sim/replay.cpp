@@ -8,6 +8,7 @@
 //   replay <shape file> tune <max_k> <partitions> <warmup> <iters>
 //   replay <shape file> evict
 //   replay <shape file> mixed
+//   replay <shape file> opclass <k> <stagger> <memory CUs> <use_graph>
 // shape file: "dtype n_layers hidden n_q n_kv head_dim inter n_experts top_k page_size n_seqs" then "q_len ctx_len" per sequence.
 #include <cstdio>
 #include <cstdlib>
@@ -210,6 +211,52 @@ void mixed(Setup &s) {
     if (hipStreamDestroy(stream) != hipSuccess) ++g_failures;
 }
 
+// Partitions by operator class instead of by micro-batch: every micro-batch's attention on a
+// "memory" partition (the low `mem_cus` bits of the mask), its other operators on the rest of the
+// device, so consecutive operators of one micro-batch change streams.
+void opclass(Setup &s, int k, int stagger, int mem_cus, int use_graph) {
+    hipStream_t stream;
+    if (hipStreamCreateWithFlags(&stream, hipStreamNonBlocking) != hipSuccess) ++g_failures;
+    std::vector<int> chain = {DYN_OP_NORM1, DYN_OP_QKV, DYN_OP_ROPE_KV, DYN_OP_ATTN, DYN_OP_OPROJ, DYN_OP_NORM2};
+    if (s.cfg.n_experts) chain.push_back(DYN_OP_ROUTE);
+    chain.insert(chain.end(), {DYN_OP_GATE_UP, DYN_OP_SILU, DYN_OP_DOWN});
+    std::vector<int32_t> rows(k + 1);
+    for (int i = 0; i <= k; ++i) rows[i] = s.q_start[(size_t)s.n_seqs * i / k];
+    std::vector<uint32_t> masks(16, 0u);
+    for (int i = 0; i < 256; ++i) masks[(i < mem_cus ? 0 : 8) + i / 32] |= 1u << (i % 32);
+    std::vector<dyn_slot> slots;
+    std::vector<int> pos(k, 0);
+    for (int tick = 0;; ++tick) {
+        bool done = true;
+        for (int b = 0; b < k; ++b) done = done && pos[b] >= (int)chain.size();
+        if (done) break;
+        for (int b = 0; b < k; ++b) {
+            if (pos[b] >= (int)chain.size() || tick < b * stagger) continue;
+            const int op = chain[pos[b]++];
+            slots.push_back(dyn_slot{(uint8_t)op, (uint8_t)b, 1, (uint8_t)b, (uint8_t)(op == DYN_OP_ATTN ? 1 : 2)});
+        }
+    }
+    dyn_schedule sched{};
+    sched.mode = DYN_SCHED_EXPLICIT; sched.k = k; sched.nano_rows = rows.data(); sched.n_streams = k;
+    sched.n_partitions = 2; sched.cu_masks = masks.data(); sched.cu_mask_words = 8;
+    sched.n_slots = (int)slots.size(); sched.slots = slots.data(); sched.use_graph = use_graph;
+    EXPECT_OK(dyn_schedule_validate(s.layer, &s.batch, &sched));
+    EXPECT_OK(dyn_layer_prepare(s.layer, &sched));
+    for (int it = 0; it < 4; ++it) EXPECT_OK(dyn_layer_forward(s.layer, &s.batch, &sched, stream));
+    if (hipStreamSynchronize(stream) != hipSuccess) ++g_failures;
+    EXPECT_OK(dyn_layer_set_profiling(s.layer, 1));
+    dyn_schedule eager = sched;
+    eager.use_graph = 0;
+    EXPECT_OK(dyn_layer_forward(s.layer, &s.batch, &eager, stream));
+    if (hipStreamSynchronize(stream) != hipSuccess) ++g_failures;
+    int n_rec = 0;
+    std::vector<dyn_slot_time> recs(8192);
+    EXPECT_OK(dyn_layer_get_slot_times(s.layer, recs.data(), (int)recs.size(), &n_rec));
+    EXPECT_OK(dyn_layer_set_profiling(s.layer, 0));
+    dyn_layer_destroy(s.layer);
+    if (hipStreamDestroy(stream) != hipSuccess) ++g_failures;
+}
+
 // The checker checked: each misuse the stand-in exists to catch is committed against it directly,
 // once, and must be counted.  Returns the number of misuses that went unseen.
 int selftest() {
@@ -306,6 +353,7 @@ int main(int argc, char **argv) {
     if (mode == "tune" && argc >= 7) tune_like(s, atoi(argv[3]), atoi(argv[4]), atoi(argv[5]), atoi(argv[6]));
     else if (mode == "evict") evict_like(s);
     else if (mode == "mixed") mixed(s);
+    else if (mode == "opclass" && argc >= 7) opclass(s, atoi(argv[3]), atoi(argv[4]), atoi(argv[5]), atoi(argv[6]));
     else { fprintf(stderr, "replay: unknown mode\n"); return 2; }
     const hipstub_stats *st = hipstub_get_stats();
     // CU-masked streams live for the process by design; everything else must be gone

@@ -84,6 +84,20 @@ def expect_schedule_error(layer, b, sched, needle):
     assert needle in str(e.value), str(e.value)
 
 
+@pytest.mark.parametrize("name", ["c5_small", "c3_small", "c4_small"])
+def test_validator_accepts_partitions_by_operator_class(name):
+    """A slot's partition need not follow its micro-batch: attention of every micro-batch on
+    partition 1, its other operators on partition 2."""
+    w, layer = fake_layer(name)
+    chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
+    k = len(w.nano_rows) - 1
+    masks = [[0xFFFFFFFF] * 4 + [0] * 4, [0] * 4 + [0xFFFFFFFF] * 4]
+    sched = B.nano_schedule(w.nano_rows, chain, stagger=2, partitions=[2] * k, op_partitions={B.DYN_OP_ATTN: 1}, cu_masks=masks)
+    assert {s[4] for s in sched.slots if s[0] == B.DYN_OP_ATTN} == {1}
+    assert {s[4] for s in sched.slots if s[0] != B.DYN_OP_ATTN} == {2}
+    layer.validate(host_batch(w), sched)
+
+
 def test_validator_rejects_illegal_schedules():
     w, layer = fake_layer("c2_small")        # 13 decode sequences, cut (0, 6, 13)
     b = host_batch(w)

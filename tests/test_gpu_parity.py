@@ -88,8 +88,8 @@ def test_forward_rejects_small_workspace_and_aliasing():
 
 
 def cu_masks_halves():
-    """Two CU masks that split every XCD's CUs in half (bit i of the mask is CU i of the
-    device-wide enumeration; 256 CUs -> 8 words)."""
+    """Two CU masks that split every XCD's CUs in half (bit i of the mask is CU i / 8 of XCD
+    i % 8; 256 CUs -> 8 words)."""
     lo = [0x0000FFFF] * 8
     hi = [0xFFFF0000] * 8
     return [lo, hi]
@@ -97,9 +97,10 @@ def cu_masks_halves():
 
 @pytest.mark.parametrize("name", ["c2_small", "c5_small", "stack_mixed"])
 def test_cu_partitioned_streams_and_graph_replay(name):
-    """Micro-batches on CU-masked streams, eager and captured into a HIP graph; the graph is
-    replayed several times with eager forwards and synchronisations in between and every
-    replay must reproduce the sequential bits."""
+    """Micro-batches on CU-masked streams, with and without use_graph (the library issues a
+    schedule on CU partitions eagerly either way: a replayed graph would drop the masks),
+    several forwards with eager forwards and synchronisations in between; each must reproduce
+    the sequential bits."""
     w = gen.config(name)
     data = gen.generate(w)
     run = GpuRun(w, data)
@@ -128,6 +129,28 @@ def test_cu_partitioned_streams_and_graph_replay(name):
     seq_graph = B.sequential(use_graph=True)
     y2, k2, _ = run.run(seq_graph, repeat=3)
     assert torch.equal(y2.view(torch.uint8), y0.view(torch.uint8))
+
+
+@pytest.mark.parametrize("name", ["c5_small", "c3_small", "c4_small"])
+def test_partitions_by_operator_class_match_sequential(name):
+    """Every micro-batch's attention on one CU partition (the low 128 bits of the mask: 16 CUs of
+    every XCD) and all its other operators on the other half, so consecutive operators of a
+    micro-batch change hardware queues and every dependency is an event between two masked
+    streams.  Same bits as the sequential order; use_graph is set and ignored."""
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
+    masks = [[0xFFFFFFFF] * 4 + [0] * 4, [0] * 4 + [0xFFFFFFFF] * 4]
+    k = len(w.nano_rows) - 1
+    for use_graph in (False, True):
+        sched = B.nano_schedule(w.nano_rows, chain, stagger=2, partitions=[2] * k, op_partitions={B.DYN_OP_ATTN: 1},
+                                cu_masks=masks, use_graph=use_graph)
+        say("case %s attention on its own partition graph=%s" % (name, use_graph))
+        y1, k1, v1 = run.run(sched, repeat=2)
+        assert torch.equal(y1.view(torch.uint8), y0.view(torch.uint8))
+        assert torch.equal(k1.view(torch.uint8), k0.view(torch.uint8)) and torch.equal(v1.view(torch.uint8), v0.view(torch.uint8))
 
 
 def test_profiling_reports_every_dispatch():

@@ -106,9 +106,10 @@ def test_the_stand_in_detects_each_misuse_it_is_there_for(replay):
 def test_tuning_run_with_four_micro_batches_keeps_every_object_alive_while_used(replay):
     """The sequence that ended in a segmentation fault inside hipGraphLaunch on the GPU: 13
     tokens, candidates with up to four micro-batches, one CU-share pair, one warm-up and three
-    timed runs of three replays each."""
+    timed runs of three replays each.  (The candidates on CU partitions, captured like the others
+    at the time, are issued eagerly now: 38 graphs instead of 51.)"""
     stats = _run(replay, "c2_small", "tune", 4, 1, 1, 3)
-    assert stats["captures"] == stats["instantiations"] >= 50
+    assert stats["captures"] == stats["instantiations"] >= 38
     assert stats["execs_destroyed"] == stats["instantiations"]
     assert stats["max_live_execs"] <= 17 and stats["max_live_side_branches"] <= 20
     assert stats["empty_branches"] == 0                      # no stream is forked into a capture without launching in it
@@ -133,3 +134,12 @@ def test_graph_cache_overflow_without_host_waits(replay, name):
 def test_mixed_eager_profiled_captured_masked_and_allocation_free_forwards(replay, name):
     stats = _run(replay, name, "mixed")
     assert stats["kernel_launches"] > 1000
+
+
+@pytest.mark.parametrize("name,k,stagger,mem_cus", [("c5_small", 2, 2, 160), ("c5_small", 4, 2, 192), ("c4_small", 2, 4, 128)])
+def test_partitions_by_operator_class_are_issued_eagerly(replay, name, k, stagger, mem_cus):
+    """Every micro-batch's attention on one CU partition and its other operators on another, so
+    consecutive operators of a micro-batch change streams; use_graph is set, and nothing may be
+    captured, because a replayed graph would drop the masks."""
+    stats = _run(replay, name, "opclass", k, stagger, mem_cus, 1)
+    assert stats["captures"] == 0 and stats["graph_launches"] == 0 and stats["kernel_launches"] > 100
