@@ -44,7 +44,7 @@ class dyn_batch(C.Structure):
                 ("seq_of_token", C.c_void_p), ("pos_of_token", C.c_void_p), ("block_table", C.c_void_p),
                 ("max_pages_per_seq", C.c_int), ("q_start_host", C.c_void_p), ("k_cache", C.c_void_p),
                 ("v_cache", C.c_void_p), ("kv_layer_stride", C.c_size_t), ("workspace", C.c_void_p),
-                ("workspace_bytes", C.c_size_t)]
+                ("workspace_bytes", C.c_size_t), ("k_cache_layers", C.c_void_p), ("v_cache_layers", C.c_void_p)]
 
 
 class dyn_slot(C.Structure):
@@ -471,26 +471,41 @@ def make_config(sh) -> dyn_layer_config:
 
 class DeviceStep:
     """Device copies of one generated step (workloads.gen.generate output) and the dyn_batch
-    describing them.  Layer caches are stacked so that kv_layer_stride is uniform."""
+    describing them.  Layer caches are stacked so that kv_layer_stride is uniform, unless the
+    caller has placed them layer by layer."""
 
-    def __init__(self, layer: DynLayer, data: dict, device="cuda:0", sched: Optional["Schedule"] = None, guard: int = 0):
+    def __init__(self, layer: DynLayer, data: dict, device="cuda:0", sched: Optional["Schedule"] = None, guard: int = 0,
+                 placed: bool = False):
         """sched: size the workspace for this schedule alone (dyn_schedule_workspace_bytes) instead of
-        for any schedule; guard: extra bytes behind the workspace that the library is not told about."""
+        for any schedule; guard: extra bytes behind the workspace that the library is not told about;
+        placed: data["k_cache"] / data["v_cache"] are lists of per-layer device tensors that stay
+        where they are (k_cache_layers / v_cache_layers of the batch) instead of being stacked."""
         dev = torch.device(device)
         self.x = data["x"].to(dev)
         self.y = torch.empty_like(self.x)
-        self.k_cache = torch.stack([k.to(dev) for k in data["k_cache"]]) if isinstance(data["k_cache"], list) else data["k_cache"]
-        self.v_cache = torch.stack([v.to(dev) for v in data["v_cache"]]) if isinstance(data["v_cache"], list) else data["v_cache"]
+        self.k_layers = self.v_layers = None
+        if placed:
+            self.k_layers, self.v_layers = list(data["k_cache"]), list(data["v_cache"])
+            assert all(t.is_cuda and t.is_contiguous() for t in self.k_layers + self.v_layers)
+            self.k_cache, self.v_cache = self.k_layers[0], self.v_layers[0]
+        else:
+            self.k_cache = torch.stack([k.to(dev) for k in data["k_cache"]]) if isinstance(data["k_cache"], list) else data["k_cache"]
+            self.v_cache = torch.stack([v.to(dev) for v in data["v_cache"]]) if isinstance(data["v_cache"], list) else data["v_cache"]
         self.seq_of_token = torch.from_numpy(data["seq_of_token"]).to(dev)
         self.pos_of_token = torch.from_numpy(data["pos_of_token"]).to(dev)
         self.block_table = torch.from_numpy(np.ascontiguousarray(data["block_table"])).to(dev)
         self.q_start_host = np.ascontiguousarray(data["q_start"], dtype=np.int32)
         n_tokens, n_seqs = self.x.shape[0], len(self.q_start_host) - 1
         max_pages = int(data["block_table"].shape[1])
-        stride = self.k_cache[0].numel() * self.k_cache.element_size()
+        stride = 0 if placed else self.k_cache[0].numel() * self.k_cache.element_size()
         self.batch = dyn_batch(n_tokens, n_seqs, _ptr(self.x), _ptr(self.y), _ptr(self.seq_of_token),
                                _ptr(self.pos_of_token), _ptr(self.block_table), max_pages, _ptr(self.q_start_host),
                                _ptr(self.k_cache), _ptr(self.v_cache), stride, None, 0)
+        if placed:
+            self._k_ptrs = (C.c_void_p * len(self.k_layers))(*[t.data_ptr() for t in self.k_layers])
+            self._v_ptrs = (C.c_void_p * len(self.v_layers))(*[t.data_ptr() for t in self.v_layers])
+            self.batch.k_cache_layers = C.cast(self._k_ptrs, C.c_void_p)
+            self.batch.v_cache_layers = C.cast(self._v_ptrs, C.c_void_p)
         nbytes = layer.workspace_bytes(n_tokens, max_pages) if sched is None else layer.schedule_workspace_bytes(self.batch, sched)
         self.workspace = torch.empty(nbytes + 256 + guard, dtype=torch.uint8, device=dev)
         ws_ptr = (self.workspace.data_ptr() + 255) & ~255

@@ -629,8 +629,8 @@ dyn_status launch_op(const dyn_layer *L, const dyn_batch *b, const dyn_schedule 
     if (d.partition > 0 && s->mode == DYN_SCHED_EXPLICIT)
         for (int i = 0; i < s->cu_mask_words; ++i)
             sh.n_cus += __builtin_popcount(s->cu_masks[(d.partition - 1) * s->cu_mask_words + i]);
-    char *kc = (char *)b->k_cache + (size_t)d.layer * b->kv_layer_stride;
-    char *vc = (char *)b->v_cache + (size_t)d.layer * b->kv_layer_stride;
+    char *kc = b->k_cache_layers ? (char *)b->k_cache_layers[d.layer] : (char *)b->k_cache + (size_t)d.layer * b->kv_layer_stride;
+    char *vc = b->v_cache_layers ? (char *)b->v_cache_layers[d.layer] : (char *)b->v_cache + (size_t)d.layer * b->kv_layer_stride;
     // the dispatch's own scratch: split-K planes of `rows` rows each
     float *const planes = (float *)(base + sc.planes);
     hipError_t err = hipSuccess;
@@ -844,6 +844,11 @@ std::vector<unsigned char> graph_key(const dyn_batch *b, const dyn_schedule *s, 
                             (int64_t)b->workspace_bytes, (int64_t)plan.size()};
     put(dims, sizeof dims);
     put(b->q_start_host, sizeof(int32_t) * ((size_t)b->n_seqs + 1));
+    if (b->k_cache_layers) {               // caches placed layer by layer: the pointers are the launches' arguments
+        const int n_layers = plan.empty() ? 0 : plan.back().layer + 1;
+        put(b->k_cache_layers, sizeof(void *) * n_layers);
+        put(b->v_cache_layers, sizeof(void *) * n_layers);
+    }
     for (const Dispatch &d : plan) {
         const int f[] = {d.layer, d.op, d.r0, d.r1, d.stream, d.partition, d.any_multi, d.noop, d.lists_ready};
         put(f, sizeof f);
@@ -999,9 +1004,21 @@ dyn_status scratch_pointer(void **out) {
 }
 
 dyn_status check_batch_tensors(const dyn_layer *L, const dyn_batch *b) {
-    if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table || !b->k_cache || !b->v_cache)
+    if (!b->x || !b->y || !b->seq_of_token || !b->pos_of_token || !b->block_table)
         return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
     if (b->x == b->y) return fail(DYN_ERR_INVALID_ARG, "y must not alias x");
+    if ((b->k_cache_layers != nullptr) != (b->v_cache_layers != nullptr))
+        return fail(DYN_ERR_INVALID_ARG, "k_cache_layers and v_cache_layers go together");
+    if (b->k_cache_layers) {
+        for (int l = 0; l < L->cfg.n_layers; ++l) {
+            if (!b->k_cache_layers[l] || !b->v_cache_layers[l])
+                return fail(DYN_ERR_INVALID_ARG, "layer %d: NULL cache pointer in k_cache_layers / v_cache_layers", l);
+            if (((uintptr_t)b->k_cache_layers[l] | (uintptr_t)b->v_cache_layers[l]) & 15)
+                return fail(DYN_ERR_INVALID_ARG, "layer %d: cache pointer not 16-byte aligned", l);
+        }
+        return DYN_OK;
+    }
+    if (!b->k_cache || !b->v_cache) return fail(DYN_ERR_INVALID_ARG, "NULL tensor pointer in batch");
     if (L->cfg.n_layers > 1 && b->kv_layer_stride == 0) return fail(DYN_ERR_INVALID_ARG, "kv_layer_stride is 0 with several layers");
     return DYN_OK;
 }

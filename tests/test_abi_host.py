@@ -50,6 +50,28 @@ def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.dyn_slot_time) == 10 * 4
 
 
+def test_forward_rejects_inconsistent_per_layer_cache_pointers():
+    """k_cache_layers / v_cache_layers: both or neither, one non-NULL 16-byte-aligned pointer per
+    layer.  The check comes before anything touches a GPU."""
+    w, layer = fake_layer("c5_small")
+    b = host_batch(w)
+    for name in ("x", "seq_of_token", "pos_of_token", "block_table"):
+        setattr(b, name, 0x10000)
+    b.y = 0x20000
+    L = w.shape.n_layers
+    good = (C.c_void_p * L)(*[0x100000 * (i + 1) for i in range(L)])
+    hole = (C.c_void_p * L)(*([0x100000] * (L - 1) + [None]))
+    odd = (C.c_void_p * L)(*([0x100000] * (L - 1) + [0x100008]))
+    for k, v, needle in [(good, None, "go together"), (None, good, "go together"), (good, hole, "NULL cache pointer"),
+                         (odd, good, "not 16-byte aligned")]:
+        b.k_cache_layers = C.cast(k, C.c_void_p) if k is not None else None
+        b.v_cache_layers = C.cast(v, C.c_void_p) if v is not None else None
+        sc = B.sequential().to_c()
+        rc = B.lib().dyn_layer_forward(layer.handle, C.addressof(b), C.addressof(sc), None)
+        msg = B.lib().dyn_last_error().decode()
+        assert rc == B.DYN_ERR_INVALID_ARG and needle in msg, (rc, msg)
+
+
 def test_create_rejects_bad_configs():
     w = gen.config("c2_small")
     good = {n: 0x1000 for n in ("w_qkv", "w_o", "w_gate_up", "w_down", "g_norm1", "g_norm2")}

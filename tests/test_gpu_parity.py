@@ -153,6 +153,45 @@ def test_partitions_by_operator_class_match_sequential(name):
         assert torch.equal(k1.view(torch.uint8), k0.view(torch.uint8)) and torch.equal(v1.view(torch.uint8), v0.view(torch.uint8))
 
 
+@pytest.mark.parametrize("name", ["c5_small", "stack_mixed"])
+def test_caches_placed_layer_by_layer_match_the_stacked_ones(name):
+    """k_cache_layers / v_cache_layers: every layer's K and V pool in a buffer of its own, in
+    shuffled order inside one arena with gaps, instead of one stacked tensor with a uniform
+    stride.  Same output bits and same cache contents, eagerly and as a replayed graph."""
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data)
+    y0, k0, v0 = run.run(B.sequential())
+    L = w.shape.n_layers
+    n = data["k_cache"][0].numel()
+    slot = n + 1024                                   # elements; keeps every pool 16-byte aligned and apart
+    arena = torch.zeros(2 * L * slot, dtype=data["k_cache"][0].dtype, device="cuda:0")
+    order = torch.randperm(2 * L, generator=torch.Generator().manual_seed(3)).tolist()
+    for use_graph in (False, True):
+        ks = [arena[order[l] * slot: order[l] * slot + n].view(data["k_cache"][l].shape) for l in range(L)]
+        vs = [arena[order[L + l] * slot: order[L + l] * slot + n].view(data["v_cache"][l].shape) for l in range(L)]
+        for l in range(L):
+            ks[l].copy_(data["k_cache"][l])
+            vs[l].copy_(data["v_cache"][l])
+        step = B.DeviceStep(run.layer, dict(data, k_cache=ks, v_cache=vs), placed=True)
+        st = torch.cuda.Stream()
+        say("case %s placed layers graph=%s" % (name, use_graph))
+        with torch.cuda.stream(st):
+            for _ in range(3 if use_graph else 1):
+                run.layer.forward(step.batch, B.sequential(use_graph=use_graph), st)
+        st.synchronize()
+        torch.cuda.synchronize()
+        assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8))
+        for l in range(L):
+            assert torch.equal(ks[l].cpu().view(torch.uint8), k0[l].view(torch.uint8)), l
+            assert torch.equal(vs[l].cpu().view(torch.uint8), v0[l].view(torch.uint8)), l
+    sched = B.nano_schedule(w.nano_rows, stagger=2, use_graph=True)
+    with torch.cuda.stream(st):
+        run.layer.forward(step.batch, sched, st)
+    st.synchronize()
+    assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8))
+
+
 def test_profiling_reports_every_dispatch():
     w = gen.config("c2_small")
     data = gen.generate(w)
