@@ -14,6 +14,7 @@ splitting does not pay), `config.schedule` names it, and per schedule the median
 maximum and the wall-clock mean over the K steps are reported beside it.  Prints one JSON line.
 """
 import argparse
+import dataclasses
 import hashlib
 import json
 import os
@@ -339,6 +340,10 @@ def main():
                     help="also run the library's measured search over micro-batch sizes, forms and CU shares and time its choice")
     ap.add_argument("--no-event-profile", action="store_true", help="skip the per-operator HIP-event pass")
     ap.add_argument("--no-mix", action="store_true", help="skip the chunked-prefill + decode step timed beside the main workload")
+    ap.add_argument("--kv-placement", default="measured", choices=["measured", "stacked"],
+                    help="measured: one large arena, the attention launch timed with the K and V pools at pairs of arena chunks, "
+                         "every layer's pools at the fastest pair with room; stacked: one tensor per cache, layers back to back")
+    ap.add_argument("--arena-gib", type=int, default=224, help="--kv-placement measured: size of the arena (chunks of 16 GiB)")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
     ap.add_argument("--sweep-grid", default="fit", choices=["fit", "holdout"],
@@ -372,17 +377,54 @@ def main():
         return
 
     w = gen.config(args.workload)
+    stream = torch.cuda.Stream()
+    # The arena comes first, while the device memory is still in large free blocks.
+    arena, placement = None, None
+    if args.kv_placement == "measured" and w.shape.dtype == "bf16":
+        from paper_2605_21603_amd import placement as P
+        try:
+            arena = P.Arena(args.arena_gib // 16, 16 * P.GiB)
+            arena.fill_random()
+        except RuntimeError as e:           # not enough free memory for the arena: the plain layout
+            log("no %d GiB arena (%s): stacked caches" % (args.arena_gib, str(e).splitlines()[0]))
+            arena = None
+            torch.cuda.empty_cache()
+
+    def place(so_far, k_shape, v_shape):
+        """Times the first layer's attention launch on this step with the pools at pairs of arena
+        chunks and hands out every layer's pools accordingly."""
+        nonlocal placement
+        dt = w.shape.torch_dtype
+        w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
+        layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1)), w0)
+        times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream)
+        del layer1
+        plan = P.assign(times, w.shape.n_layers, arena.chunk_bytes // P.slot_bytes_of(k_shape, dt), arena.n_chunks)
+        placement = dict(P.summary(times, plan), arena_GiB=arena.buf.numel() / P.GiB, chunk_GiB=16)
+        log("cache placement: attention probe %.1f us fastest / %.1f median / %.1f slowest pair of chunks; chosen mean %.1f, worst %.1f"
+            % (placement["probe_us_fastest"], placement["probe_us_median"], placement["probe_us_slowest"],
+               placement["chosen_us_mean"], placement["chosen_us_worst"]))
+        return P.place_layers(arena, plan, k_shape, v_shape, dt)
+
     log("generating %s (seed %d) ..." % (w.name, w.seed))
+    host_data = None                        # the step as generated on the host, where it was
     if w.shape.n_layers > 1:                # caches beyond host memory: drawn directly in device memory
-        data = gen.generate(w, device="cuda:0", stacked=True)
+        data = gen.generate(w, device="cuda:0", stacked=True, place=place if arena is not None else None)
         torch.cuda.synchronize()
         log("generated in device memory: %.1f GB allocated" % (torch.cuda.memory_allocated() / 1e9))
     else:
         data = gen.generate(w)
+        if arena is not None:               # generated on the host: copy every layer's pools to their places
+            host_k, host_v = data["k_cache"], data["v_cache"]
+            dev = dict(data, weights=[{k: v.to("cuda:0") for k, v in lw.items()} for lw in data["weights"]])
+            ks, vs = place(dev, tuple(host_k[0].shape), tuple(host_v[0].shape))
+            for l in range(w.shape.n_layers):
+                ks[l].copy_(host_k[l])
+                vs[l].copy_(host_v[l])
+            host_data, data = data, dict(data, k_cache=ks, v_cache=vs)
     weights = [{k: v.to("cuda:0") for k, v in lw.items()} for lw in data["weights"]]
     layer = B.DynLayer(B.make_config(w.shape), weights)
-    step = B.DeviceStep(layer, data)
-    stream = torch.cuda.Stream()
+    step = B.DeviceStep(layer, data, placed=arena is not None)
     use_graph = not args.no_graph
 
     stats = {}
@@ -499,6 +541,7 @@ def main():
         "schedules_ms": results,
         "schedules_stats_ms": stats,
         "hbm": {"peak_GB/s": HBM_PEAK_GBS, "measured_stream_read": stream_read},
+        "kv_placement": placement if placement is not None else "stacked",
         "mfma": {"peak_TFLOP/s": MFMA_BF16_PEAK_TFLOPS, "measured_loop": mfma_loop},
         "tuned": tuned,
         "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",
@@ -520,7 +563,7 @@ def main():
         log("prefill + decode mix: %s" % out["prefill_decode_mix"])
     if not args.no_cpu_baseline:
         log("timing the CPU oracle on a sample ...")
-        out["cpu_baseline"] = cpu_baseline(w, data, 128 if w.shape.n_layers == 1 else 16)
+        out["cpu_baseline"] = cpu_baseline(w, host_data if host_data is not None else data, 128 if w.shape.n_layers == 1 else 16)
     print(json.dumps(out), flush=True)
 
 

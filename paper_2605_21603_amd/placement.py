@@ -1,0 +1,126 @@
+"""Measured placement of the K and V cache pools in HBM.  Caller-side helper: it decides where
+caller-owned buffers go and computes nothing of the layer.
+
+The attention launch of a layer streams that layer's K pool and V pool together, page by page,
+and on MI355X its rate depends on which regions of HBM the two pools lie in: for one
+Llama-3-8B-shaped layer at batch 256 (2.3 GiB per pool) the same launch takes 827-849, 857-885 or
+940-957 us depending on the pair of regions, in blocks of 32 or 64 GiB that follow the physical
+backing of the allocation (a bare reader sees only a third of that contrast, so the launch itself
+is the probe).  Two pools allocated one after the other early in a process land in the slowest
+class.  So: take one large arena, time the real attention launch with the pools at pairs of arena
+chunks, and give every layer the fastest pair that still has room.  The library takes the result
+through k_cache_layers / v_cache_layers of the batch."""
+from typing import Dict, List, Optional, Sequence, Tuple
+import ctypes as C
+import dataclasses
+
+import torch
+
+from . import binding as B
+
+GiB = 1 << 30
+
+
+class Arena:
+    """One allocation cut into chunks of chunk_bytes; a chunk holds whole pools ("slots")."""
+
+    def __init__(self, n_chunks: int, chunk_bytes: int, device="cuda:0"):
+        self.n_chunks, self.chunk_bytes = n_chunks, chunk_bytes
+        self.buf = torch.empty(n_chunks * chunk_bytes, dtype=torch.uint8, device=device)
+
+    def fill_random(self, seed: int = 1) -> None:
+        """N(0, 1) bf16 values everywhere (one 512 MiB block repeated): the probe reads pools at
+        places that hold no cache yet, and what it reads should cost what real values cost."""
+        g = torch.Generator(device=self.buf.device)
+        g.manual_seed(seed)
+        blk = torch.empty(256 << 20, dtype=torch.float32, device=self.buf.device).normal_(generator=g).to(torch.bfloat16).view(torch.uint8)
+        for o in range(0, self.buf.numel(), blk.numel()):
+            n = min(blk.numel(), self.buf.numel() - o)
+            self.buf[o:o + n].copy_(blk[:n])
+
+    def view(self, chunk: int, slot: int, slot_bytes: int, shape, dtype) -> torch.Tensor:
+        off = chunk * self.chunk_bytes + slot * slot_bytes
+        n = 1
+        for d in shape:
+            n *= d
+        e = torch.empty(0, dtype=dtype).element_size()
+        assert slot * slot_bytes + n * e <= self.chunk_bytes
+        return self.buf[off:off + n * e].view(dtype).view(shape)
+
+
+def slot_bytes_of(k_shape, dtype) -> int:
+    n = 1
+    for d in k_shape:
+        n *= d
+    b = n * torch.empty(0, dtype=dtype).element_size()
+    return (b + 255) & ~255
+
+
+def measure_pairs(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_shape, dtype, stream, reps: int = 2) -> Dict[Tuple[int, int], float]:
+    """Attention launch time (us, by the library's own per-dispatch events) of the one-layer model
+    `layer1` on the step in `data`, with the K pool at the start of chunk i and the V pool at the
+    start of chunk j (i < j), or right behind the K pool in the same chunk (i == j)."""
+    sb = slot_bytes_of(k_shape, dtype)
+    k0 = arena.view(0, 0, sb, k_shape, dtype)
+    v0 = arena.view(0, 1, sb, v_shape, dtype)
+    step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True)
+    base = arena.buf.data_ptr()
+    sched = B.sequential()
+    layer1.set_profiling(True)
+    times = {}
+    try:
+        for i in range(arena.n_chunks):
+            for j in range(i, arena.n_chunks):
+                step._k_ptrs[0] = base + i * arena.chunk_bytes
+                step._v_ptrs[0] = base + j * arena.chunk_bytes + (sb if i == j else 0)
+                ts = []
+                with torch.cuda.stream(stream):
+                    for r in range(reps + 1):
+                        layer1.forward(step.batch, sched, stream)
+                        stream.synchronize()
+                        if r == 0:
+                            continue
+                        for rec in layer1.slot_times():
+                            if rec["op"] == B.DYN_OP_ATTN:
+                                ts.append(rec["main_stop_ms"] - rec["main_start_ms"])
+                times[(i, j)] = 1e3 * sum(ts) / len(ts)
+    finally:
+        layer1.set_profiling(False)
+    return times
+
+
+def assign(times: Dict[Tuple[int, int], float], n_layers: int, slots_per_chunk: int, n_chunks: int) -> List[Tuple[int, int, int, int, float]]:
+    """Fastest pairs first, as many layers per pair as both chunks still have slots for.
+    Returns per layer (K chunk, K slot, V chunk, V slot, probed us)."""
+    free = [slots_per_chunk] * n_chunks
+    used = [0] * n_chunks
+    out = []
+    for (i, j), t in sorted(times.items(), key=lambda kv: kv[1]):
+        while len(out) < n_layers and (free[i] >= 2 if i == j else free[i] >= 1 and free[j] >= 1):
+            ks = used[i]
+            used[i] += 1
+            free[i] -= 1
+            vs = used[j]
+            used[j] += 1
+            free[j] -= 1
+            out.append((i, ks, j, vs, t))
+        if len(out) == n_layers:
+            break
+    if len(out) < n_layers:
+        raise RuntimeError("the arena has room for %d of %d layers" % (len(out), n_layers))
+    return out
+
+
+def place_layers(arena: Arena, plan: Sequence[Tuple[int, int, int, int, float]], k_shape, v_shape, dtype):
+    sb = slot_bytes_of(k_shape, dtype)
+    ks = [arena.view(kc, ksl, sb, k_shape, dtype) for kc, ksl, _, _, _ in plan]
+    vs = [arena.view(vc, vsl, sb, v_shape, dtype) for _, _, vc, vsl, _ in plan]
+    return ks, vs
+
+
+def summary(times: Dict[Tuple[int, int], float], plan) -> dict:
+    all_t = sorted(times.values())
+    chosen = [p[4] for p in plan]
+    return {"pairs_probed": len(all_t), "probe_us_fastest": all_t[0], "probe_us_median": all_t[len(all_t) // 2],
+            "probe_us_slowest": all_t[-1], "chosen_us_mean": sum(chosen) / len(chosen), "chosen_us_worst": max(chosen),
+            "pairs": [[p[0], p[2]] for p in plan]}

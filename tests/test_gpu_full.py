@@ -261,7 +261,8 @@ def test_bench_line_keeps_its_contract_on_a_small_workload():
     import sys
     root = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
     say("bench.py --workload c2_small")
-    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c2_small", "--steps", "20", "--warmup", "3"],
+    p = subprocess.run([sys.executable, os.path.join(root, "bench.py"), "--workload", "c2_small", "--steps", "20", "--warmup", "3",
+                        "--arena-gib", "64"],
                        stdout=subprocess.PIPE, stderr=subprocess.PIPE, text=True, timeout=500)
     assert p.returncode == 0, p.stderr[-3000:]
     lines = [l for l in p.stdout.splitlines() if l.strip()]
@@ -281,3 +282,6 @@ def test_bench_line_keeps_its_contract_on_a_small_workload():
     mix = d["prefill_decode_mix"]
     assert mix["bit_identical_to_sequential"] is True and mix["tokens"] == 576
     assert set(d["schedules_stats_ms"]["sequential"]) >= {"median_ms", "min_ms", "max_ms", "slowest_step"}
+    # the cache pools were placed by measurement in a 64 GiB arena (4 chunks: 10 pairs), or the arena did not fit
+    kp = d["kv_placement"]
+    assert kp == "stacked" or (kp["pairs_probed"] == 10 and kp["probe_us_fastest"] <= kp["chosen_us_mean"] <= kp["probe_us_slowest"])

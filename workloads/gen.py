@@ -292,13 +292,16 @@ def layer_weights(sh: LayerShape, gen: torch.Generator, device="cpu") -> Dict[st
     return wts
 
 
-def generate(w: Workload, device="cpu", stacked: bool = False) -> Dict[str, object]:
+def generate(w: Workload, device="cpu", stacked: bool = False, place=None) -> Dict[str, object]:
     """All tensors of one step: per-layer weights, per-layer caches, x and the metadata.
 
     With device="cpu" the torch CPU generator is used; a GPU device draws directly in
     device memory (needed only for the 32-layer configuration whose caches exceed host
     memory); the two do not produce the same numbers.  stacked=True returns each cache as
-    one [n_layers, ...] tensor filled layer by layer instead of a list of layer tensors."""
+    one [n_layers, ...] tensor filled layer by layer instead of a list of layer tensors.
+    place: a callable that gets everything generated before the caches (weights, x, metadata)
+    and the two pool shapes and returns two lists of per-layer tensors to fill in place, for a
+    caller that decides where each layer's pools go; the values are those of stacked=True."""
     sh = w.shape
     gen = torch.Generator(device=device)
     gen.manual_seed(w.seed)
@@ -308,15 +311,18 @@ def generate(w: Workload, device="cpu", stacked: bool = False) -> Dict[str, obje
     out["x"] = _normal(gen, (w.n_tokens, sh.hidden), 1.0, sh.dtype, device)
     k_shape = (md["n_pages"], sh.n_kv, sh.page_size, sh.head_dim)
     v_shape = (md["n_pages"], sh.n_kv, sh.head_dim, sh.page_size)
-    if stacked:
-        kc = torch.empty((sh.n_layers,) + k_shape, dtype=sh.torch_dtype, device=device)
-        vc = torch.empty((sh.n_layers,) + v_shape, dtype=sh.torch_dtype, device=device)
+    if stacked or place is not None:
+        if place is not None:
+            kc, vc = place(out, k_shape, v_shape)
+        else:
+            kc = torch.empty((sh.n_layers,) + k_shape, dtype=sh.torch_dtype, device=device)
+            vc = torch.empty((sh.n_layers,) + v_shape, dtype=sh.torch_dtype, device=device)
         chunk = max(1, md["n_pages"] // 8)          # keeps the fp32 staging buffers small
         for l in range(sh.n_layers):
             for p0 in range(0, md["n_pages"], chunk):
                 p1 = min(md["n_pages"], p0 + chunk)
-                kc[l, p0:p1] = _normal(gen, (p1 - p0,) + k_shape[1:], 1.0, sh.dtype, device)
-                vc[l, p0:p1] = _normal(gen, (p1 - p0,) + v_shape[1:], 1.0, sh.dtype, device)
+                kc[l][p0:p1] = _normal(gen, (p1 - p0,) + k_shape[1:], 1.0, sh.dtype, device)
+                vc[l][p0:p1] = _normal(gen, (p1 - p0,) + v_shape[1:], 1.0, sh.dtype, device)
     else:
         kc, vc = [], []
         for _ in range(sh.n_layers):
