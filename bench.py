@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # since, the figure is withheld (traffic = null) instead of going stale silently.
 ATTN_SOURCE = os.path.join(ROOT, "paper_2605_21603_amd", "csrc", "kernels_attn_mfma.hip")
 ROCPROF_TRAFFIC = {
-    "c2": {"bytes": 1272927027 + 21844378, "source_sha256_16": "97acdd680f24a790",
-           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,546.4 x 2.0 KiB + WRITE_SIZE 21,332.4 KiB)"},
-    "c5": {"bytes": 5051984077 + 86334157, "source_sha256_16": "97acdd680f24a790",
-           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,789.1 x 2.0 KiB + WRITE_SIZE 84,310.7 KiB)"},
+    "c2": {"bytes": 1272987034 + 21844070, "source_sha256_16": "97acdd680f24a790",
+           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,575.7 x 2.0 KiB + WRITE_SIZE 21,332.1 KiB)"},
+    "c5": {"bytes": 5051700224 + 86376653, "source_sha256_16": "97acdd680f24a790",
+           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,650.5 x 2.0 KiB + WRITE_SIZE 84,352.2 KiB)"},
 }
 
 
