@@ -90,24 +90,62 @@ def measure_pairs(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_sha
 
 
 def assign(times: Dict[Tuple[int, int], float], n_layers: int, slots_per_chunk: int, n_chunks: int) -> List[Tuple[int, int, int, int, float]]:
-    """Fastest pairs first, as many layers per pair as both chunks still have slots for.
+    """Every layer gets a K slot and a V slot.  Fastest pairs first, as many layers per pair as both
+    chunks still have slots for; then pairs of layers trade partners while that lowers the sum
+    (two layers on (i, j) and (k, l) become (i, k), (j, l) or (i, l), (j, k): every chunk keeps its
+    number of used slots) - without it the greedy pass can spend the slots of good partners on each
+    other and leave the last layers a pair of the slowest class.
     Returns per layer (K chunk, K slot, V chunk, V slot, probed us)."""
+    def cost(i, j):
+        return times[(i, j) if i <= j else (j, i)]
+
     free = [slots_per_chunk] * n_chunks
+    pairs = []
+    for (i, j), _ in sorted(times.items(), key=lambda kv: kv[1]):
+        while len(pairs) < n_layers and (free[i] >= 2 if i == j else free[i] >= 1 and free[j] >= 1):
+            free[i] -= 1
+            free[j] -= 1
+            pairs.append((i, j))
+        if len(pairs) == n_layers:
+            break
+    if len(pairs) < n_layers:
+        raise RuntimeError("the arena has room for %d of %d layers" % (len(pairs), n_layers))
+    improved = True
+    while improved:
+        improved = False
+        # a layer moves to a pair with free slots
+        for a in range(len(pairs)):
+            i, j = pairs[a]
+            free[i] += 1
+            free[j] += 1
+            best, best_c = (i, j), cost(i, j)
+            for (k, l), t in times.items():
+                if t < best_c - 1e-9 and (free[k] >= 2 if k == l else free[k] >= 1 and free[l] >= 1):
+                    best, best_c = (k, l), t
+            if best != (i, j):
+                improved = True
+            pairs[a] = best
+            free[best[0]] -= 1
+            free[best[1]] -= 1
+        # two layers trade partners
+        for a in range(len(pairs)):
+            for b in range(a + 1, len(pairs)):
+                (i, j), (k, l) = pairs[a], pairs[b]
+                now = cost(i, j) + cost(k, l)
+                for (p, q), (r, u) in (((i, k), (j, l)), ((i, l), (j, k))):
+                    if (min(p, q), max(p, q)) in times and (min(r, u), max(r, u)) in times and cost(p, q) + cost(r, u) < now - 1e-9:
+                        pairs[a], pairs[b] = (p, q), (r, u)
+                        now = cost(p, q) + cost(r, u)
+                        (i, j), (k, l) = pairs[a], pairs[b]
+                        improved = True
     used = [0] * n_chunks
     out = []
-    for (i, j), t in sorted(times.items(), key=lambda kv: kv[1]):
-        while len(out) < n_layers and (free[i] >= 2 if i == j else free[i] >= 1 and free[j] >= 1):
-            ks = used[i]
-            used[i] += 1
-            free[i] -= 1
-            vs = used[j]
-            used[j] += 1
-            free[j] -= 1
-            out.append((i, ks, j, vs, t))
-        if len(out) == n_layers:
-            break
-    if len(out) < n_layers:
-        raise RuntimeError("the arena has room for %d of %d layers" % (len(out), n_layers))
+    for i, j in sorted(pairs, key=lambda pq: cost(*pq)):
+        ks = used[i]
+        used[i] += 1
+        vs = used[j]
+        used[j] += 1
+        out.append((i, ks, j, vs, cost(i, j)))
     return out
 
 

@@ -5,13 +5,13 @@ import pytest
 from paper_2605_21603_amd import placement as P
 
 
-def test_fastest_pairs_first_within_each_chunks_capacity():
+def test_fastest_pairs_first_then_partners_are_traded():
     times = {(0, 0): 950.0, (0, 1): 870.0, (0, 2): 830.0, (1, 1): 950.0, (1, 2): 868.0, (2, 2): 940.0}
     plan = P.assign(times, n_layers=4, slots_per_chunk=3, n_chunks=3)
-    # three layers fit the fastest pair (0, 2), which fills both chunks; chunk 1 then hosts one layer with two of its slots
-    assert [(p[0], p[2]) for p in plan[:3]] == [(0, 2)] * 3
-    assert [p[4] for p in plan[:3]] == [830.0] * 3
-    assert (plan[3][0], plan[3][2]) == (1, 1) and plan[3][1] != plan[3][3] and plan[3][4] == 950.0
+    # greedy alone: three layers on (0, 2), which fills both chunks, and the fourth on (1, 1) at 950; trading partners
+    # with one of the three gives (0, 2), (0, 2), (1, 2), (0, 1)
+    assert sorted(p[4] for p in plan) == [830.0, 830.0, 868.0, 870.0]
+    assert sorted(tuple(sorted((p[0], p[2]))) for p in plan) == [(0, 1), (0, 2), (0, 2), (1, 2)]
 
 
 def test_slots_are_distinct_and_inside_their_chunks():
@@ -35,3 +35,23 @@ def test_slot_size_is_rounded_to_256_bytes():
     import torch
     assert P.slot_bytes_of((3, 2, 16, 8), torch.bfloat16) == 1536
     assert P.slot_bytes_of((3, 2, 16, 9), torch.bfloat16) == 1792
+
+
+def test_layers_trade_partners_instead_of_ending_in_the_slowest_class():
+    """Chunk classes a (0, 1), b (2), c (3, 4): a with b is fast, c with c slow, everything else in
+    the middle.  Greedy alone pairs the a chunks' left-over slots with each other and leaves the
+    last layers (c, c); after the exchange pass no layer is in the slowest class."""
+    cls = {0: "a", 1: "a", 2: "b", 3: "c", 4: "c"}
+    def t(i, j):
+        x, y = sorted((cls[i], cls[j]))
+        return {("a", "b"): 830.0, ("c", "c"): 950.0}.get((x, y), 868.0 + 0.01 * (i + j))
+    times = {(i, j): t(i, j) for i in range(5) for j in range(i, 5)}
+    plan = P.assign(times, n_layers=12, slots_per_chunk=6, n_chunks=5)
+    costs = sorted(p[4] for p in plan)
+    assert costs[:6] == [830.0] * 6              # chunk 2 has six slots: six layers in the fast class
+    assert max(costs) < 900.0                    # and nobody in the slowest
+    used = {}
+    for kc, ks, vc, vs, _ in plan:
+        for c, s_ in ((kc, ks), (vc, vs)):
+            assert (c, s_) not in used and 0 <= s_ < 6
+            used[(c, s_)] = 1
