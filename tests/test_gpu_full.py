@@ -205,6 +205,17 @@ def test_32_layer_decode_step_full_size():
         assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8)), label
         assert torch.equal(kk.view(torch.uint8), k0.view(torch.uint8)), label
         assert torch.equal(vv.view(torch.uint8), v0.view(torch.uint8)), label
+    # the same step with one pointer per layer and cache (what the benchmark's measured placement hands
+    # over), here pointing at the layers of the stacked tensors, in the graph form the benchmark times
+    import ctypes as C
+    L = w.shape.n_layers
+    k_ptrs = (C.c_void_p * L)(*[step.k_cache[l].data_ptr() for l in range(L)])
+    v_ptrs = (C.c_void_p * L)(*[step.v_cache[l].data_ptr() for l in range(L)])
+    step.batch.k_cache_layers, step.batch.v_cache_layers = C.cast(k_ptrs, C.c_void_p), C.cast(v_ptrs, C.c_void_p)
+    y, kk, vv = run(B.sequential(use_graph=True), "sequential, caches named layer by layer")
+    step.batch.k_cache_layers = step.batch.v_cache_layers = None
+    assert torch.equal(y.view(torch.uint8), y0.view(torch.uint8))
+    assert torch.equal(kk.view(torch.uint8), k0.view(torch.uint8)) and torch.equal(vv.view(torch.uint8), v0.view(torch.uint8))
     # ---- against the oracle, layer by layer (teacher-forced)
     # A stack of random layers amplifies storage roundings from layer to layer (about sqrt(L); the
     # end-to-end figure is printed below and is not the gate).  The stated bound is a per-layer
