@@ -10,9 +10,7 @@ is the probe).  Two pools allocated one after the other early in a process land 
 class.  So: take one large arena, time the real attention launch with the pools at pairs of arena
 chunks, and give every layer the fastest pair that still has room.  The library takes the result
 through k_cache_layers / v_cache_layers of the batch."""
-from typing import Dict, List, Optional, Sequence, Tuple
-import ctypes as C
-import dataclasses
+from typing import Dict, List, Sequence, Tuple
 
 import torch
 
