@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # since, the figure is withheld (traffic = null) instead of going stale silently.
 ATTN_SOURCE = os.path.join(ROOT, "paper_2605_21603_amd", "csrc", "kernels_attn_mfma.hip")
 ROCPROF_TRAFFIC = {
-    "c2": {"bytes": 1272987034 + 21844070, "source_sha256_16": "97acdd680f24a790",
-           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,575.7 x 2.0 KiB + WRITE_SIZE 21,332.1 KiB)"},
-    "c5": {"bytes": 5051700224 + 86376653, "source_sha256_16": "97acdd680f24a790",
-           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,650.5 x 2.0 KiB + WRITE_SIZE 84,352.2 KiB)"},
+    "c2": {"bytes": 1273028198 + 21844685, "source_sha256_16": "85bef3b785132150", "kv_chunk_positions": 256,
+           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,595.8 x 2.0 KiB + WRITE_SIZE 21,332.7 KiB)"},
+    "c5": {"bytes": 5050698957 + 22979686, "source_sha256_16": "85bef3b785132150", "kv_chunk_positions": 1024,
+           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,161.6 x 2.0 KiB + WRITE_SIZE 22,441.1 KiB)"},
 }
 
 
@@ -344,6 +344,10 @@ def main():
                     help="measured: one large arena, the attention launch timed with the K and V pools at pairs of arena chunks, "
                          "every layer's pools at the fastest pair with room; stacked: one tensor per cache, layers back to back")
     ap.add_argument("--arena-gib", type=int, default=224, help="--kv-placement measured: size of the arena (chunks of 16 GiB)")
+    ap.add_argument("--kv-chunk", default="rule",
+                    help="split-KV chunk of decode attention in positions (kv_chunk_positions of the configuration): a number; "
+                         "'rule' (default): 1024 when the batch has at least eight decode work items per persistent wave at 256, "
+                         "else 256; 'auto': the whole attention dispatch of the first layer timed with 256, 1024 and 2048 and the fastest taken")
     ap.add_argument("--policy-sweep", action="store_true",
                     help="sequential vs split over a grid of prefill / decode mixes, beside the policy's estimates")
     ap.add_argument("--sweep-grid", default="fit", choices=["fit", "holdout"],
@@ -390,13 +394,20 @@ def main():
             arena = None
             torch.cuda.empty_cache()
 
+    if args.kv_chunk == "rule":
+        from paper_2605_21603_amd import placement as P0
+        kv_chunk = P0.rule_chunk([c for _, c in w.seqs], [q for q, _ in w.seqs], w.shape.n_kv) if w.shape.dtype == "bf16" else 0
+    else:
+        kv_chunk = 0 if args.kv_chunk == "auto" else int(args.kv_chunk)
+    chunk_us = None
+
     def place(so_far, k_shape, v_shape):
         """Times the first layer's attention launch on this step with the pools at pairs of arena
         chunks and hands out every layer's pools accordingly."""
         nonlocal placement
         dt = w.shape.torch_dtype
         w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
-        layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1)), w0)
+        layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1), kv_chunk), w0)
         times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream)
         del layer1
         plan = P.assign(times, w.shape.n_layers, arena.chunk_bytes // P.slot_bytes_of(k_shape, dt), arena.n_chunks)
@@ -404,7 +415,22 @@ def main():
         log("cache placement: attention probe %.1f us fastest / %.1f median / %.1f slowest pair of chunks; chosen mean %.1f, worst %.1f"
             % (placement["probe_us_fastest"], placement["probe_us_median"], placement["probe_us_slowest"],
                placement["chosen_us_mean"], placement["chosen_us_worst"]))
-        return P.place_layers(arena, plan, k_shape, v_shape, dt)
+        ks, vs = P.place_layers(arena, plan, k_shape, v_shape, dt)
+        pick_chunk(so_far, ks[0], vs[0])
+        return ks, vs
+
+
+    def pick_chunk(so_far, k0, v0):
+        """--kv-chunk auto: the first layer's attention dispatch on this step, pools where they will be, per candidate."""
+        nonlocal kv_chunk, chunk_us
+        if args.kv_chunk != "auto" or w.shape.dtype != "bf16":
+            return
+        from paper_2605_21603_amd import placement as P
+        w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
+        sh1 = dataclasses.replace(w.shape, n_layers=1)
+        kv_chunk, chunk_us = P.choose_chunk(lambda c: B.DynLayer(B.make_config(sh1, c), w0), so_far, k0, v0, (256, 1024, 2048), stream)
+        log("split-KV chunk: attention dispatch %s us -> %d positions"
+            % (", ".join("%d: %.1f" % (c, t) for c, t in chunk_us.items()), kv_chunk))
 
     log("generating %s (seed %d) ..." % (w.name, w.seed))
     host_data = None                        # the step as generated on the host, where it was
@@ -423,7 +449,12 @@ def main():
                 vs[l].copy_(host_v[l])
             host_data, data = data, dict(data, k_cache=ks, v_cache=vs)
     weights = [{k: v.to("cuda:0") for k, v in lw.items()} for lw in data["weights"]]
-    layer = B.DynLayer(B.make_config(w.shape), weights)
+    if arena is None:                       # stacked caches: the chunk is chosen on layer 0's pools where they are
+        k0 = data["k_cache"][0] if data["x"].is_cuda else data["k_cache"][0].to("cuda:0")
+        v0 = data["v_cache"][0] if data["x"].is_cuda else data["v_cache"][0].to("cuda:0")
+        pick_chunk(dict(data, weights=weights), k0, v0)
+        del k0, v0
+    layer = B.DynLayer(B.make_config(w.shape, kv_chunk), weights)
     step = B.DeviceStep(layer, data, placed=arena is not None)
     use_graph = not args.no_graph
 
@@ -514,6 +545,9 @@ def main():
                         "avg_launch_ms": gu_avg_ms}
 
     traffic = ROCPROF_TRAFFIC.get(w.name)
+    if traffic and traffic["kv_chunk_positions"] != (kv_chunk or 256):
+        log("the committed counters were read with another split-KV chunk size: traffic withheld")
+        traffic = None
     if traffic and traffic["source_sha256_16"] != source_hash(ATTN_SOURCE):
         log("the attention kernel's source changed since its counters were read: traffic withheld")
         traffic = None
@@ -542,6 +576,7 @@ def main():
         "schedules_stats_ms": stats,
         "hbm": {"peak_GB/s": HBM_PEAK_GBS, "measured_stream_read": stream_read},
         "kv_placement": placement if placement is not None else "stacked",
+        "kv_chunk_positions": {"used": kv_chunk or 256, "attention_dispatch_us": chunk_us},
         "mfma": {"peak_TFLOP/s": MFMA_BF16_PEAK_TFLOPS, "measured_loop": mfma_loop},
         "tuned": tuned,
         "policy": {"choice": "split at row %d" % policy["cut_row"] if policy["split"] else "sequential",

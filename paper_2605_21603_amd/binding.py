@@ -32,7 +32,8 @@ MOE_CHAIN = DENSE_CHAIN[:6] + [DYN_OP_ROUTE] + DENSE_CHAIN[6:]
 class dyn_layer_config(C.Structure):
     _fields_ = [("dtype", C.c_int), ("n_layers", C.c_int), ("hidden", C.c_int), ("n_q_heads", C.c_int),
                 ("n_kv_heads", C.c_int), ("head_dim", C.c_int), ("mlp_inter", C.c_int), ("n_experts", C.c_int),
-                ("top_k", C.c_int), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("page_size", C.c_int)]
+                ("top_k", C.c_int), ("rms_eps", C.c_float), ("rope_base", C.c_float), ("page_size", C.c_int),
+                ("kv_chunk_positions", C.c_int)]
 
 
 class dyn_layer_weights(C.Structure):
@@ -463,10 +464,12 @@ def probe_mfma_loop(buf: torch.Tensor, n_stages: int, sink: torch.Tensor, stream
     return flops.value
 
 
-def make_config(sh) -> dyn_layer_config:
-    """From a workloads.gen.LayerShape-like object."""
+def make_config(sh, kv_chunk_positions: int = 0) -> dyn_layer_config:
+    """From a workloads.gen.LayerShape-like object.  kv_chunk_positions: the split-KV chunk of
+    decode attention (0: the library's default of 256 positions)."""
     return dyn_layer_config(DYN_BF16 if sh.dtype == "bf16" else DYN_F32, sh.n_layers, sh.hidden, sh.n_q, sh.n_kv,
-                            sh.head_dim, sh.inter, sh.n_experts, sh.top_k, sh.eps, sh.rope_base, sh.page_size)
+                            sh.head_dim, sh.inter, sh.n_experts, sh.top_k, sh.eps, sh.rope_base, sh.page_size,
+                            kv_chunk_positions)
 
 
 class DeviceStep:

@@ -973,6 +973,8 @@ dyn_status check_config(const dyn_layer_config *c) {
         if (!dyn::gemm_supported(c->dtype, p[0], p[1]))
             return fail(DYN_ERR_UNSUPPORTED, "projection %d x %d: bf16 needs widths that are multiples of 128 and depths that are multiples of 256", p[0], p[1]);
     if (c->n_experts > 16) return fail(DYN_ERR_UNSUPPORTED, "at most 16 experts");
+    if (c->kv_chunk_positions != 0 && (c->kv_chunk_positions < 64 || c->kv_chunk_positions > 65536 || c->kv_chunk_positions % c->page_size))
+        return fail(DYN_ERR_INVALID_ARG, "kv_chunk_positions = %d: 0, or a multiple of page_size in 64..65536", c->kv_chunk_positions);
     return DYN_OK;
 }
 
@@ -1044,8 +1046,8 @@ dyn_status dyn_layer_create(const dyn_layer_config *cfg, const dyn_layer_weights
     L->w.assign(weights, weights + cfg->n_layers);
     for (int i = 0; i < cfg->head_dim / 2; ++i)
         L->rope.inv_freq[i] = std::pow((double)cfg->rope_base, -2.0 * i / cfg->head_dim);
-    // split-KV chunk: 256 positions, a constant of the layer
-    L->chunk_pages = std::max(1, 256 / cfg->page_size);
+    // split-KV chunk: a constant of the handle (256 positions unless the configuration says otherwise)
+    L->chunk_pages = std::max(1, (cfg->kv_chunk_positions ? cfg->kv_chunk_positions : 256) / cfg->page_size);
     *out = L;
     return DYN_OK;
 }

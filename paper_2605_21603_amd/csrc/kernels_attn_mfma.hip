@@ -45,9 +45,9 @@ constexpr int kPersistentGroups = 512;   // two 4-wave workgroups for each of th
 // chunks of prefill_chunk_positions() positions (1024 unless the block reaches past 8192 keys).
 // One entry per (group, chunk) that exists: list[0] = number of entries, entry i =
 // (first token row, chunk | tokens << 20) at list[2 + 2 i].
-// List 0 is ordered by work, largest first: its entries are bucketed by the number of tile pairs
-// (four pages each) the chunk is walked in - kPlanBuckets of them, a chunk has at most 16 pages -
-// and inside a bucket they stay in token order, so the eight kv heads of a chunk and the chunks
+// List 0 is ordered by work, largest first: its entries are bucketed by their size in quarters of
+// the largest chunk (kPlanBuckets buckets; with the default chunk of 16 pages a quarter is one
+// tile pair of four pages) and inside a bucket they stay in token order, so the eight kv heads of a chunk and the chunks
 // of a sequence remain neighbours.  The persistent decode kernel deals the list out by wave index
 // in a snake (attn_mfma_kernel): with equal-sized items first and the small ones at the end, the
 // waves' totals differ by about one percent instead of six on contexts spread over 1024..8192.
@@ -65,7 +65,7 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
     __shared__ int wave_tot[NL][16];
     __shared__ int bucket_total[kPlanBuckets];
     const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-    const int chunk_pages = ct / PS, pair_pages = 2 * TILE_PAGES;
+    const int chunk_pages = ct / PS, bucket_pages = max(1, (chunk_pages + kPlanBuckets - 1) / kPlanBuckets);
 
     // What token row t contributes: which list, how many entries, and for list 0 the buckets of
     // its chunks (all but the last have the sequence's balanced chunk size, the last the rest).
@@ -92,8 +92,8 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
             if (!r.which) {                                  // the decode kernel's own chunking of this sequence
                 const int seq_pages = (p + PS) / PS;         // ceil((p + 1) / PS)
                 const int cp = (seq_pages + r.nc - 1) / r.nc, last = seq_pages - (r.nc - 1) * cp;
-                r.b_full = max(0, kPlanBuckets - (cp + pair_pages - 1) / pair_pages);
-                r.b_last = max(0, kPlanBuckets - (last + pair_pages - 1) / pair_pages);
+                r.b_full = max(0, kPlanBuckets - (cp + bucket_pages - 1) / bucket_pages);
+                r.b_last = max(0, kPlanBuckets - (last + bucket_pages - 1) / bucket_pages);
             }
         }
         return r;
@@ -118,7 +118,6 @@ __global__ __launch_bounds__(1024) void attn_plan_kernel(const int32_t *__restri
     for (int k = 1; k < kPlanBuckets; ++k) base[k] = base[k - 1] + bucket_total[k - 1];
     const int total0 = base[kPlanBuckets - 1] + bucket_total[kPlanBuckets - 1];
     base[kPlanBuckets] = 0;
-    (void)chunk_pages;
 
     // pass 2: entries, in token order inside each bucket
     for (int t0 = 0; t0 < rows; t0 += 1024) {

@@ -147,6 +147,46 @@ def assign(times: Dict[Tuple[int, int], float], n_layers: int, slots_per_chunk: 
     return out
 
 
+def rule_chunk(ctx_len: Sequence[int], q_len: Sequence[int], n_kv: int, n_waves: int = 2048) -> int:
+    """kv_chunk_positions by rule: 1024 positions when the decode sequences of the batch make at
+    least eight work items per persistent wave at 256 (so that a quarter as many still keep every
+    wave supplied), else the library's 256.  Measured (MI355X, pools placed): batch 256 at contexts
+    1024..8192 (18 items per wave at 256): attention dispatch 884-887 us at 256, 868-873 at 1024,
+    871 at 2048; batch 128 at 512..4096 (4.8 per wave): 246-250, 252-255, 261-267 us."""
+    items = sum((c + 255) // 256 for c, q in zip(ctx_len, q_len) if q == 1) * n_kv
+    return 1024 if items >= 8 * n_waves else 256
+
+
+def choose_chunk(make_layer1, data: dict, k0: torch.Tensor, v0: torch.Tensor, candidates: Sequence[int], stream, reps: int = 4) -> Tuple[int, Dict[int, float]]:
+    """Split-KV chunk size of decode attention (kv_chunk_positions of the configuration) by
+    measurement: the whole attention dispatch (work lists, attention kernels, merge) of a one-layer
+    handle per candidate, on the step in `data` with its layer-0 pools k0 / v0 where they will be.
+    make_layer1(chunk) returns the handle.  Returns the fastest candidate and every candidate's us."""
+    out = {}
+    for chunk in candidates:
+        layer1 = make_layer1(chunk)
+        step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True)
+        sched = B.sequential()
+        layer1.set_profiling(True)
+        ts = []
+        try:
+            with torch.cuda.stream(stream):
+                for r in range(reps + 1):
+                    layer1.forward(step.batch, sched, stream)
+                    stream.synchronize()
+                    if r == 0:
+                        continue
+                    for rec in layer1.slot_times():
+                        if rec["op"] == B.DYN_OP_ATTN:
+                            ts.append(rec["stop_ms"] - rec["start_ms"])
+        finally:
+            layer1.set_profiling(False)
+        out[chunk] = 1e3 * sum(ts) / len(ts)
+        layer1.close()
+    best = min(out, key=lambda c: out[c])
+    return best, out
+
+
 def place_layers(arena: Arena, plan: Sequence[Tuple[int, int, int, int, float]], k_shape, v_shape, dtype):
     sb = slot_bytes_of(k_shape, dtype)
     ks = [arena.view(kc, ksl, sb, k_shape, dtype) for kc, ksl, _, _, _ in plan]

@@ -30,10 +30,10 @@ def to_device_weights(data, device="cuda:0"):
 
 
 class GpuRun:
-    def __init__(self, w, data, device="cuda:0"):
+    def __init__(self, w, data, device="cuda:0", kv_chunk_positions=0):
         self.w, self.data = w, data
         self.weights = to_device_weights(data, device)
-        self.layer = B.DynLayer(B.make_config(w.shape), self.weights)
+        self.layer = B.DynLayer(B.make_config(w.shape, kv_chunk_positions), self.weights)
         self.device = device
 
     def run(self, sched, stream=None, repeat=1):

@@ -46,7 +46,7 @@ def host_batch(w):
 
 def test_struct_sizes_match_header_layout():
     assert C.sizeof(B.dyn_slot) == 5
-    assert C.sizeof(B.dyn_layer_config) == 12 * 4
+    assert C.sizeof(B.dyn_layer_config) == 13 * 4
     assert C.sizeof(B.dyn_slot_time) == 10 * 4
 
 
@@ -77,7 +77,9 @@ def test_create_rejects_bad_configs():
     good = {n: 0x1000 for n in ("w_qkv", "w_o", "w_gate_up", "w_down", "g_norm1", "g_norm2")}
     for field, value, status in [("n_kv_heads", 3, B.DYN_ERR_INVALID_ARG), ("head_dim", 96, B.DYN_ERR_UNSUPPORTED),
                                  ("dtype", 7, B.DYN_ERR_INVALID_ARG), ("hidden", 0, B.DYN_ERR_INVALID_ARG),
-                                 ("top_k", 2, B.DYN_ERR_INVALID_ARG), ("mlp_inter", 100, B.DYN_ERR_UNSUPPORTED)]:
+                                 ("top_k", 2, B.DYN_ERR_INVALID_ARG), ("mlp_inter", 100, B.DYN_ERR_UNSUPPORTED),
+                                 ("kv_chunk_positions", 32, B.DYN_ERR_INVALID_ARG), ("kv_chunk_positions", 1000, B.DYN_ERR_INVALID_ARG),
+                                 ("kv_chunk_positions", 131072, B.DYN_ERR_INVALID_ARG)]:
         cfg = B.make_config(w.shape)
         setattr(cfg, field, value)
         with pytest.raises(B.DynError) as e:

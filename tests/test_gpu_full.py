@@ -248,6 +248,18 @@ def test_32_layer_decode_step_full_size():
         kc, vc = orc.to_storage(d2["k_cache"][l]).copy(), orc.to_storage(d2["v_cache"][l]).copy()
         y_ref = orc.layer_forward(sh1, wts, x_in, d2["seq_of_token"], d2["pos_of_token"], d2["block_table"], kc, vc)
         err = row_rel_err(as_f64(y_l[torch.as_tensor(rows, device=x_l.device)].cpu()), y_ref)
+        if l in (0, 13, 31):          # the other split-KV chunk sizes the benchmark may choose, on the same input
+            for chunk in (1024, 2048):
+                other = B.DynLayer(B.make_config(sh1, chunk), [data["weights"][l]])
+                y_c = torch.empty_like(x_l)
+                batch.y = y_c.data_ptr()
+                with torch.cuda.stream(st):
+                    other.forward(batch, B.sequential(), st)
+                st.synchronize()
+                err_c = row_rel_err(as_f64(y_c[torch.as_tensor(rows, device=x_l.device)].cpu()), y_ref)
+                say("case c5: layer %2d with split-KV chunks of %d positions: max rel err %.3e" % (l, chunk, err_c))
+                assert err_c <= TOL[w.shape.dtype], "layer %d, chunk %d: %.3e" % (l, chunk, err_c)
+                other.close()
         kc2, vc2 = orc.to_storage(d2["k_cache"][l]).copy(), orc.to_storage(d2["v_cache"][l]).copy()
         x_ref_chain = orc.layer_forward(sh1, wts, x_ref_chain, d2["seq_of_token"], d2["pos_of_token"], d2["block_table"], kc2, vc2)
         say("case c5: layer %2d alone on the step's own input: max rel err %.3e" % (l, err))

@@ -192,6 +192,31 @@ def test_caches_placed_layer_by_layer_match_the_stacked_ones(name):
     assert torch.equal(step.y.cpu().view(torch.uint8), y0.view(torch.uint8))
 
 
+@pytest.mark.parametrize("name,chunk", [("c2_small", 64), ("c2_small", 1024), ("c5_small", 128), ("c5_small", 2048), ("dec_deep", 1024),
+                                        ("dec_deep", 8192), ("c3_small", 512), ("stack_mixed", 64), ("bf16_ps32", 1024), ("f32_small", 64)])
+def test_other_split_kv_chunk_sizes_match_the_oracle_and_every_schedule(name, chunk):
+    """kv_chunk_positions of the configuration: the chunking of decode attention is part of the
+    arithmetic of a handle, not of a schedule.  Against the oracle, and bit for bit between the
+    sequential order, a split and a merged-MLP form (eager and as a graph), for chunks from four
+    pages to far more than any sequence has (no split at all) and a context of 70 thousand
+    positions in 9 and 69 chunks (one- and two-level merges)."""
+    w = gen.config(name)
+    data = gen.generate(w)
+    run = GpuRun(w, data, kv_chunk_positions=chunk)
+    say("case %s chunk %d sequential" % (name, chunk))
+    y0, k0, v0 = run.run(B.sequential())
+    err = check_against_oracle(w, data, y0, k0, v0)
+    say("case %s chunk %d: max rel err vs oracle %.3e" % (name, chunk, err))
+    chain = B.MOE_CHAIN if w.shape.n_experts else B.DENSE_CHAIN
+    mlp = [B.DYN_OP_GATE_UP, B.DYN_OP_SILU, B.DYN_OP_DOWN]
+    for label, sched in [("split", B.nano_schedule(w.nano_rows, chain, stagger=2)),
+                         ("mlp merged, graph", B.nano_schedule(w.nano_rows, chain, merged_ops=mlp, stagger=1, use_graph=True))]:
+        say("case %s chunk %d %s" % (name, chunk, label))
+        y1, k1, v1 = run.run(sched, repeat=2 if sched.use_graph else 1)
+        assert torch.equal(y1.view(torch.uint8), y0.view(torch.uint8)), label
+        assert torch.equal(k1.view(torch.uint8), k0.view(torch.uint8)) and torch.equal(v1.view(torch.uint8), v0.view(torch.uint8)), label
+
+
 def test_profiling_reports_every_dispatch():
     w = gen.config("c2_small")
     data = gen.generate(w)

@@ -55,3 +55,12 @@ def test_layers_trade_partners_instead_of_ending_in_the_slowest_class():
         for c, s_ in ((kc, ks), (vc, vs)):
             assert (c, s_) not in used and 0 <= s_ < 6
             used[(c, s_)] = 1
+
+
+def test_chunk_rule_follows_the_decode_work_items_per_wave():
+    from workloads import gen
+    for name, want in (("c5", 1024), ("c2", 256), ("c3", 256), ("c4", 256), ("c2_small", 256)):
+        w = gen.config(name)
+        assert P.rule_chunk([c for _, c in w.seqs], [q for q, _ in w.seqs], w.shape.n_kv) == want, name
+    # a prefill chunk's tokens are not decode work items
+    assert P.rule_chunk([8192] * 4, [4096] * 4, 8) == 256
