@@ -39,6 +39,7 @@ struct Setup {
     std::vector<int32_t> q_start, ctx;
     int n_tokens = 0, n_seqs = 0, max_pages = 1;
     std::vector<dyn_layer_weights> weights;
+    std::vector<void *> k_layers, v_layers;      // the caches named layer by layer (used by every other forward of "mixed")
     dyn_layer *layer = nullptr;
     dyn_batch batch{};
 };
@@ -81,6 +82,10 @@ bool load(const char *path, Setup &s) {
     b.block_table = (const int32_t *)fake(5); b.max_pages_per_seq = s.max_pages; b.q_start_host = s.q_start.data();
     b.k_cache = fake(6); b.v_cache = fake(7); b.kv_layer_stride = 1 << 20;
     b.workspace = fake(8); b.workspace_bytes = dyn_layer_workspace_bytes(s.layer, s.n_tokens, s.max_pages);
+    for (int l = 0; l < s.cfg.n_layers; ++l) {
+        s.k_layers.push_back(fake(200 + 2 * (s.cfg.n_layers - l)));
+        s.v_layers.push_back(fake(201 + 2 * l));
+    }
     return true;
 }
 
@@ -186,6 +191,9 @@ void mixed(Setup &s) {
                 if (hipDeviceSynchronize() != hipSuccess) ++g_failures;                // masked streams are made on an idle device
                 EXPECT_OK(dyn_layer_prepare(s.layer, &sched));
             }                               // other masked candidates: the forward creates the stream itself (and waits for the device first)
+            // every other candidate with one cache pointer per layer instead of base + stride (another graph: the key holds them)
+            s.batch.k_cache_layers = i % 2 ? s.k_layers.data() : nullptr;
+            s.batch.v_cache_layers = i % 2 ? s.v_layers.data() : nullptr;
             EXPECT_OK(dyn_layer_forward(s.layer, &s.batch, &sched, stream));
             if (i % 7 == 0) {
                 EXPECT_OK(dyn_layer_set_profiling(s.layer, 1));
