@@ -2,8 +2,8 @@
 // HBM-bound operator (the paper's memory-bound "decode attention", Section 2), plus the
 // device-side work lists shared with the prefill form (kernels_attn_prefill.hip).
 //
-// A wave serves one token of a single-token sequence against one chunk (up to 256 positions;
-// a sequence's chunks are of equal size up to rounding) of one kv head, all q heads of that kv head's group at once, so K and V are fetched once per kv
+// A wave serves one token of a single-token sequence against one chunk (up to the handle's
+// chunk size, 256 positions by default; a sequence's chunks are of equal size up to rounding) of one kv head, all q heads of that kv head's group at once, so K and V are fetched once per kv
 // head.  A page of K is 16 rows of 256 bytes, a page of V is 128 rows (one per head-dim
 // index) of 32 bytes; both are loaded straight into MFMA operand layout with fully used
 // 64-byte / 32-byte row segments, no LDS.  The group's scores are a skinny but real
