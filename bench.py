@@ -344,6 +344,9 @@ def main():
                     help="measured: one large arena, the attention launch timed with the K and V pools at pairs of arena chunks, "
                          "every layer's pools at the fastest pair with room; stacked: one tensor per cache, layers back to back")
     ap.add_argument("--arena-gib", type=int, default=224, help="--kv-placement measured: size of the arena (chunks of 16 GiB)")
+    ap.add_argument("--placement-map", action="store_true",
+                    help="only print the attention launch time of the workload's first layer for every pair of arena chunks "
+                         "(K pool at the row's chunk, V pool at the column's; same chunk: V right behind K)")
     ap.add_argument("--kv-chunk", default="rule",
                     help="split-KV chunk of decode attention in positions (kv_chunk_positions of the configuration): a number; "
                          "'rule' (default): 1024 when the batch has at least eight decode work items per persistent wave at 256, "
@@ -410,6 +413,15 @@ def main():
         layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1), kv_chunk), w0)
         times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream)
         del layer1
+        if args.placement_map:
+            n = arena.n_chunks
+            print("attention launch time in us, workload %s, split-KV chunk %d positions; arena of %d chunks of 16 GiB; rows: chunk of the K pool, "
+                  "columns: chunk of the V pool" % (w.name, kv_chunk or 256, n))
+            print("      " + " ".join("%5d" % j for j in range(n)))
+            for i in range(n):
+                print("K %3d " % i + " ".join("%5.0f" % times[(i, j)] if j >= i else "     " for j in range(n)))
+            sys.stdout.flush()
+            os._exit(0)
         plan = P.assign(times, w.shape.n_layers, arena.chunk_bytes // P.slot_bytes_of(k_shape, dt), arena.n_chunks)
         placement = dict(P.summary(times, plan), arena_GiB=arena.buf.numel() / P.GiB, chunk_GiB=16)
         log("cache placement: attention probe %.1f us fastest / %.1f median / %.1f slowest pair of chunks; chosen mean %.1f, worst %.1f"
