@@ -390,7 +390,21 @@ def main():
     if args.kv_placement == "measured" and w.shape.dtype == "bf16":
         from paper_2605_21603_amd import placement as P
         try:
-            arena = P.Arena(args.arena_gib // 16, 16 * P.GiB)
+            # room for the weights and everything else must remain: shrink the arena if the device has less free memory
+            # than it usually has (the pools need 2 slots per layer; a 16 GiB chunk holds a whole number of them)
+            sh = w.shape
+            e = 2
+            wbytes = sh.n_layers * e * (sh.qkv_rows * sh.hidden + sh.hidden * sh.n_q * sh.head_dim + 3 * sh.inter * sh.hidden * max(1, sh.n_experts))
+            free_b, _ = torch.cuda.mem_get_info()
+            n_chunks = min(args.arena_gib // 16, int((free_b - wbytes - 12 * P.GiB) // (16 * P.GiB)))
+            md0 = gen.metadata(w)
+            pool = md0["n_pages"] * sh.n_kv * sh.page_size * sh.head_dim * e
+            slots = n_chunks * ((16 * P.GiB) // max(pool, 1)) if n_chunks > 0 else 0
+            if n_chunks < 2 or slots < 2 * sh.n_layers:
+                raise RuntimeError("%.0f GiB free" % (free_b / P.GiB))
+            if n_chunks < args.arena_gib // 16:
+                log("arena reduced to %d GiB (%.0f GiB free)" % (16 * n_chunks, free_b / P.GiB))
+            arena = P.Arena(n_chunks, 16 * P.GiB)
             arena.fill_random()
         except RuntimeError as e:           # not enough free memory for the arena: the plain layout
             log("no %d GiB arena (%s): stacked caches" % (args.arena_gib, str(e).splitlines()[0]))
