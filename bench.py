@@ -418,6 +418,20 @@ def main():
         kv_chunk = 0 if args.kv_chunk == "auto" else int(args.kv_chunk)
     chunk_us = None
 
+    ws_tensor = None
+
+    def the_workspace(so_far):
+        """One workspace buffer for the probes and for the timed step: the attention kernel writes its split-KV partials
+        there, and where that third stream lies moves the launch like the pools' places do."""
+        nonlocal ws_tensor
+        if ws_tensor is None:
+            sizing = B.DynLayer(B.make_config(w.shape, 256), [{k: v.to("cuda:0") for k, v in lw.items()} for lw in so_far["weights"]])
+            md_ = gen.metadata(w)
+            # the smallest chunk any --kv-chunk choice uses has the most chunks and the largest partial arrays
+            ws_tensor = torch.empty(sizing.workspace_bytes(w.n_tokens, int(md_["max_pages_per_seq"])) + 512, dtype=torch.uint8, device="cuda:0")
+            sizing.close()
+        return ws_tensor
+
     def place(so_far, k_shape, v_shape):
         """Times the first layer's attention launch on this step with the pools at pairs of arena
         chunks and hands out every layer's pools accordingly."""
@@ -425,7 +439,7 @@ def main():
         dt = w.shape.torch_dtype
         w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
         layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1), kv_chunk), w0)
-        times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream)
+        times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream, workspace=the_workspace(so_far))
         del layer1
         if args.placement_map:
             n = arena.n_chunks
@@ -454,7 +468,8 @@ def main():
         from paper_2605_21603_amd import placement as P
         w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
         sh1 = dataclasses.replace(w.shape, n_layers=1)
-        kv_chunk, chunk_us = P.choose_chunk(lambda c: B.DynLayer(B.make_config(sh1, c), w0), so_far, k0, v0, (256, 1024, 2048), stream)
+        kv_chunk, chunk_us = P.choose_chunk(lambda c: B.DynLayer(B.make_config(sh1, c), w0), so_far, k0, v0, (256, 1024, 2048), stream,
+                                            workspace=the_workspace(so_far))
         log("split-KV chunk: attention dispatch %s us -> %d positions"
             % (", ".join("%d: %.1f" % (c, t) for c, t in chunk_us.items()), kv_chunk))
 
@@ -481,7 +496,7 @@ def main():
         pick_chunk(dict(data, weights=weights), k0, v0)
         del k0, v0
     layer = B.DynLayer(B.make_config(w.shape, kv_chunk), weights)
-    step = B.DeviceStep(layer, data, placed=arena is not None)
+    step = B.DeviceStep(layer, data, placed=arena is not None, workspace=the_workspace(dict(data, weights=weights)))
     use_graph = not args.no_graph
 
     stats = {}

@@ -478,11 +478,12 @@ class DeviceStep:
     caller has placed them layer by layer."""
 
     def __init__(self, layer: DynLayer, data: dict, device="cuda:0", sched: Optional["Schedule"] = None, guard: int = 0,
-                 placed: bool = False):
+                 placed: bool = False, workspace: Optional[torch.Tensor] = None):
         """sched: size the workspace for this schedule alone (dyn_schedule_workspace_bytes) instead of
         for any schedule; guard: extra bytes behind the workspace that the library is not told about;
         placed: data["k_cache"] / data["v_cache"] are lists of per-layer device tensors that stay
-        where they are (k_cache_layers / v_cache_layers of the batch) instead of being stacked."""
+        where they are (k_cache_layers / v_cache_layers of the batch) instead of being stacked;
+        workspace: a device byte tensor to use (at least the needed bytes + 256) instead of a new one."""
         dev = torch.device(device)
         self.x = data["x"].to(dev)
         self.y = torch.empty_like(self.x)
@@ -510,7 +511,11 @@ class DeviceStep:
             self.batch.k_cache_layers = C.cast(self._k_ptrs, C.c_void_p)
             self.batch.v_cache_layers = C.cast(self._v_ptrs, C.c_void_p)
         nbytes = layer.workspace_bytes(n_tokens, max_pages) if sched is None else layer.schedule_workspace_bytes(self.batch, sched)
-        self.workspace = torch.empty(nbytes + 256 + guard, dtype=torch.uint8, device=dev)
+        if workspace is not None:
+            assert workspace.is_cuda and workspace.dtype == torch.uint8 and workspace.numel() >= nbytes + 256 + guard
+            self.workspace = workspace
+        else:
+            self.workspace = torch.empty(nbytes + 256 + guard, dtype=torch.uint8, device=dev)
         ws_ptr = (self.workspace.data_ptr() + 255) & ~255
         self.workspace_offset = ws_ptr - self.workspace.data_ptr()
         self.batch.workspace = ws_ptr

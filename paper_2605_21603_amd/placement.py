@@ -54,14 +54,20 @@ def slot_bytes_of(k_shape, dtype) -> int:
     return (b + 255) & ~255
 
 
-def measure_pairs(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_shape, dtype, stream, reps: int = 2) -> Dict[Tuple[int, int], float]:
+def measure_pairs(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_shape, dtype, stream, reps: int = 2,
+                  workspace: "torch.Tensor" = None) -> Dict[Tuple[int, int], float]:
     """Attention launch time (us, by the library's own per-dispatch events) of the one-layer model
     `layer1` on the step in `data`, with the K pool at the start of chunk i and the V pool at the
-    start of chunk j (i < j), or right behind the K pool in the same chunk (i == j)."""
+    start of chunk j (i < j), or right behind the K pool in the same chunk (i == j).
+    workspace: the buffer the timed step will use.  The attention kernel writes its split-KV
+    partials there, a third stream next to the two pools, and which region that buffer lies in
+    moves the launch by 4-5 % (one Llama-3-8B layer at batch 128, chunks of 256 positions: 215-219
+    us with pools and workspace in three different regions' classes, 227-230 us when the workspace
+    shares a class with a pool): measure with the buffer that will be used."""
     sb = slot_bytes_of(k_shape, dtype)
     k0 = arena.view(0, 0, sb, k_shape, dtype)
     v0 = arena.view(0, 1, sb, v_shape, dtype)
-    step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True)
+    step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True, workspace=workspace)
     base = arena.buf.data_ptr()
     sched = B.sequential()
     layer1.set_profiling(True)
@@ -157,7 +163,8 @@ def rule_chunk(ctx_len: Sequence[int], q_len: Sequence[int], n_kv: int, n_waves:
     return 1024 if items >= 8 * n_waves else 256
 
 
-def choose_chunk(make_layer1, data: dict, k0: torch.Tensor, v0: torch.Tensor, candidates: Sequence[int], stream, reps: int = 4) -> Tuple[int, Dict[int, float]]:
+def choose_chunk(make_layer1, data: dict, k0: torch.Tensor, v0: torch.Tensor, candidates: Sequence[int], stream, reps: int = 4,
+                 workspace: "torch.Tensor" = None) -> Tuple[int, Dict[int, float]]:
     """Split-KV chunk size of decode attention (kv_chunk_positions of the configuration) by
     measurement: the whole attention dispatch (work lists, attention kernels, merge) of a one-layer
     handle per candidate, on the step in `data` with its layer-0 pools k0 / v0 where they will be.
@@ -165,7 +172,7 @@ def choose_chunk(make_layer1, data: dict, k0: torch.Tensor, v0: torch.Tensor, ca
     out = {}
     for chunk in candidates:
         layer1 = make_layer1(chunk)
-        step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True)
+        step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True, workspace=workspace)
         sched = B.sequential()
         layer1.set_profiling(True)
         ts = []
