@@ -399,7 +399,7 @@ def main():
             n_chunks = min(args.arena_gib // 16, int((free_b - wbytes - 12 * P.GiB) // (16 * P.GiB)))
             md0 = gen.metadata(w)
             pool = md0["n_pages"] * sh.n_kv * sh.page_size * sh.head_dim * e
-            slots = n_chunks * ((16 * P.GiB) // max(pool, 1)) if n_chunks > 0 else 0
+            slots = n_chunks * ((14 * P.GiB) // max(pool, 1)) if n_chunks > 0 else 0      # 2 GiB per chunk kept for a workspace
             if n_chunks < 2 or slots < 2 * sh.n_layers:
                 raise RuntimeError("%.0f GiB free" % (free_b / P.GiB))
             if n_chunks < args.arena_gib // 16:
@@ -420,16 +420,21 @@ def main():
 
     ws_tensor = None
 
+    def workspace_bytes(so_far):
+        sizing = B.DynLayer(B.make_config(w.shape, 256), [{k: v.to("cuda:0") for k, v in lw.items()} for lw in so_far["weights"]])
+        md_ = gen.metadata(w)
+        # the smallest chunk any --kv-chunk choice uses has the most chunks and the largest partial arrays
+        n = sizing.workspace_bytes(w.n_tokens, int(md_["max_pages_per_seq"])) + 512
+        sizing.close()
+        return n
+
     def the_workspace(so_far):
         """One workspace buffer for the probes and for the timed step: the attention kernel writes its split-KV partials
-        there, and where that third stream lies moves the launch like the pools' places do."""
+        there and the projections their split-K planes, and where those streams lie moves the launches like the pools'
+        places do.  (Inside the arena when there is one: place() picks the chunk.)"""
         nonlocal ws_tensor
         if ws_tensor is None:
-            sizing = B.DynLayer(B.make_config(w.shape, 256), [{k: v.to("cuda:0") for k, v in lw.items()} for lw in so_far["weights"]])
-            md_ = gen.metadata(w)
-            # the smallest chunk any --kv-chunk choice uses has the most chunks and the largest partial arrays
-            ws_tensor = torch.empty(sizing.workspace_bytes(w.n_tokens, int(md_["max_pages_per_seq"])) + 512, dtype=torch.uint8, device="cuda:0")
-            sizing.close()
+            ws_tensor = torch.empty(workspace_bytes(so_far), dtype=torch.uint8, device="cuda:0")
         return ws_tensor
 
     def place(so_far, k_shape, v_shape):
@@ -439,6 +444,14 @@ def main():
         dt = w.shape.torch_dtype
         w0 = [{k: v.to("cuda:0") for k, v in so_far["weights"][0].items()}]
         layer1 = B.DynLayer(B.make_config(dataclasses.replace(w.shape, n_layers=1), kv_chunk), w0)
+        # the workspace first: the end of the chunk where everything but attention runs fastest (the weights stay where they are)
+        nonlocal ws_tensor
+        ws_bytes = workspace_bytes(so_far)
+        arena.reserved_tail = (ws_bytes + 4095) & ~4095
+        ws_us = P.measure_workspace(layer1, so_far, arena, k_shape, v_shape, dt, ws_bytes, stream)
+        ws_chunk = min(ws_us, key=lambda c: ws_us[c])
+        ws_tensor = P.workspace_view(arena, ws_chunk, ws_bytes)
+        log("workspace: the step without attention takes %.1f .. %.1f us by the workspace's chunk -> chunk %d" % (min(ws_us.values()), max(ws_us.values()), ws_chunk))
         times = P.measure_pairs(layer1, so_far, arena, k_shape, v_shape, dt, stream, workspace=the_workspace(so_far))
         del layer1
         if args.placement_map:
@@ -450,8 +463,9 @@ def main():
                 print("K %3d " % i + " ".join("%5.0f" % times[(i, j)] if j >= i else "     " for j in range(n)))
             sys.stdout.flush()
             os._exit(0)
-        plan = P.assign(times, w.shape.n_layers, arena.chunk_bytes // P.slot_bytes_of(k_shape, dt), arena.n_chunks)
-        placement = dict(P.summary(times, plan), arena_GiB=arena.buf.numel() / P.GiB, chunk_GiB=16)
+        plan = P.assign(times, w.shape.n_layers, (arena.chunk_bytes - arena.reserved_tail) // P.slot_bytes_of(k_shape, dt), arena.n_chunks)
+        placement = dict(P.summary(times, plan), arena_GiB=arena.buf.numel() / P.GiB, chunk_GiB=16, workspace_chunk=ws_chunk,
+                         non_attention_us_by_workspace_chunk=[ws_us[c] for c in range(arena.n_chunks)])
         log("cache placement: attention probe %.1f us fastest / %.1f median / %.1f slowest pair of chunks; chosen mean %.1f, worst %.1f"
             % (placement["probe_us_fastest"], placement["probe_us_median"], placement["probe_us_slowest"],
                placement["chosen_us_mean"], placement["chosen_us_worst"]))

@@ -24,6 +24,7 @@ class Arena:
 
     def __init__(self, n_chunks: int, chunk_bytes: int, device="cuda:0"):
         self.n_chunks, self.chunk_bytes = n_chunks, chunk_bytes
+        self.reserved_tail = 0              # bytes at the end of every chunk kept free of pools (a workspace may go there)
         self.buf = torch.empty(n_chunks * chunk_bytes, dtype=torch.uint8, device=device)
 
     def fill_random(self, seed: int = 1) -> None:
@@ -42,7 +43,7 @@ class Arena:
         for d in shape:
             n *= d
         e = torch.empty(0, dtype=dtype).element_size()
-        assert slot * slot_bytes + n * e <= self.chunk_bytes
+        assert slot * slot_bytes + n * e <= self.chunk_bytes - self.reserved_tail
         return self.buf[off:off + n * e].view(dtype).view(shape)
 
 
@@ -91,6 +92,43 @@ def measure_pairs(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_sha
     finally:
         layer1.set_profiling(False)
     return times
+
+
+def measure_workspace(layer1: "B.DynLayer", data: dict, arena: Arena, k_shape, v_shape, dtype, ws_bytes: int, stream,
+                      reps: int = 3) -> Dict[int, float]:
+    """Time (us) of everything but attention in the one-layer step - the projections write their
+    split-K planes to the workspace while they stream their weights - with the workspace in the
+    last ws_bytes of each arena chunk (pools at the first and the last chunk).  Weights in the
+    workspace's region cost the projections 2-3 %, an expert-grouped down projection 10 %."""
+    sb = slot_bytes_of(k_shape, dtype)
+    k0 = arena.view(0, 0, sb, k_shape, dtype)
+    v0 = arena.view(arena.n_chunks - 1, 0, sb, v_shape, dtype)
+    sched = B.sequential()
+    out = {}
+    for c in range(arena.n_chunks):
+        ws = workspace_view(arena, c, ws_bytes)
+        step = B.DeviceStep(layer1, dict(data, k_cache=[k0], v_cache=[v0]), placed=True, workspace=ws)
+        layer1.set_profiling(True)
+        ts = []
+        try:
+            with torch.cuda.stream(stream):
+                for r in range(reps + 1):
+                    layer1.forward(step.batch, sched, stream)
+                    stream.synchronize()
+                    if r == 0:
+                        continue
+                    ts.append(sum(rec["stop_ms"] - rec["start_ms"] for rec in layer1.slot_times() if rec["op"] != B.DYN_OP_ATTN))
+        finally:
+            layer1.set_profiling(False)
+        out[c] = 1e3 * sum(ts) / len(ts)
+    return out
+
+
+def workspace_view(arena: Arena, chunk: int, ws_bytes: int) -> torch.Tensor:
+    """The last ws_bytes (rounded up to 4 KiB) of a chunk."""
+    n = (ws_bytes + 4095) & ~4095
+    end = (chunk + 1) * arena.chunk_bytes
+    return arena.buf[end - n:end]
 
 
 def assign(times: Dict[Tuple[int, int], float], n_layers: int, slots_per_chunk: int, n_chunks: int) -> List[Tuple[int, int, int, int, float]]:
