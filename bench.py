@@ -36,10 +36,10 @@ MFMA_BF16_PEAK_TFLOPS = 2500.0
 # since, the figure is withheld (traffic = null) instead of going stale silently.
 ATTN_SOURCE = os.path.join(ROOT, "paper_2605_21603_amd", "csrc", "kernels_attn_mfma.hip")
 ROCPROF_TRAFFIC = {
-    "c2": {"bytes": 1273028198 + 21844685, "source_sha256_16": "1a36022dc5bf28f3", "kv_chunk_positions": 256,
-           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,595.8 x 2.0 KiB + WRITE_SIZE 21,332.7 KiB)"},
-    "c5": {"bytes": 5050698957 + 22979686, "source_sha256_16": "1a36022dc5bf28f3", "kv_chunk_positions": 1024,
-           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,161.6 x 2.0 KiB + WRITE_SIZE 22,441.1 KiB)"},
+    "c2": {"bytes": 1272940954 + 21841510, "source_sha256_16": "1a36022dc5bf28f3", "kv_chunk_positions": 256,
+           "source": "profiles/c2_sequential_attn_mfma_kernel.md (FETCH_SIZE 621,553.2 x 2.0 KiB + WRITE_SIZE 21,329.6 KiB)"},
+    "c5": {"bytes": 5050486784 + 22979686, "source_sha256_16": "1a36022dc5bf28f3", "kv_chunk_positions": 1024,
+           "source": "profiles/c5_sequential_32_layer_decode.md (FETCH_SIZE 2,466,058.0 x 2.0 KiB + WRITE_SIZE 22,441.1 KiB)"},
 }
 
 
